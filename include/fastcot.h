@@ -1,0 +1,171 @@
+/* fastcot.h -- C ABI of the MI355X (gfx950) FastCoT Jacobi-decoding library.
+ *
+ * The library runs the hot path of FastCoT (arXiv 2311.08263): one causal-decoder forward
+ * over the committed KV cache plus a window of W tokens (Sec. 4.3, Eq. 4), per-row greedy
+ * argmax (Eq. 1/2), verification of the approximate tokens (Eq. 5), acceptance of the verified
+ * prefix, commit of its K/V and the shift of the window (Sec. 4.3 "Cache Update").
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative fastcot_status; fastcot_last_error()
+ *     gives a text for the last failure of a context (or of a context-less call).
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *     host memory owned by the caller.  The library never allocates or frees device memory; it
+ *     owns only its host-side context (and a few pinned host words inside it).
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  All device work
+ *     of a context is enqueued on the stream given to fastcot_init.
+ *   - Host arrays are row-major int32 unless stated otherwise.
+ *   - Window size W ("window" below) is the number of query rows per sequence per step: slot 0
+ *     carries the newest exact token, slots 1..W-1 approximate tokens.  The paper's window size
+ *     c counts only the extra tokens, so W = c + 1 and W = 1 is autoregressive decoding
+ *     (Sec. 3.1, Fig. 2 caption).
+ *   - Calls on one context must not overlap in time.
+ */
+#ifndef FASTCOT_H
+#define FASTCOT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FASTCOT_OK = 0,
+    FASTCOT_EINVAL = -1,    /* bad argument */
+    FASTCOT_ESTATE = -2,    /* call order (e.g. step before prefill) */
+    FASTCOT_ECAPACITY = -3, /* batch / sequence / buffer / workspace capacity exceeded */
+    FASTCOT_EHIP = -4,      /* a HIP runtime call failed */
+    FASTCOT_ENOMEM = -5     /* host allocation failed */
+} fastcot_status;
+
+enum { FASTCOT_F32 = 0, FASTCOT_BF16 = 1 };
+
+/* Llama-style decoder shape plus capacities.  dtype is the storage type of weights and KV
+ * cache; activations, accumulation, softmax and norm statistics are always fp32. */
+typedef struct fastcot_config {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    float rms_eps, rope_base;
+    int32_t dtype;
+    int32_t max_batch; /* sequences per step */
+    int32_t max_seq;   /* KV-cache positions per sequence, also capacity of the token buffer */
+    int32_t window;    /* W, query rows per sequence per step */
+} fastcot_config;
+
+/* Tensors of the model, in the caller's canonical layout: linear weights row-major [in][out]
+ * (y = x . W), the embedding row-major [vocab][d_model], gains fp32 [d_model]. */
+typedef enum {
+    FASTCOT_T_EMB = 0, FASTCOT_T_WLM = 1, FASTCOT_T_GF = 2,
+    FASTCOT_T_WQ = 3, FASTCOT_T_WK = 4, FASTCOT_T_WV = 5, FASTCOT_T_WO = 6,
+    FASTCOT_T_WG = 7, FASTCOT_T_WU = 8, FASTCOT_T_WD = 9, FASTCOT_T_G1 = 10, FASTCOT_T_G2 = 11
+} fastcot_tensor;
+
+typedef struct fastcot_ctx fastcot_ctx;
+
+/* Bytes of the library's packed device weight layout / of the device workspace (KV cache,
+ * activations, token buffers, counters) for a configuration.  0 on an invalid configuration. */
+size_t fastcot_weight_bytes(const fastcot_config* cfg);
+size_t fastcot_workspace_bytes(const fastcot_config* cfg);
+
+/* Rearranges one tensor from the canonical layout into its place inside the packed weights.
+ * d_canonical: device pointer, elements of cfg->dtype (gains: fp32); NULL for a gain tensor
+ * means "all ones".  d_packed: device pointer to fastcot_weight_bytes() bytes.  `layer` is
+ * ignored for EMB/WLM/GF.  Asynchronous on hip_stream; the canonical buffer may be reused once
+ * the stream has passed this call.  Every tensor must be packed before fastcot_init's context
+ * is used. */
+int fastcot_pack_tensor(const fastcot_config* cfg, int32_t tensor, int32_t layer, const void* d_canonical,
+                        void* d_packed, void* hip_stream);
+
+/* Creates a context over packed weights and a zero-initialised-or-not workspace (the library
+ * initialises what it needs, synchronously).  Both device buffers must stay alive and untouched
+ * by the caller until fastcot_free. */
+int fastcot_init(const fastcot_config* cfg, const void* d_packed, void* d_workspace, size_t workspace_bytes,
+                 void* hip_stream, fastcot_ctx** out);
+void fastcot_free(fastcot_ctx* ctx);
+const char* fastcot_last_error(const fastcot_ctx* ctx); /* ctx may be NULL */
+
+/* Starts B sequences (Sec. 4.1: prompt construction is the caller's; Sec. 4.2: the buffer).
+ * prompts: host [B][max_P], row b valid for lens[b] >= 1 tokens.  buffer_init: host [B][buf_len],
+ * the initial Approximate Tokens Buffer, entry i being the first guess for generated token i;
+ * buf_len <= max_seq.  Computes K/V of prompt tokens 0..len-2 and makes the last prompt token
+ * slot 0 of the first window, so the first generated token comes from the first step.
+ * Requires lens[b] - 1 + 2*window <= max_seq.  Synchronous. */
+int fastcot_prefill(fastcot_ctx* ctx, int32_t B, const int32_t* prompts, int32_t max_P, const int32_t* lens,
+                    const int32_t* buffer_init, int32_t buf_len);
+
+/* One Jacobi step (Eq. 4, Eq. 5, cache update) for every unfinished sequence.  Host outputs,
+ * each nullable: n_accepted[B] in 1..W (0 for a finished sequence); accepted[B][W], the first
+ * n_accepted[b] entries valid; window_next[B][W], the next step's window (slot 0 exact).  With
+ * all three NULL the call only enqueues work and returns without synchronising. */
+int fastcot_jacobi_step(fastcot_ctx* ctx, int32_t* n_accepted, int32_t* accepted, int32_t* window_next);
+
+/* Steps until every sequence has max_new_tokens exact tokens, or an exact token equals eos_id
+ * (eos_id < 0: off; approximate EOS tokens are ignored), or max_steps steps were taken
+ * (max_steps <= 0: no cap) -- the stop conditions of Sec. 4.4.  May be called after
+ * fastcot_prefill, once.  Host outputs: out_ids[B][max_new_tokens]; out_len[B] (count of valid
+ * ids, the EOS included); out_steps[B] (steps taken while the sequence was unfinished);
+ * approx_tail[B][W-1] (nullable), the approximate tokens left in the window at stop.  Requires
+ * buf_len >= max_new_tokens + 2*W and lens[b] - 1 + max_new_tokens + 2*W <= max_seq. */
+int fastcot_generate(fastcot_ctx* ctx, int32_t max_new_tokens, int32_t max_steps, int32_t eos_id,
+                     int32_t* out_ids, int32_t* out_len, int32_t* out_steps, int32_t* approx_tail);
+
+/* Per-sequence state after the last completed call, host outputs, each nullable: n[B] committed
+ * KV length; generated[B] exact tokens so far; done[B]; window[B][W] the window the next step
+ * will feed; last_o[B][W] and last_K[B], the argmax rows and verified count of the last step.
+ * Synchronises the stream. */
+int fastcot_get_state(fastcot_ctx* ctx, int32_t* n, int32_t* generated, int32_t* done, int32_t* window,
+                      int32_t* last_o, int32_t* last_K);
+
+/* Debug: if d_logits (device, fp32 [max_batch*W][vocab]) is non-NULL every following step also
+ * stores the full logits there (row b*W + j); NULL switches it off. */
+int fastcot_debug_logits(fastcot_ctx* ctx, float* d_logits);
+
+/* Options.  FASTCOT_OPT_PLAIN_KERNELS = 1 routes every step through the plain one-thread-per-
+ * output kernels (always used for fp32 models); 0 (default) uses the MFMA kernels for bf16.
+ * FASTCOT_OPT_GRAPH = 1 (default) replays a captured HIP graph per step; 0 launches kernels
+ * one by one.  A context on the default (NULL) stream always launches one by one, since that
+ * stream cannot be captured. */
+enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2 };
+int fastcot_set_option(fastcot_ctx* ctx, int32_t option, int32_t value);
+
+/* Wall time of the steps of the last fastcot_generate, measured with HIP events on the
+ * context's stream: ms[i] for step i, up to cap entries; *n_steps = steps taken. */
+int fastcot_step_times(fastcot_ctx* ctx, float* ms, int32_t cap, int32_t* n_steps);
+
+/* Runs `iters` forward passes of the current state (no accept, state unchanged), launching
+ * kernels one by one with a HIP event pair around each, and reports per kernel kind the mean
+ * duration of one launch in ms and the launches per step.  kinds: see fastcot_kernel_name().
+ * Host outputs sized FASTCOT_N_KERNEL_KINDS. */
+enum { FASTCOT_N_KERNEL_KINDS = 16 };
+int fastcot_profile_step(fastcot_ctx* ctx, int32_t iters, float* mean_ms, int32_t* launches_per_step);
+const char* fastcot_kernel_name(int32_t kind);
+
+/* Kernel-isolation entry points (the same kernels the step uses, on raw device pointers).
+ *
+ * Window-causal attention (Eq. 2 conditioning as a mask): q device fp32 [W][H][Dh] (already
+ * rotated); k_cache / vt_cache in the library's cache layout for one sequence, K as
+ * [Hkv][max_seq][Dh] and V transposed as [Hkv][Dh][max_seq], elements of `dtype`, positions
+ * 0..n+W-1 filled; row j attends positions 0..n+j.  out device fp32 [W][H*Dh].  scratch: device,
+ * fastcot_attn_scratch_bytes() bytes, zeroed once by the caller before first use.
+ * fastcot_kv_scatter writes canonical k, v (device, [S][Hkv][Dh], `dtype`) into that layout. */
+size_t fastcot_attn_scratch_bytes(int32_t W, int32_t H, int32_t Dh);
+int fastcot_kv_scatter(const void* d_k, const void* d_v, int32_t S, int32_t Hkv, int32_t Dh, int32_t max_seq,
+                       int32_t dtype, void* d_k_cache, void* d_vt_cache, void* hip_stream);
+int fastcot_attn_window(const float* d_q, const void* d_k_cache, const void* d_vt_cache, int32_t n, int32_t W,
+                        int32_t H, int32_t Hkv, int32_t Dh, int32_t max_seq, int32_t dtype, float* d_out,
+                        void* d_scratch, void* hip_stream);
+
+/* LM head fused with argmax (Eq. 1/2, lowest id on ties): act device fp32 [M][d] (already
+ * normalised), packed W_lm as written by fastcot_lmhead_pack from canonical bf16 [d][V];
+ * ids device int32 [M], top device fp32 [M] (the winning logit); d_logits nullable fp32 [M][V].
+ * scratch: device, fastcot_lmhead_scratch_bytes() bytes, zeroed once by the caller. */
+size_t fastcot_lmhead_packed_bytes(int32_t d, int32_t V);
+size_t fastcot_lmhead_scratch_bytes(int32_t M, int32_t d, int32_t V);
+int fastcot_lmhead_pack(const void* d_canonical_bf16, int32_t d, int32_t V, void* d_packed, void* hip_stream);
+int fastcot_lmhead_argmax(const float* d_act, const void* d_packed, int32_t M, int32_t d, int32_t V,
+                          int32_t* d_ids, float* d_top, float* d_logits, void* d_scratch, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTCOT_H */

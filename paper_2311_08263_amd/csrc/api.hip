@@ -1,0 +1,541 @@
+// C ABI of the FastCoT gfx950 library: context, weight packing, prefill, Jacobi step, generate.
+// The host code here only sequences kernel launches; every step of the decoding path (forward,
+// argmax, verification, acceptance, commit, window shift) runs in device kernels.
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include <vector>
+#include "kernels.h"
+#include "fast.h"
+
+static thread_local char g_err[512] = "";
+
+struct fastcot_ctx {
+    fastcot_config cfg;
+    ModelMap mm;
+    WorkspaceMap wm;
+    KernelDims kd;
+    const char* weights;
+    char* ws;
+    hipStream_t st;
+    int Bact;            // sequences of the current run
+    int prefilled, generated;
+    int buf_len;
+    int opt_plain, opt_graph;
+    float* dbg_logits;
+    hipGraphExec_t graph_exec;
+    hipGraph_t graph;
+    int graph_valid;
+    FastPlan plan;
+    // profiling of single launches
+    int prof_on;
+    std::vector<hipEvent_t> prof_ev;
+    std::vector<int> prof_kind;
+    size_t prof_used;
+    // step timing
+    std::vector<hipEvent_t> step_ev;
+    std::vector<float> step_ms;
+    int32_t* pinned;     // small pinned host block for polling
+    char err[512];
+};
+
+static int fail(fastcot_ctx* c, int code, const char* fmt, const char* a = "", long x = 0, long y = 0) {
+    char* dst = c ? c->err : g_err;
+    snprintf(dst, 512, fmt, a, x, y);
+    if (c) snprintf(g_err, 512, "%s", dst);
+    return code;
+}
+#define HIPCHK(c, call)                                                                          \
+    do {                                                                                         \
+        hipError_t e_ = (call);                                                                  \
+        if (e_ != hipSuccess) return fail(c, FASTCOT_EHIP, "HIP error '%s' at line %ld", hipGetErrorString(e_), __LINE__); \
+    } while (0)
+
+static const char* kKernelNames[FASTCOT_N_KERNEL_KINDS] = {
+    "embed", "rmsnorm", "gemm_qkv", "rope_cache", "attention", "gemm_o", "gemm_gate_up", "swiglu",
+    "gemm_down", "lm_head", "argmax", "accept_commit", "attn_combine", "reserved13", "reserved14", "reserved15"};
+enum { KK_EMBED = 0, KK_RMSNORM, KK_QKV, KK_ROPE, KK_ATTN, KK_O, KK_GU, KK_SWIGLU, KK_DOWN, KK_LM, KK_ARGMAX, KK_ACCEPT };
+
+extern "C" const char* fastcot_kernel_name(int32_t kind) {
+    return (kind >= 0 && kind < FASTCOT_N_KERNEL_KINDS) ? kKernelNames[kind] : "";
+}
+extern "C" const char* fastcot_last_error(const fastcot_ctx* ctx) { return ctx ? ctx->err : g_err; }
+
+// ------------------------------------------------------------------ layout maps
+static int valid_cfg(const fastcot_config* c) {
+    if (!c) return 0;
+    if (c->n_layers < 0 || c->d_model <= 0 || c->n_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 ||
+        c->d_ffn <= 0 || c->vocab <= 0 || c->max_batch <= 0 || c->max_seq <= 0 || c->window <= 0) return 0;
+    if (c->dtype != FASTCOT_F32 && c->dtype != FASTCOT_BF16) return 0;
+    if (c->n_heads % c->n_kv_heads) return 0;
+    if (c->head_dim % 16 || c->d_model % 16 || c->d_ffn % 16 || c->vocab % 16) return 0;
+    if (c->dtype == FASTCOT_BF16 && (c->d_model % 32 || c->d_ffn % 32 || (c->n_heads * c->head_dim) % 32)) return 0;
+    if (c->max_seq > 16000 || c->max_seq < 2 * c->window) return 0;
+    if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return 0;
+    return 1;
+}
+
+int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, KernelDims* kd) {
+    if (!valid_cfg(c)) return FASTCOT_EINVAL;
+    const size_t esz = c->dtype == FASTCOT_F32 ? 4 : 2;
+    const int d = c->d_model, qd = c->n_heads * c->head_dim, kvd = c->n_kv_heads * c->head_dim, F = c->d_ffn;
+    auto fused = [&](size_t& cur, int K, int N) {
+        FusedMat f; f.off = cur; f.K = K; f.N = N; f.NP = (N + 15) & ~15;
+        cur = FC_ALIGN(cur + (size_t)K * f.NP * esz);
+        return f;
+    };
+    if (mm) {
+        size_t cur = 0;
+        mm->qkv = fused(cur, d, qd + 2 * kvd);
+        mm->o = fused(cur, qd, d);
+        mm->gu = fused(cur, d, 2 * F);
+        mm->down = fused(cur, F, d);
+        mm->g1_off = cur; cur = FC_ALIGN(cur + (size_t)d * 4);
+        mm->g2_off = cur; cur = FC_ALIGN(cur + (size_t)d * 4);
+        mm->layer_stride = cur;
+        size_t top = 0;
+        mm->emb_off = top; top = FC_ALIGN(top + (size_t)c->vocab * d * esz);
+        mm->lm = fused(top, d, c->vocab);
+        mm->gf_off = top; top = FC_ALIGN(top + (size_t)d * 4);
+        mm->layers_off = top;
+        mm->total = top + (size_t)c->n_layers * mm->layer_stride;
+    }
+    KernelDims k;
+    k.L = c->n_layers; k.d = d; k.H = c->n_heads; k.Hkv = c->n_kv_heads; k.Dh = c->head_dim; k.F = F;
+    k.V = c->vocab; k.B = c->max_batch; k.S = c->max_seq; k.W = c->window; k.M = k.B * k.W;
+    k.qkvN = qd + 2 * kvd; k.eps = c->rms_eps; k.esz = (int)esz;
+    if (kd) *kd = k;
+    if (wm) {
+        size_t cur = 0;
+        auto take = [&](size_t bytes) { size_t o = cur; cur = FC_ALIGN(cur + bytes); return o; };
+        const size_t M = (size_t)k.M;
+        size_t cache = (size_t)k.L * k.B * k.Hkv * k.S * k.Dh * esz;
+        wm->kc = take(cache); wm->vc = take(cache);
+        wm->rope_cos = take((size_t)k.S * (k.Dh / 2) * 4); wm->rope_sin = take((size_t)k.S * (k.Dh / 2) * 4);
+        wm->x = take(M * d * 4); wm->nx = take(M * d * 4); wm->qkv = take(M * k.qkvN * 4);
+        wm->att = take(M * qd * 4); wm->gu = take(M * 2 * F * 4); wm->h = take(M * F * 4);
+        wm->logits = take(M * k.V * 4); wm->topv = take(M * 4);
+        fc_fast_scratch_sizes(k, &wm->gemm_part_bytes, &wm->attn_part_bytes);
+        wm->gemm_part = take(wm->gemm_part_bytes); wm->gemm_cnt = take(FC_MAX_COUNTERS * 4);
+        wm->attn_part = take(wm->attn_part_bytes); wm->attn_cnt = take(FC_MAX_COUNTERS * 4);
+        wm->amax_part = take(M * (size_t)((k.V + 127) / 128) * 8);
+        StateMap s; int w = 0;
+        auto ti = [&](int words) { int o = w; w += (words + 3) & ~3; return o; };
+        s.n = ti(k.B); s.g = ti(k.B); s.done = ti(k.B); s.steps = ti(k.B); s.newest = ti(k.B); s.lastK = ti(k.B);
+        s.plen = ti(k.B); s.olen = ti(k.B); s.win = ti(k.B * k.W); s.o = ti(k.B * k.W);
+        s.buf = ti(k.B * k.S); s.out = ti(k.B * k.S); s.prompt = ti(k.B * k.S); s.flags = ti(8); s.params = ti(8);
+        s.words = w;
+        wm->st = s;
+        wm->state = take((size_t)w * 4);
+        wm->total = cur;
+    }
+    return 0;
+}
+
+extern "C" size_t fastcot_weight_bytes(const fastcot_config* cfg) {
+    ModelMap mm;
+    return fc_build_maps(cfg, &mm, nullptr, nullptr) == 0 ? mm.total : 0;
+}
+extern "C" size_t fastcot_workspace_bytes(const fastcot_config* cfg) {
+    WorkspaceMap wm;
+    return fc_build_maps(cfg, nullptr, &wm, nullptr) == 0 ? wm.total : 0;
+}
+
+// ------------------------------------------------------------------ weight packing
+extern "C" int fastcot_pack_tensor(const fastcot_config* cfg, int32_t tensor, int32_t layer, const void* src,
+                                   void* d_packed, void* hip_stream) {
+    ModelMap mm; KernelDims kd;
+    if (fc_build_maps(cfg, &mm, nullptr, &kd) != 0) return fail(nullptr, FASTCOT_EINVAL, "invalid configuration%s");
+    if (!d_packed) return fail(nullptr, FASTCOT_EINVAL, "d_packed is NULL%s");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int dt = cfg->dtype, d = kd.d, qd = kd.H * kd.Dh, kvd = kd.Hkv * kd.Dh;
+    char* base = (char*)d_packed;
+    const bool per_layer = tensor >= FASTCOT_T_WQ;
+    if (per_layer && (layer < 0 || layer >= kd.L)) return fail(nullptr, FASTCOT_EINVAL, "layer out of range%s");
+    char* lbase = base + mm.layers_off + (size_t)(per_layer ? layer : 0) * mm.layer_stride;
+    const bool gain = tensor == FASTCOT_T_GF || tensor == FASTCOT_T_G1 || tensor == FASTCOT_T_G2;
+    if (!src && !gain) return fail(nullptr, FASTCOT_EINVAL, "d_canonical is NULL%s");
+    hipError_t e = hipSuccess;
+    switch (tensor) {
+        case FASTCOT_T_EMB: e = fc_copy_bytes(base + mm.emb_off, src, (size_t)kd.V * d * kd.esz, st); break;
+        case FASTCOT_T_WLM: e = fc_pack(src, dt, d, kd.V, base, mm.lm, 0, 0, st); break;
+        case FASTCOT_T_GF: case FASTCOT_T_G1: case FASTCOT_T_G2: {
+            float* dst = (float*)(tensor == FASTCOT_T_GF ? base + mm.gf_off
+                                  : lbase + (tensor == FASTCOT_T_G1 ? mm.g1_off : mm.g2_off));
+            e = src ? fc_copy_bytes(dst, src, (size_t)d * 4, st) : fc_fill_f32(dst, d, 1.0f, st);
+            break;
+        }
+        case FASTCOT_T_WQ: e = fc_pack(src, dt, d, qd, lbase, mm.qkv, 0, 0, st); break;
+        case FASTCOT_T_WK: e = fc_pack(src, dt, d, kvd, lbase, mm.qkv, qd, 0, st); break;
+        case FASTCOT_T_WV: e = fc_pack(src, dt, d, kvd, lbase, mm.qkv, qd + kvd, 0, st); break;
+        case FASTCOT_T_WO: e = fc_pack(src, dt, qd, d, lbase, mm.o, 0, 0, st); break;
+        case FASTCOT_T_WG: e = fc_pack(src, dt, d, kd.F, lbase, mm.gu, 0, 1, st); break;
+        case FASTCOT_T_WU: e = fc_pack(src, dt, d, kd.F, lbase, mm.gu, 0, 2, st); break;
+        case FASTCOT_T_WD: e = fc_pack(src, dt, kd.F, d, lbase, mm.down, 0, 0, st); break;
+        default: return fail(nullptr, FASTCOT_EINVAL, "unknown tensor id%s");
+    }
+    if (e != hipSuccess) return fail(nullptr, FASTCOT_EHIP, "pack launch failed: %s", hipGetErrorString(e));
+    return 0;
+}
+
+// ------------------------------------------------------------------ context
+static int32_t* state_ptr(fastcot_ctx* c) { return (int32_t*)(c->ws + c->wm.state); }
+
+extern "C" int fastcot_init(const fastcot_config* cfg, const void* d_packed, void* d_workspace, size_t workspace_bytes,
+                            void* hip_stream, fastcot_ctx** out) {
+    if (!out) return fail(nullptr, FASTCOT_EINVAL, "out is NULL%s");
+    *out = nullptr;
+    if (!d_packed || !d_workspace) return fail(nullptr, FASTCOT_EINVAL, "NULL device buffer%s");
+    fastcot_ctx* c = new (std::nothrow) fastcot_ctx();
+    if (!c) return fail(nullptr, FASTCOT_ENOMEM, "out of host memory%s");
+    if (fc_build_maps(cfg, &c->mm, &c->wm, &c->kd) != 0) { delete c; return fail(nullptr, FASTCOT_EINVAL, "invalid configuration%s"); }
+    if (workspace_bytes < c->wm.total) { delete c; return fail(nullptr, FASTCOT_ECAPACITY, "workspace too small%s"); }
+    c->cfg = *cfg; c->weights = (const char*)d_packed; c->ws = (char*)d_workspace; c->st = (hipStream_t)hip_stream;
+    c->Bact = 0; c->prefilled = 0; c->generated = 0; c->buf_len = 0;
+    c->opt_plain = (cfg->dtype == FASTCOT_F32); c->opt_graph = 1; c->dbg_logits = nullptr;
+    c->graph_exec = nullptr; c->graph = nullptr; c->graph_valid = 0; c->prof_on = 0; c->prof_used = 0;
+    c->pinned = nullptr; c->err[0] = 0;
+    fc_fast_plan(c->kd, &c->plan);
+    // rotary table: cos/sin of pos * base^(-2i/Dh), evaluated in double on the host
+    const int half = c->kd.Dh / 2;
+    std::vector<float> cs((size_t)c->kd.S * half), sn((size_t)c->kd.S * half);
+    for (int p = 0; p < c->kd.S; ++p)
+        for (int i = 0; i < half; ++i) {
+            double ang = (double)p * pow((double)cfg->rope_base, -2.0 * i / (double)c->kd.Dh);
+            cs[(size_t)p * half + i] = (float)cos(ang); sn[(size_t)p * half + i] = (float)sin(ang);
+        }
+#define INITCHK(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { int rc_ = fail(nullptr, FASTCOT_EHIP, "HIP error '%s' in init line %ld", hipGetErrorString(e_), __LINE__); if (c->pinned) (void)hipHostFree(c->pinned); delete c; return rc_; } } while (0)
+    INITCHK(hipHostMalloc((void**)&c->pinned, 4096 * 4, hipHostMallocDefault));
+    INITCHK(hipMemcpyAsync(c->ws + c->wm.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice, c->st));
+    INITCHK(hipMemcpyAsync(c->ws + c->wm.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice, c->st));
+    INITCHK(hipMemsetAsync(c->ws + c->wm.state, 0, (size_t)c->wm.st.words * 4, c->st));
+    INITCHK(hipMemsetAsync(c->ws + c->wm.gemm_cnt, 0, FC_MAX_COUNTERS * 4, c->st));
+    INITCHK(hipMemsetAsync(c->ws + c->wm.attn_cnt, 0, FC_MAX_COUNTERS * 4, c->st));
+    INITCHK(hipMemsetAsync(c->ws + c->wm.kc, 0, c->wm.rope_cos - c->wm.kc, c->st));   // whole KV cache
+    INITCHK(hipStreamSynchronize(c->st));
+#undef INITCHK
+    *out = c;
+    return 0;
+}
+
+static void drop_graph(fastcot_ctx* c) {
+    if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
+    if (c->graph) (void)hipGraphDestroy(c->graph);
+    c->graph_exec = nullptr; c->graph = nullptr; c->graph_valid = 0;
+}
+
+extern "C" void fastcot_free(fastcot_ctx* c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->st);
+    drop_graph(c);
+    for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->step_ev) (void)hipEventDestroy(e);
+    if (c->pinned) (void)hipHostFree(c->pinned);
+    delete c;
+}
+
+extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value) {
+    if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
+    if (option == FASTCOT_OPT_PLAIN_KERNELS) {
+        if (!value && c->cfg.dtype == FASTCOT_F32) return fail(c, FASTCOT_EINVAL, "fp32 models only have the plain kernels%s");
+        c->opt_plain = value != 0;
+    } else if (option == FASTCOT_OPT_GRAPH) c->opt_graph = value != 0;
+    else return fail(c, FASTCOT_EINVAL, "unknown option%s");
+    drop_graph(c);
+    return 0;
+}
+
+extern "C" int fastcot_debug_logits(fastcot_ctx* c, float* d_logits) {
+    if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
+    c->dbg_logits = d_logits;
+    drop_graph(c);
+    return 0;
+}
+
+// ------------------------------------------------------------------ forward pass
+static hipError_t prof_mark(fastcot_ctx* c, int kind) {
+    if (c->prof_used >= c->prof_ev.size()) {
+        hipEvent_t e; hipError_t r = hipEventCreate(&e);
+        if (r != hipSuccess) return r;
+        c->prof_ev.push_back(e); c->prof_kind.push_back(0);
+    }
+    c->prof_kind[c->prof_used] = kind;
+    return hipEventRecord(c->prof_ev[c->prof_used++], c->st);
+}
+#define LAUNCH(c, kind, call)                                                      \
+    do {                                                                           \
+        if ((c)->prof_on) HIPCHK(c, prof_mark(c, kind));                           \
+        HIPCHK(c, call);                                                           \
+        if ((c)->prof_on) HIPCHK(c, prof_mark(c, -1));                             \
+    } while (0)
+
+static int forward_plain(fastcot_ctx* c, int lmhead) {
+    const KernelDims kd0 = c->kd;
+    KernelDims kd = kd0; kd.M = c->Bact * kd.W;
+    const int dt = c->cfg.dtype, M = kd.M, d = kd.d, qd = kd.H * kd.Dh;
+    char* ws = c->ws; const char* wt = c->weights;
+    int32_t* stp = state_ptr(c);
+    const StateMap& sm = c->wm.st;
+    float* x = (float*)(ws + c->wm.x); float* nx = (float*)(ws + c->wm.nx); float* qkv = (float*)(ws + c->wm.qkv);
+    float* att = (float*)(ws + c->wm.att); float* gu = (float*)(ws + c->wm.gu); float* h = (float*)(ws + c->wm.h);
+    LAUNCH(c, KK_EMBED, fc_embed(wt + c->mm.emb_off, dt, stp + sm.win, x, M, d, kd.V, c->st));
+    for (int l = 0; l < kd.L; ++l) {
+        const char* lb = wt + c->mm.layers_off + (size_t)l * c->mm.layer_stride;
+        LAUNCH(c, KK_RMSNORM, fc_rmsnorm_plain(x, (const float*)(lb + c->mm.g1_off), nx, M, d, kd.eps, c->st));
+        LAUNCH(c, KK_QKV, fc_gemm_plain(lb + c->mm.qkv.off, dt, d, c->mm.qkv.NP, kd.qkvN, nx, d, qkv, kd.qkvN, M, 0, c->st));
+        LAUNCH(c, KK_ROPE, fc_rope_cache_plain(qkv, kd, l, stp + sm.n, (const float*)(ws + c->wm.rope_cos),
+                                               (const float*)(ws + c->wm.rope_sin), ws + c->wm.kc, ws + c->wm.vc, dt, c->st));
+        LAUNCH(c, KK_ATTN, fc_attn_plain(qkv, kd.qkvN, ws + c->wm.kc, ws + c->wm.vc, dt, kd, l, stp + sm.n, att, c->st));
+        LAUNCH(c, KK_O, fc_gemm_plain(lb + c->mm.o.off, dt, qd, c->mm.o.NP, d, att, qd, x, d, M, 1, c->st));
+        LAUNCH(c, KK_RMSNORM, fc_rmsnorm_plain(x, (const float*)(lb + c->mm.g2_off), nx, M, d, kd.eps, c->st));
+        LAUNCH(c, KK_GU, fc_gemm_plain(lb + c->mm.gu.off, dt, d, c->mm.gu.NP, 2 * kd.F, nx, d, gu, 2 * kd.F, M, 0, c->st));
+        LAUNCH(c, KK_SWIGLU, fc_swiglu_plain(gu, h, M, kd.F, 2 * kd.F, c->st));
+        LAUNCH(c, KK_DOWN, fc_gemm_plain(lb + c->mm.down.off, dt, kd.F, c->mm.down.NP, d, h, kd.F, x, d, M, 1, c->st));
+    }
+    if (lmhead) {
+        float* logits = c->dbg_logits ? c->dbg_logits : (float*)(ws + c->wm.logits);
+        LAUNCH(c, KK_RMSNORM, fc_rmsnorm_plain(x, (const float*)(wt + c->mm.gf_off), nx, M, d, kd.eps, c->st));
+        LAUNCH(c, KK_LM, fc_gemm_plain(wt + c->mm.lm.off, dt, d, c->mm.lm.NP, kd.V, nx, d, logits, kd.V, M, 0, c->st));
+        LAUNCH(c, KK_ARGMAX, fc_argmax_plain(logits, M, kd.V, stp + sm.o, (float*)(ws + c->wm.topv), c->st));
+    }
+    return 0;
+}
+
+static int forward(fastcot_ctx* c, int lmhead) {
+    if (c->opt_plain) return forward_plain(c, lmhead);
+    FastArgs a;
+    a.kd = c->kd; a.kd.M = c->Bact * c->kd.W; a.Bact = c->Bact;
+    a.mm = &c->mm; a.wm = &c->wm; a.weights = c->weights; a.ws = c->ws; a.dbg_logits = c->dbg_logits;
+    a.plan = &c->plan; a.st = c->st; a.lmhead = lmhead;
+    a.prof = c->prof_on ? c : nullptr;
+    a.prof_mark = c->prof_on ? [](void* p, int kind) { return prof_mark((fastcot_ctx*)p, kind); } : nullptr;
+    hipError_t e = fc_fast_forward(a);
+    if (e != hipSuccess) return fail(c, FASTCOT_EHIP, "fast forward failed: %s", hipGetErrorString(e));
+    return 0;
+}
+
+static int step_body(fastcot_ctx* c) {
+    int rc = forward(c, 1);
+    if (rc) return rc;
+    LAUNCH(c, KK_ACCEPT, fc_accept_commit(state_ptr(c), c->wm.st, c->Bact, c->kd.W, c->kd.S, c->st));
+    return 0;
+}
+
+static int enqueue_step(fastcot_ctx* c) {
+    // the legacy default stream cannot be captured: launch kernel by kernel there
+    if (!c->opt_graph || c->prof_on || c->st == nullptr) return step_body(c);
+    if (!c->graph_valid) {
+        HIPCHK(c, hipStreamBeginCapture(c->st, hipStreamCaptureModeThreadLocal));
+        int rc = step_body(c);
+        hipGraph_t g = nullptr;
+        hipError_t e = hipStreamEndCapture(c->st, &g);
+        if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
+        if (e != hipSuccess) return fail(c, FASTCOT_EHIP, "graph capture failed: %s", hipGetErrorString(e));
+        c->graph = g;
+        HIPCHK(c, hipGraphInstantiate(&c->graph_exec, c->graph, nullptr, nullptr, 0));
+        c->graph_valid = 1;
+    }
+    HIPCHK(c, hipGraphLaunch(c->graph_exec, c->st));
+    return 0;
+}
+
+// ------------------------------------------------------------------ prefill
+extern "C" int fastcot_prefill(fastcot_ctx* c, int32_t B, const int32_t* prompts, int32_t max_P, const int32_t* lens,
+                               const int32_t* buffer_init, int32_t buf_len) {
+    if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
+    if (!prompts || !lens || !buffer_init || max_P < 1) return fail(c, FASTCOT_EINVAL, "NULL or empty prompt arguments%s");
+    if (B < 1) return fail(c, FASTCOT_EINVAL, "batch must be >= 1%s");
+    const KernelDims& kd = c->kd;
+    if (B > kd.B) return fail(c, FASTCOT_ECAPACITY, "batch %s%ld exceeds max_batch %ld", "", B, kd.B);
+    if (buf_len > kd.S) return fail(c, FASTCOT_ECAPACITY, "buf_len %s%ld exceeds max_seq %ld", "", buf_len, kd.S);
+    if (buf_len < 2 * kd.W) return fail(c, FASTCOT_EINVAL, "buf_len %s%ld must be at least 2*window = %ld", "", buf_len, 2 * kd.W);
+    int maxlen = 0;
+    for (int b = 0; b < B; ++b) {
+        if (lens[b] < 1 || lens[b] > max_P) return fail(c, FASTCOT_EINVAL, "prompt length out of range%s");
+        if (lens[b] - 1 + 2 * kd.W > kd.S) return fail(c, FASTCOT_ECAPACITY, "prompt of %s%ld tokens does not fit max_seq %ld", "", lens[b], kd.S);
+        for (int i = 0; i < lens[b]; ++i)
+            if (prompts[(size_t)b * max_P + i] < 0 || prompts[(size_t)b * max_P + i] >= kd.V) return fail(c, FASTCOT_EINVAL, "prompt token out of vocabulary%s");
+        if (lens[b] > maxlen) maxlen = lens[b];
+    }
+    for (size_t i = 0; i < (size_t)B * buf_len; ++i)
+        if (buffer_init[i] < 0 || buffer_init[i] >= kd.V) return fail(c, FASTCOT_EINVAL, "buffer token out of vocabulary%s");
+    const StateMap& sm = c->wm.st;
+    int32_t* stp = state_ptr(c);
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    std::vector<int32_t> tmp((size_t)B * kd.S, 0);
+    for (int b = 0; b < B; ++b) memcpy(&tmp[(size_t)b * kd.S], prompts + (size_t)b * max_P, (size_t)lens[b] * 4);
+    HIPCHK(c, hipMemcpy(stp + sm.prompt, tmp.data(), tmp.size() * 4, hipMemcpyHostToDevice));
+    std::fill(tmp.begin(), tmp.end(), 0);
+    for (int b = 0; b < B; ++b) memcpy(&tmp[(size_t)b * kd.S], buffer_init + (size_t)b * buf_len, (size_t)buf_len * 4);
+    HIPCHK(c, hipMemcpy(stp + sm.buf, tmp.data(), tmp.size() * 4, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(stp + sm.plen, lens, (size_t)B * 4, hipMemcpyHostToDevice));
+    int32_t params[8] = {0x3fffffff, -1, 0, buf_len, B, 0, 0, 0};
+    HIPCHK(c, hipMemcpy(stp + sm.params, params, sizeof(params), hipMemcpyHostToDevice));
+    int32_t zeros[8] = {0};
+    HIPCHK(c, hipMemcpy(stp + sm.flags, zeros, sizeof(zeros), hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemset(stp + sm.n, 0, (size_t)kd.B * 4));
+    if (B != c->Bact) drop_graph(c);
+    c->Bact = B; c->buf_len = buf_len; c->prefilled = 0; c->generated = 0;
+    const int chunks = (maxlen - 1 + kd.W - 1) / kd.W;
+    const int nch = chunks > 0 ? chunks : 1;   // one pass even for 1-token prompts (sets up the window)
+    for (int ch = 0; ch < nch; ++ch) {
+        HIPCHK(c, fc_prefill_window(stp, sm, B, kd.W, kd.S, ch, c->st));
+        if (chunks > 0) { int rc = forward(c, 0); if (rc) return rc; }
+        HIPCHK(c, fc_prefill_advance(stp, sm, B, kd.W, kd.S, ch, ch == nch - 1, c->st));
+    }
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    c->prefilled = 1;
+    return 0;
+}
+
+// ------------------------------------------------------------------ one step
+extern "C" int fastcot_jacobi_step(fastcot_ctx* c, int32_t* n_accepted, int32_t* accepted, int32_t* window_next) {
+    if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
+    if (!c->prefilled) return fail(c, FASTCOT_ESTATE, "fastcot_jacobi_step before fastcot_prefill%s");
+    int rc = enqueue_step(c);
+    if (rc) return rc;
+    if (!n_accepted && !accepted && !window_next) return 0;
+    const StateMap& sm = c->wm.st; const int B = c->Bact, W = c->kd.W;
+    int32_t* stp = state_ptr(c);
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    std::vector<int32_t> K(B), o((size_t)B * W);
+    HIPCHK(c, hipMemcpy(K.data(), stp + sm.lastK, (size_t)B * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(o.data(), stp + sm.o, (size_t)B * W * 4, hipMemcpyDeviceToHost));
+    for (int b = 0; b < B; ++b) {
+        if (n_accepted) n_accepted[b] = K[b] + 1;    // lastK is -1 for a finished sequence
+        if (accepted) for (int j = 0; j < W; ++j) accepted[(size_t)b * W + j] = (j <= K[b]) ? o[(size_t)b * W + j] : -1;
+    }
+    if (window_next) HIPCHK(c, hipMemcpy(window_next, stp + sm.win, (size_t)B * W * 4, hipMemcpyDeviceToHost));
+    int32_t flags[2];
+    HIPCHK(c, hipMemcpy(flags, stp + sm.flags, 8, hipMemcpyDeviceToHost));
+    if (flags[FLAG_ERROR]) return fail(c, FASTCOT_ECAPACITY, "a sequence ran out of cache or buffer capacity%s");
+    return 0;
+}
+
+// ------------------------------------------------------------------ generate
+extern "C" int fastcot_generate(fastcot_ctx* c, int32_t max_new, int32_t max_steps, int32_t eos_id, int32_t* out_ids,
+                                int32_t* out_len, int32_t* out_steps, int32_t* approx_tail) {
+    if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
+    if (!c->prefilled) return fail(c, FASTCOT_ESTATE, "fastcot_generate before fastcot_prefill%s");
+    if (c->generated) return fail(c, FASTCOT_ESTATE, "fastcot_generate may be called once per prefill%s");
+    if (!out_ids || !out_len || !out_steps || max_new < 1) return fail(c, FASTCOT_EINVAL, "bad output arguments%s");
+    const KernelDims& kd = c->kd; const StateMap& sm = c->wm.st; const int B = c->Bact, W = kd.W;
+    if (c->buf_len < max_new + 2 * W) return fail(c, FASTCOT_ECAPACITY, "buf_len %s%ld is below max_new_tokens + 2*window = %ld", "", c->buf_len, max_new + 2 * W);
+    int32_t* stp = state_ptr(c);
+    std::vector<int32_t> hn(B), hg(B), hdone(B, 0);
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    HIPCHK(c, hipMemcpy(hn.data(), stp + sm.n, (size_t)B * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(hg.data(), stp + sm.g, (size_t)B * 4, hipMemcpyDeviceToHost));
+    for (int b = 0; b < B; ++b) {
+        if (hg[b] != 0) return fail(c, FASTCOT_ESTATE, "fastcot_generate after fastcot_jacobi_step is not supported%s");
+        if (hn[b] + max_new + 2 * W > kd.S) return fail(c, FASTCOT_ECAPACITY, "prompt + max_new_tokens + 2*window exceeds max_seq%s");
+    }
+    int32_t params[8] = {max_new, eos_id < 0 ? -1 : eos_id, max_steps > 0 ? max_steps : 0, c->buf_len, B, 0, 0, 0};
+    HIPCHK(c, hipMemcpy(stp + sm.params, params, sizeof(params), hipMemcpyHostToDevice));
+    c->generated = 1;
+    c->step_ms.clear();
+    size_t ev_used = 0;
+    auto next_event = [&](hipEvent_t* ev) -> hipError_t {
+        if (ev_used >= c->step_ev.size()) {
+            if (c->step_ev.size() >= 8192) { *ev = nullptr; return hipSuccess; }
+            hipEvent_t e; hipError_t r = hipEventCreate(&e);
+            if (r != hipSuccess) return r;
+            c->step_ev.push_back(e);
+        }
+        *ev = c->step_ev[ev_used++];
+        return hipSuccess;
+    };
+    int total_steps = 0;
+    bool all_done = false;
+    hipEvent_t ev;
+    HIPCHK(c, next_event(&ev));
+    if (ev) HIPCHK(c, hipEventRecord(ev, c->st));
+    while (!all_done) {
+        // every unfinished sequence needs at least ceil((max_new - g) / W) more steps: enqueue that many
+        int need = 1;
+        for (int b = 0; b < B; ++b) {
+            int r = (max_new - hg[b] + W - 1) / W;
+            if (total_steps == 0 || !hdone[b]) need = r > need ? r : need;
+        }
+        if (max_steps > 0 && need > max_steps - total_steps) need = max_steps - total_steps;
+        if (need < 1) need = 1;
+        for (int s = 0; s < need; ++s) {
+            int rc = enqueue_step(c);
+            if (rc) return rc;
+            HIPCHK(c, next_event(&ev));
+            if (ev) HIPCHK(c, hipEventRecord(ev, c->st));
+            ++total_steps;
+        }
+        HIPCHK(c, hipMemcpyAsync(c->pinned, stp + sm.g, (size_t)B * 4, hipMemcpyDeviceToHost, c->st));
+        HIPCHK(c, hipMemcpyAsync(c->pinned + B, stp + sm.done, (size_t)B * 4, hipMemcpyDeviceToHost, c->st));
+        HIPCHK(c, hipMemcpyAsync(c->pinned + 2 * B, stp + sm.flags, 8, hipMemcpyDeviceToHost, c->st));
+        HIPCHK(c, hipStreamSynchronize(c->st));
+        all_done = c->pinned[2 * B + FLAG_ALL_DONE] != 0;
+        for (int b = 0; b < B; ++b) { hg[b] = c->pinned[b]; hdone[b] = c->pinned[B + b]; }
+        if (c->pinned[2 * B + FLAG_ERROR]) return fail(c, FASTCOT_ECAPACITY, "a sequence ran out of cache or buffer capacity%s");
+    }
+    for (size_t i = 0; i + 1 < ev_used; ++i) {
+        float ms = 0; HIPCHK(c, hipEventElapsedTime(&ms, c->step_ev[i], c->step_ev[i + 1]));
+        c->step_ms.push_back(ms);
+    }
+    std::vector<int32_t> tmp((size_t)B * kd.S);
+    HIPCHK(c, hipMemcpy(tmp.data(), stp + sm.out, tmp.size() * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(out_len, stp + sm.olen, (size_t)B * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(out_steps, stp + sm.steps, (size_t)B * 4, hipMemcpyDeviceToHost));
+    for (int b = 0; b < B; ++b)
+        for (int i = 0; i < max_new; ++i) out_ids[(size_t)b * max_new + i] = i < out_len[b] ? tmp[(size_t)b * kd.S + i] : -1;
+    if (approx_tail && W > 1) {
+        std::vector<int32_t> win((size_t)B * W);
+        HIPCHK(c, hipMemcpy(win.data(), stp + sm.win, win.size() * 4, hipMemcpyDeviceToHost));
+        for (int b = 0; b < B; ++b) for (int j = 1; j < W; ++j) approx_tail[(size_t)b * (W - 1) + j - 1] = win[(size_t)b * W + j];
+    }
+    return 0;
+}
+
+extern "C" int fastcot_step_times(fastcot_ctx* c, float* ms, int32_t cap, int32_t* n_steps) {
+    if (!c || !n_steps) return fail(c, FASTCOT_EINVAL, "NULL argument%s");
+    *n_steps = (int32_t)c->step_ms.size();
+    for (int i = 0; ms && i < cap && i < *n_steps; ++i) ms[i] = c->step_ms[i];
+    return 0;
+}
+
+extern "C" int fastcot_get_state(fastcot_ctx* c, int32_t* n, int32_t* generated, int32_t* done, int32_t* window,
+                                 int32_t* last_o, int32_t* last_K) {
+    if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
+    if (!c->prefilled) return fail(c, FASTCOT_ESTATE, "no sequences: call fastcot_prefill first%s");
+    const StateMap& sm = c->wm.st; const int B = c->Bact, W = c->kd.W;
+    int32_t* stp = state_ptr(c);
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    if (n) HIPCHK(c, hipMemcpy(n, stp + sm.n, (size_t)B * 4, hipMemcpyDeviceToHost));
+    if (generated) HIPCHK(c, hipMemcpy(generated, stp + sm.g, (size_t)B * 4, hipMemcpyDeviceToHost));
+    if (done) HIPCHK(c, hipMemcpy(done, stp + sm.done, (size_t)B * 4, hipMemcpyDeviceToHost));
+    if (window) HIPCHK(c, hipMemcpy(window, stp + sm.win, (size_t)B * W * 4, hipMemcpyDeviceToHost));
+    if (last_o) HIPCHK(c, hipMemcpy(last_o, stp + sm.o, (size_t)B * W * 4, hipMemcpyDeviceToHost));
+    if (last_K) HIPCHK(c, hipMemcpy(last_K, stp + sm.lastK, (size_t)B * 4, hipMemcpyDeviceToHost));
+    return 0;
+}
+
+// ------------------------------------------------------------------ per-kernel timing of the forward
+extern "C" int fastcot_profile_step(fastcot_ctx* c, int32_t iters, float* mean_ms, int32_t* launches_per_step) {
+    if (!c || !mean_ms || !launches_per_step || iters < 1) return fail(c, FASTCOT_EINVAL, "bad arguments%s");
+    if (!c->prefilled) return fail(c, FASTCOT_ESTATE, "fastcot_profile_step before fastcot_prefill%s");
+    double sum[FASTCOT_N_KERNEL_KINDS] = {0}; long cnt[FASTCOT_N_KERNEL_KINDS] = {0};
+    for (int it = 0; it < iters; ++it) {
+        c->prof_on = 1; c->prof_used = 0;
+        int rc = forward(c, 1);
+        c->prof_on = 0;
+        if (rc) return rc;
+        HIPCHK(c, hipStreamSynchronize(c->st));
+        for (size_t i = 0; i + 1 < c->prof_used; i += 2) {
+            float ms = 0; HIPCHK(c, hipEventElapsedTime(&ms, c->prof_ev[i], c->prof_ev[i + 1]));
+            int k = c->prof_kind[i];
+            if (k >= 0 && k < FASTCOT_N_KERNEL_KINDS) { sum[k] += ms; cnt[k]++; }
+        }
+    }
+    for (int k = 0; k < FASTCOT_N_KERNEL_KINDS; ++k) {
+        mean_ms[k] = cnt[k] ? (float)(sum[k] / cnt[k]) : 0.f;
+        launches_per_step[k] = (int32_t)(cnt[k] / iters);
+    }
+    return 0;
+}

@@ -1,0 +1,81 @@
+// Shared declarations of the FastCoT gfx950 library: workspace map, packed-weight map,
+// device-side state block and small device helpers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/fastcot.h"
+
+typedef uint16_t bf16_t;  // raw bf16 bit pattern
+
+__host__ __device__ inline float bf16_to_f32(bf16_t b) {
+    union { uint32_t u; float f; } v; v.u = (uint32_t)b << 16; return v.f;
+}
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {  // round to nearest even, finite inputs
+    union { uint32_t u; float f; } v; v.f = f;
+    v.u += 0x7FFFu + ((v.u >> 16) & 1u);
+    return (bf16_t)(v.u >> 16);
+}
+
+// ------------------------------------------------------------------ packed weights
+// A fused matrix has K rows (inputs) and NP columns (outputs, padded to a multiple of 16).
+// fp32 models keep it row-major [K][NP].  bf16 models keep it in MFMA fragment order: the
+// 16-column x 32-row tile (nt, kt) is 64 lanes x 8 values, lane = (col % 16) + 16 * ((row % 32) / 8),
+// value = row % 8, tiles ordered [nt][kt]; one wave reads a tile with one 16-byte load per lane.
+struct FusedMat {
+    size_t off;     // byte offset inside the packed weights
+    int32_t K, N;   // logical rows, logical columns
+    int32_t NP;     // padded columns
+};
+__host__ __device__ inline size_t frag_index(int32_t K, int32_t k, int32_t n) {
+    int32_t KT = K >> 5;
+    int32_t nt = n >> 4, kt = k >> 5;
+    int32_t lane = (n & 15) + 16 * ((k & 31) >> 3);
+    return ((size_t)(nt * (size_t)KT + kt) * 64 + lane) * 8 + (k & 7);
+}
+
+// column order of the fused gate/up matrix: 16-column blocks alternate gate, up
+__host__ __device__ inline int32_t gu_col(int32_t feature, int32_t is_up) {
+    return ((feature >> 4) << 5) + (is_up << 4) + (feature & 15);
+}
+
+struct ModelMap {
+    FusedMat qkv, o, gu, down;   // per layer, offsets relative to the layer base
+    size_t g1_off, g2_off;       // per layer fp32 gains
+    size_t layer_stride;         // bytes per layer
+    size_t layers_off;           // byte offset of layer 0
+    size_t emb_off;              // [V][d] row-major, model dtype
+    FusedMat lm;                 // absolute offset
+    size_t gf_off;
+    size_t total;
+};
+
+// ------------------------------------------------------------------ device state block (int32 words)
+struct StateMap {      // offsets in int32 words from the state base
+    int32_t n, g, done, steps, newest, lastK, plen, olen, win, o, buf, out, prompt, flags, params;
+    int32_t words;
+};
+enum { FLAG_ALL_DONE = 0, FLAG_ERROR = 1 };
+enum { PARAM_MAX_NEW = 0, PARAM_EOS = 1, PARAM_MAX_STEPS = 2, PARAM_BUF_LEN = 3, PARAM_B = 4 };
+
+struct WorkspaceMap {
+    size_t kc, vc;              // KV cache: K [L][B][Hkv][S][Dh], V transposed [L][B][Hkv][Dh][S]
+    size_t rope_cos, rope_sin;  // fp32 [S][Dh/2]
+    size_t x, nx, qkv, att, gu, h, logits, topv;
+    size_t gemm_part, gemm_cnt, attn_part, attn_cnt, amax_part;
+    size_t state;
+    size_t total;
+    size_t gemm_part_bytes, attn_part_bytes;
+    StateMap st;
+};
+
+struct KernelDims {    // model + capacities as the kernels need them
+    int32_t L, d, H, Hkv, Dh, F, V, B, S, W, M;
+    int32_t qkvN;      // (H + 2 Hkv) * Dh
+    float eps;
+    int32_t esz;       // bytes per weight / cache element
+};
+
+int fc_build_maps(const fastcot_config* cfg, ModelMap* mm, WorkspaceMap* wm, KernelDims* kd);
+
+#define FC_ALIGN(x) (((x) + 255) & ~(size_t)255)

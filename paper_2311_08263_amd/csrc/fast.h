@@ -1,0 +1,39 @@
+// MFMA (matrix-core) forward path for bf16 models: launch plan and entry point.
+#pragma once
+#include "common.h"
+
+#define FC_MAX_COUNTERS 8192
+
+struct GemmPlan {      // how one weight-streaming GEMM is cut into workgroups
+    int32_t ncg;       // column groups of 8 n-tiles (128 columns)
+    int32_t sk;        // K slices per column group (cross-workgroup split-K with ordered fix-up)
+};
+struct FastPlan {
+    GemmPlan qkv, o, gu, down, lm;
+    int32_t attn_splits;
+};
+struct FastArgs {
+    KernelDims kd;
+    int Bact, lmhead;
+    const ModelMap* mm;
+    const WorkspaceMap* wm;
+    const char* weights;
+    char* ws;
+    float* dbg_logits;
+    const FastPlan* plan;
+    hipStream_t st;
+    void* prof;
+    hipError_t (*prof_mark)(void*, int);
+};
+
+void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t* attn_part_bytes);
+void fc_fast_plan(const KernelDims& kd, FastPlan* plan);
+hipError_t fc_fast_forward(const FastArgs& a);
+
+// isolation launchers (same kernels as the step)
+size_t fc_attn_iso_scratch_bytes(int W, int H, int Dh);
+hipError_t fc_attn_iso(const float* q, const void* kc, const void* vc, int n, int W, int H, int Hkv, int Dh, int S,
+                       int dt, float* out, void* scratch, hipStream_t st);
+size_t fc_lmhead_iso_scratch_bytes(int M, int d, int V);
+hipError_t fc_lmhead_iso(const float* act, const void* packed, int M, int d, int V, int32_t* ids, float* top,
+                         float* logits, void* scratch, hipStream_t st);

@@ -1,0 +1,52 @@
+// Kernel-isolation entry points: the step's attention and LM-head kernels on raw device pointers.
+#include <stdio.h>
+#include "kernels.h"
+#include "fast.h"
+
+
+extern "C" size_t fastcot_attn_scratch_bytes(int32_t W, int32_t H, int32_t Dh) {
+    if (W <= 0 || H <= 0 || Dh <= 0) return 0;
+    return fc_attn_iso_scratch_bytes(W, H, Dh);
+}
+
+extern "C" int fastcot_kv_scatter(const void* d_k, const void* d_v, int32_t S, int32_t Hkv, int32_t Dh, int32_t max_seq,
+                                  int32_t dtype, void* d_k_cache, void* d_vt_cache, void* hip_stream) {
+    if (!d_k || !d_v || !d_k_cache || !d_vt_cache || S <= 0 || S > max_seq || Hkv <= 0 || Dh <= 0 ||
+        (dtype != FASTCOT_F32 && dtype != FASTCOT_BF16)) return FASTCOT_EINVAL;
+    hipError_t e = fc_kv_scatter(d_k, d_v, S, Hkv, Dh, max_seq, dtype, d_k_cache, d_vt_cache, (hipStream_t)hip_stream);
+    return e == hipSuccess ? 0 : FASTCOT_EHIP;
+}
+
+extern "C" int fastcot_attn_window(const float* d_q, const void* d_k_cache, const void* d_vt_cache, int32_t n, int32_t W,
+                                   int32_t H, int32_t Hkv, int32_t Dh, int32_t max_seq, int32_t dtype, float* d_out,
+                                   void* d_scratch, void* hip_stream) {
+    if (!d_q || !d_k_cache || !d_vt_cache || !d_out || !d_scratch) return FASTCOT_EINVAL;
+    if (n < 0 || W <= 0 || H <= 0 || Hkv <= 0 || H % Hkv || Dh <= 0 || Dh % 16 || max_seq > 16000) return FASTCOT_EINVAL;
+    if (dtype != FASTCOT_F32 && dtype != FASTCOT_BF16) return FASTCOT_EINVAL;
+    if (n + W > max_seq) return FASTCOT_ECAPACITY;
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e = fc_attn_iso(d_q, d_k_cache, d_vt_cache, n, W, H, Hkv, Dh, max_seq, dtype, d_out, d_scratch, st);
+    return e == hipSuccess ? 0 : FASTCOT_EHIP;
+}
+
+extern "C" size_t fastcot_lmhead_packed_bytes(int32_t d, int32_t V) {
+    if (d <= 0 || V <= 0 || d % 32 || V % 16) return 0;
+    return (size_t)d * V * 2;
+}
+extern "C" size_t fastcot_lmhead_scratch_bytes(int32_t M, int32_t d, int32_t V) {
+    if (M <= 0 || d <= 0 || V <= 0) return 0;
+    return fc_lmhead_iso_scratch_bytes(M, d, V);
+}
+extern "C" int fastcot_lmhead_pack(const void* src, int32_t d, int32_t V, void* d_packed, void* hip_stream) {
+    if (!src || !d_packed || d <= 0 || V <= 0 || d % 32 || V % 16) return FASTCOT_EINVAL;
+    FusedMat fm; fm.off = 0; fm.K = d; fm.N = V; fm.NP = V;
+    hipError_t e = fc_pack(src, FASTCOT_BF16, d, V, d_packed, fm, 0, 0, (hipStream_t)hip_stream);
+    return e == hipSuccess ? 0 : FASTCOT_EHIP;
+}
+extern "C" int fastcot_lmhead_argmax(const float* d_act, const void* d_packed, int32_t M, int32_t d, int32_t V,
+                                     int32_t* d_ids, float* d_top, float* d_logits, void* d_scratch, void* hip_stream) {
+    if (!d_act || !d_packed || !d_ids || !d_top || !d_scratch) return FASTCOT_EINVAL;
+    if (M <= 0 || d <= 0 || V <= 0 || d % 32 || V % 16) return FASTCOT_EINVAL;
+    hipError_t e = fc_lmhead_iso(d_act, d_packed, M, d, V, d_ids, d_top, d_logits, d_scratch, (hipStream_t)hip_stream);
+    return e == hipSuccess ? 0 : FASTCOT_EHIP;
+}

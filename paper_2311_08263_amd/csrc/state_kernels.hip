@@ -1,0 +1,92 @@
+// Decoding-state kernels: all per-sequence state (committed length n, generated count g, the
+// Approximate Tokens Buffer, the window, done flags) lives in device memory so that a captured
+// step can be replayed without host arguments.
+#include "kernels.h"
+
+// Prefill chunk `chunk`: window slot j of sequence b carries prompt token chunk*W + j if that
+// token is one of the first len-1 prompt tokens, else a pad (its K/V is never committed).
+__global__ void k_prefill_window(int32_t* st, StateMap sm, int B, int W, int S, int chunk) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B * W) return;
+    int b = i / W, j = i % W;
+    int len = st[sm.plen + b];
+    int p = chunk * W + j;
+    st[sm.win + i] = (p < len - 1) ? st[sm.prompt + (size_t)b * S + p] : 0;
+}
+hipError_t fc_prefill_window(int32_t* state, const StateMap& sm, int B, int W, int S, int chunk, hipStream_t st) {
+    k_prefill_window<<<(B * W + 255) / 256, 256, 0, st>>>(state, sm, B, W, S, chunk);
+    return hipGetLastError();
+}
+
+// After the forward of a prefill chunk: commit the K/V of the real prompt rows.  After the last
+// chunk, set up the first Jacobi window: slot 0 = last prompt token, slots 1.. = buffer[0..W-2].
+__global__ void k_prefill_advance(int32_t* st, StateMap sm, int B, int W, int S, int chunk, int last) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int len = st[sm.plen + b];
+    int n = (chunk + 1) * W;
+    if (n > len - 1) n = len - 1;
+    st[sm.n + b] = n;
+    if (last) {
+        st[sm.g + b] = 0; st[sm.done + b] = 0; st[sm.steps + b] = 0; st[sm.lastK + b] = 0; st[sm.olen + b] = 0;
+        int newest = st[sm.prompt + (size_t)b * S + len - 1];
+        st[sm.newest + b] = newest;
+        st[sm.win + b * W] = newest;
+        for (int j = 1; j < W; ++j) st[sm.win + b * W + j] = st[sm.buf + (size_t)b * S + j - 1];
+    }
+}
+hipError_t fc_prefill_advance(int32_t* state, const StateMap& sm, int B, int W, int S, int chunk, int last,
+                              hipStream_t st) {
+    k_prefill_advance<<<(B + 63) / 64, 64, 0, st>>>(state, sm, B, W, S, chunk, last);
+    return hipGetLastError();
+}
+
+// Verification (Eq. 5), acceptance, cache update and window shift (Sec. 4.3), stop conditions
+// (Sec. 4.4) for every sequence.  o[b][j] is the argmax of row j, i.e. the prediction for the
+// token after window slot j.  Approximate slot i is verified when o[i-1] == win[i]; slots are
+// checked in order and the first miss stops.  K verified slots => K+1 exact tokens o[0..K].
+// Committing their K/V is the bump of n: rows 0..K of this step wrote their K/V at positions
+// n..n+K already.  All W fresh outputs go back to the buffer; the window slides by K+1.
+__global__ void k_accept_commit(int32_t* st, StateMap sm, int B, int W, int S) {
+    __shared__ int not_done;
+    if (threadIdx.x == 0) not_done = 0;
+    __syncthreads();
+    const int max_new = st[sm.params + PARAM_MAX_NEW], eos = st[sm.params + PARAM_EOS];
+    const int max_steps = st[sm.params + PARAM_MAX_STEPS], buf_len = st[sm.params + PARAM_BUF_LEN];
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        if (st[sm.done + b]) { st[sm.lastK + b] = -1; continue; }
+        const int32_t* w = st + sm.win + b * W;
+        const int32_t* o = st + sm.o + b * W;
+        int32_t* buf = st + sm.buf + (size_t)b * S;
+        int32_t* out = st + sm.out + (size_t)b * S;
+        int n = st[sm.n + b], g = st[sm.g + b], steps = st[sm.steps + b];
+        int K = 0;
+        while (K < W - 1 && o[K] == w[K + 1]) ++K;
+        for (int j = 0; j < W; ++j) if (g + j < buf_len) buf[g + j] = o[j];
+        int stop = 0, emitted = 0;
+        for (int j = 0; j <= K && !stop; ++j) {
+            if (g + j < max_new && g + j < S) { out[g + j] = o[j]; emitted = g + j + 1; }
+            if (eos >= 0 && o[j] == eos) stop = 1;
+        }
+        if (emitted > st[sm.olen + b]) st[sm.olen + b] = emitted;
+        int newest = o[K];
+        n += K + 1; g += K + 1; ++steps;
+        if (g >= max_new || (max_steps > 0 && steps >= max_steps)) stop = 1;
+        if (n + W > S || g + 2 * W - 1 > buf_len) {       // no room for another window: stop, flag it
+            if (!stop) st[sm.flags + FLAG_ERROR] = 1;
+            stop = 1;
+        }
+        st[sm.n + b] = n; st[sm.g + b] = g; st[sm.steps + b] = steps; st[sm.lastK + b] = K;
+        st[sm.newest + b] = newest; st[sm.done + b] = stop;
+        int32_t* wn = st + sm.win + b * W;
+        wn[0] = newest;
+        for (int j = 1; j < W; ++j) { int p = g + j - 1; wn[j] = p < buf_len ? buf[p] : 0; }
+        if (!stop) atomicAdd(&not_done, 1);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) st[sm.flags + FLAG_ALL_DONE] = (not_done == 0);
+}
+hipError_t fc_accept_commit(int32_t* state, const StateMap& sm, int B, int W, int S, hipStream_t st) {
+    k_accept_commit<<<1, 64, 0, st>>>(state, sm, B, W, S);
+    return hipGetLastError();
+}

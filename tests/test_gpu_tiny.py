@@ -1,0 +1,147 @@
+"""GPU parity on the small fp32 configuration (2 layers, d 256, 4 heads x 64, FFN 688, vocab
+1024; batch 1, prompt 32, window 8, 64 new tokens) and its edge cases.  Bars: token ids, step
+counts and per-step verified counts bit-exact; |dlogit| <= 1e-4."""
+import numpy as np
+import pytest
+
+import oracle
+import synthgen
+from gpu_util import follow_steps, margins, say
+
+pytestmark = pytest.mark.gpu
+TINY = synthgen.SHAPES["tiny"]
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def env():
+    import paper_2311_08263_amd as fc
+    om = oracle.model_from_synth(TINY)
+    return fc, om
+
+
+def make_ctx(fc, B, S, W):
+    cfg = fc.Config.from_shape(TINY, B, S, W)
+    packed = fc.load_synth_weights(cfg, TINY)
+    return fc.Context(cfg, packed)
+
+
+def test_generate_matches_oracle_free_run(env):
+    fc, om = env
+    P, W, N = 32, 8, 64
+    prompt = synthgen.prompts(1, P, TINY.vocab)
+    buf = synthgen.buffer_init(1, N + 2 * W, TINY.vocab)
+    ref = om.jacobi_generate(prompt[0], buf[0], W, N)
+    say("tiny generate B1 P32 W8 N64")
+    ctx = make_ctx(fc, 1, P + N + 2 * W, W)
+    ctx.prefill(prompt, [P], buf)
+    out = ctx.generate(N)
+    assert out["len"][0] == N
+    assert (out["ids"][0] == ref["ids"]).all()
+    assert out["steps"][0] == ref["steps"]
+    assert (out["tail"][0] == ref["tail"]).all()
+    assert (out["ids"][0] == om.greedy_ar(prompt[0], N)).all()
+
+
+def test_stepwise_logits_and_counts(env):
+    fc, om = env
+    P, W, N = 32, 8, 64
+    prompt = synthgen.prompts(1, P, TINY.vocab)
+    buf = synthgen.buffer_init(1, N + 2 * W, TINY.vocab)
+    ref = om.jacobi_generate(prompt[0], buf[0], W, N)
+    ctx = make_ctx(fc, 1, P + N + 2 * W, W)
+    ctx.prefill(prompt, [P], buf)
+    r = follow_steps(ctx, om, prompt, [P], ref["steps"], TOL, margin=4 * TOL)
+    assert r["K"] == ref["K"].tolist()          # free-running trajectories coincide step by step
+    assert r["max_err"] < TOL
+    print("tiny max |dlogit|", r["max_err"])
+
+
+@pytest.mark.parametrize("W", [1, 2, 5, 16])
+def test_windows(env, W):
+    fc, om = env
+    P, N = 20, 40
+    prompt = synthgen.prompts(1, P, TINY.vocab, seed=12)
+    buf = synthgen.buffer_init(1, N + 2 * W, TINY.vocab, seed=3)
+    ref = om.jacobi_generate(prompt[0], buf[0], W, N)
+    say(f"tiny window W={W}")
+    ctx = make_ctx(fc, 1, P + N + 2 * W, W)
+    ctx.prefill(prompt, [P], buf)
+    out = ctx.generate(N)
+    assert (out["ids"][0] == ref["ids"]).all() and out["steps"][0] == ref["steps"]
+    if W == 1:
+        assert out["steps"][0] == N
+
+
+def test_ragged_batch_eos_and_cap(env):
+    """Sequences of different prompt lengths advance independently; EOS among the accepted tokens
+    stops a sequence (approximate EOS does not); max_steps caps the iterations."""
+    fc, om = env
+    W, N, B = 4, 24, 3
+    lens = [9, 1, 17]
+    prompts = synthgen.prompts(B, 17, TINY.vocab, seed=5)
+    buf = synthgen.buffer_init(B, N + 2 * W, TINY.vocab, seed=6)
+    refs = [om.jacobi_generate(prompts[b, :lens[b]], buf[b], W, N) for b in range(B)]
+    say("tiny ragged batch")
+    ctx = make_ctx(fc, B, 17 + N + 2 * W, W)
+    ctx.prefill(prompts, lens, buf)
+    out = ctx.generate(N)
+    for b in range(B):
+        assert (out["ids"][b] == refs[b]["ids"]).all() and out["steps"][b] == refs[b]["steps"], b
+        assert (out["tail"][b] == refs[b]["tail"]).all()
+    # EOS: take a token of sequence 0's stream as EOS
+    eos = int(refs[0]["ids"][7])
+    refs = [om.jacobi_generate(prompts[b, :lens[b]], buf[b], W, N, eos=eos) for b in range(B)]
+    ctx.prefill(prompts, lens, buf)
+    out = ctx.generate(N, eos_id=eos)
+    for b in range(B):
+        L = len(refs[b]["ids"])
+        assert out["len"][b] == L and (out["ids"][b, :L] == refs[b]["ids"]).all() and out["steps"][b] == refs[b]["steps"]
+    # iteration cap
+    refs = [om.jacobi_generate(prompts[b, :lens[b]], buf[b], W, N, max_steps=3) for b in range(B)]
+    ctx.prefill(prompts, lens, buf)
+    out = ctx.generate(N, max_steps=3)
+    for b in range(B):
+        L = len(refs[b]["ids"])
+        assert out["steps"][b] == 3 and out["len"][b] == L and (out["ids"][b, :L] == refs[b]["ids"]).all()
+
+
+def test_graph_and_eager_agree_and_are_deterministic(env):
+    fc, om = env
+    P, W, N = 16, 8, 32
+    prompt = synthgen.prompts(1, P, TINY.vocab, seed=8)
+    buf = synthgen.buffer_init(1, N + 2 * W, TINY.vocab, seed=9)
+    ctx = make_ctx(fc, 1, P + N + 2 * W, W)
+    outs = []
+    for graph in (1, 0, 1):
+        ctx.set_option(2, graph)
+        ctx.prefill(prompt, [P], buf)
+        outs.append(ctx.generate(N))
+    for o in outs[1:]:
+        assert (o["ids"] == outs[0]["ids"]).all() and (o["steps"] == outs[0]["steps"]).all()
+
+
+def test_capacity_and_state_errors(env):
+    fc, om = env
+    W = 4
+    ctx = make_ctx(fc, 2, 64, W)
+    prompt = synthgen.prompts(1, 8, TINY.vocab)
+    buf = synthgen.buffer_init(1, 40, TINY.vocab)
+    with pytest.raises(fc.FastcotError) as e:
+        ctx.step()
+    assert e.value.rc == -2
+    with pytest.raises(fc.FastcotError) as e:
+        ctx.prefill(synthgen.prompts(3, 8, TINY.vocab), [8, 8, 8], synthgen.buffer_init(3, 40, TINY.vocab))
+    assert e.value.rc == -3
+    with pytest.raises(fc.FastcotError) as e:
+        ctx.prefill(synthgen.prompts(1, 60, TINY.vocab), [60], buf)
+    assert e.value.rc == -3
+    ctx.prefill(prompt, [8], buf)
+    with pytest.raises(fc.FastcotError) as e:
+        ctx.generate(60)        # buffer (40) shorter than 60 + 2W
+    assert e.value.rc == -3
+    out = ctx.generate(16)
+    assert out["len"][0] == 16
+    with pytest.raises(fc.FastcotError) as e:
+        ctx.generate(16)
+    assert e.value.rc == -2
