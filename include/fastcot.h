@@ -41,8 +41,9 @@ typedef enum {
 
 enum { FASTCOT_F32 = 0, FASTCOT_BF16 = 1 };
 
-/* Llama-style decoder shape plus capacities.  dtype is the storage type of weights and KV
- * cache; activations, accumulation, softmax and norm statistics are always fp32. */
+/* Llama-style decoder shape plus capacities.  dtype is the storage type of the weights; the KV
+ * cache is fp32 for fp32 models and bf16 planes for bf16 models (see FASTCOT_OPT_KV_PLANES);
+ * activations, accumulation, softmax and norm statistics are always fp32. */
 typedef struct fastcot_config {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
     float rms_eps, rope_base;
@@ -124,8 +125,11 @@ int fastcot_debug_logits(fastcot_ctx* ctx, float* d_logits);
  * output kernels (always used for fp32 models); 0 (default) uses the MFMA kernels for bf16.
  * FASTCOT_OPT_GRAPH = 1 (default) replays a captured HIP graph per step; 0 launches kernels
  * one by one.  A context on the default (NULL) stream always launches one by one, since that
- * stream cannot be captured. */
-enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2 };
+ * stream cannot be captured.
+ * FASTCOT_OPT_KV_PLANES (bf16 models): 2 (default) keeps every cached K/V value as a bf16 hi +
+ * bf16 lo pair (4 bytes, ~16 mantissa bits); 1 keeps the hi plane only (2 bytes, plain bf16).
+ * Changing it invalidates the sequences: call fastcot_prefill again. */
+enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLANES = 3 };
 int fastcot_set_option(fastcot_ctx* ctx, int32_t option, int32_t value);
 
 /* Wall time of the steps of the last fastcot_generate, measured with HIP events on the
@@ -143,7 +147,7 @@ const char* fastcot_kernel_name(int32_t kind);
 /* Kernel-isolation entry points (the same kernels the step uses, on raw device pointers).
  *
  * Window-causal attention (Eq. 2 conditioning as a mask): q device fp32 [W][H][Dh] (already
- * rotated); k_cache / vt_cache in the library's cache layout for one sequence, K as
+ * rotated); k_cache / vt_cache in the library's single-plane cache layout for one sequence, K as
  * [Hkv][max_seq][Dh] and V transposed as [Hkv][Dh][max_seq], elements of `dtype`, positions
  * 0..n+W-1 filled; row j attends positions 0..n+j.  out device fp32 [W][H*Dh].  scratch: device,
  * fastcot_attn_scratch_bytes() bytes, zeroed once by the caller before first use.

@@ -103,14 +103,14 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
     }
     KernelDims k;
     k.L = c->n_layers; k.d = d; k.H = c->n_heads; k.Hkv = c->n_kv_heads; k.Dh = c->head_dim; k.F = F;
-    k.V = c->vocab; k.B = c->max_batch; k.S = c->max_seq; k.W = c->window; k.M = k.B * k.W;
-    k.qkvN = qd + 2 * kvd; k.eps = c->rms_eps; k.esz = (int)esz;
+    k.V = c->vocab; k.B = c->max_batch; k.S = (c->max_seq + 31) & ~31; k.W = c->window; k.M = k.B * k.W;
+    k.qkvN = qd + 2 * kvd; k.eps = c->rms_eps; k.esz = (int)esz; k.kvp = c->dtype == FASTCOT_BF16 ? 2 : 1;
     if (kd) *kd = k;
     if (wm) {
         size_t cur = 0;
         auto take = [&](size_t bytes) { size_t o = cur; cur = FC_ALIGN(cur + bytes); return o; };
         const size_t M = (size_t)k.M;
-        size_t cache = (size_t)k.L * k.B * k.Hkv * k.S * k.Dh * esz;
+        size_t cache = (size_t)k.L * k.B * k.Hkv * k.kvp * k.S * k.Dh * esz;
         wm->kc = take(cache); wm->vc = take(cache);
         wm->rope_cos = take((size_t)k.S * (k.Dh / 2) * 4); wm->rope_sin = take((size_t)k.S * (k.Dh / 2) * 4);
         wm->x = take(M * d * 4); wm->nx = take(M * d * 4); wm->qkv = take(M * k.qkvN * 4);
@@ -119,7 +119,7 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
         fc_fast_scratch_sizes(k, &wm->gemm_part_bytes, &wm->attn_part_bytes);
         wm->gemm_part = take(wm->gemm_part_bytes); wm->gemm_cnt = take(FC_MAX_COUNTERS * 4);
         wm->attn_part = take(wm->attn_part_bytes); wm->attn_cnt = take(FC_MAX_COUNTERS * 4);
-        wm->amax_part = take(M * (size_t)((k.V + 127) / 128) * 8);
+        wm->amax_part = take((M > 32 ? M : 32) * (size_t)((k.V + 127) / 128) * 8);
         StateMap s; int w = 0;
         auto ti = [&](int words) { int o = w; w += (words + 3) & ~3; return o; };
         s.n = ti(k.B); s.g = ti(k.B); s.done = ti(k.B); s.steps = ti(k.B); s.newest = ti(k.B); s.lastK = ti(k.B);
@@ -241,6 +241,10 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
         if (!value && c->cfg.dtype == FASTCOT_F32) return fail(c, FASTCOT_EINVAL, "fp32 models only have the plain kernels%s");
         c->opt_plain = value != 0;
     } else if (option == FASTCOT_OPT_GRAPH) c->opt_graph = value != 0;
+    else if (option == FASTCOT_OPT_KV_PLANES) {
+        if (c->cfg.dtype != FASTCOT_BF16 || (value != 1 && value != 2)) return fail(c, FASTCOT_EINVAL, "KV planes: 1 or 2, bf16 models only%s");
+        c->kd.kvp = value; c->prefilled = 0;      // the cache layout changes: a new prefill is required
+    }
     else return fail(c, FASTCOT_EINVAL, "unknown option%s");
     drop_graph(c);
     return 0;
@@ -303,7 +307,7 @@ static int forward_plain(fastcot_ctx* c, int lmhead) {
 }
 
 static int forward(fastcot_ctx* c, int lmhead) {
-    if (c->opt_plain) return forward_plain(c, lmhead);
+    if (c->opt_plain || !fc_fast_supported(c->kd, c->Bact * c->kd.W)) return forward_plain(c, lmhead);
     FastArgs a;
     a.kd = c->kd; a.kd.M = c->Bact * c->kd.W; a.Bact = c->Bact;
     a.mm = &c->mm; a.wm = &c->wm; a.weights = c->weights; a.ws = c->ws; a.dbg_logits = c->dbg_logits;
@@ -348,12 +352,12 @@ extern "C" int fastcot_prefill(fastcot_ctx* c, int32_t B, const int32_t* prompts
     if (B < 1) return fail(c, FASTCOT_EINVAL, "batch must be >= 1%s");
     const KernelDims& kd = c->kd;
     if (B > kd.B) return fail(c, FASTCOT_ECAPACITY, "batch %s%ld exceeds max_batch %ld", "", B, kd.B);
-    if (buf_len > kd.S) return fail(c, FASTCOT_ECAPACITY, "buf_len %s%ld exceeds max_seq %ld", "", buf_len, kd.S);
+    if (buf_len > c->cfg.max_seq) return fail(c, FASTCOT_ECAPACITY, "buf_len %s%ld exceeds max_seq %ld", "", buf_len, c->cfg.max_seq);
     if (buf_len < 2 * kd.W) return fail(c, FASTCOT_EINVAL, "buf_len %s%ld must be at least 2*window = %ld", "", buf_len, 2 * kd.W);
     int maxlen = 0;
     for (int b = 0; b < B; ++b) {
         if (lens[b] < 1 || lens[b] > max_P) return fail(c, FASTCOT_EINVAL, "prompt length out of range%s");
-        if (lens[b] - 1 + 2 * kd.W > kd.S) return fail(c, FASTCOT_ECAPACITY, "prompt of %s%ld tokens does not fit max_seq %ld", "", lens[b], kd.S);
+        if (lens[b] - 1 + 2 * kd.W > c->cfg.max_seq) return fail(c, FASTCOT_ECAPACITY, "prompt of %s%ld tokens does not fit max_seq %ld", "", lens[b], c->cfg.max_seq);
         for (int i = 0; i < lens[b]; ++i)
             if (prompts[(size_t)b * max_P + i] < 0 || prompts[(size_t)b * max_P + i] >= kd.V) return fail(c, FASTCOT_EINVAL, "prompt token out of vocabulary%s");
         if (lens[b] > maxlen) maxlen = lens[b];
@@ -429,7 +433,7 @@ extern "C" int fastcot_generate(fastcot_ctx* c, int32_t max_new, int32_t max_ste
     HIPCHK(c, hipMemcpy(hg.data(), stp + sm.g, (size_t)B * 4, hipMemcpyDeviceToHost));
     for (int b = 0; b < B; ++b) {
         if (hg[b] != 0) return fail(c, FASTCOT_ESTATE, "fastcot_generate after fastcot_jacobi_step is not supported%s");
-        if (hn[b] + max_new + 2 * W > kd.S) return fail(c, FASTCOT_ECAPACITY, "prompt + max_new_tokens + 2*window exceeds max_seq%s");
+        if (hn[b] + max_new + 2 * W > c->cfg.max_seq) return fail(c, FASTCOT_ECAPACITY, "prompt + max_new_tokens + 2*window exceeds max_seq%s");
     }
     int32_t params[8] = {max_new, eos_id < 0 ? -1 : eos_id, max_steps > 0 ? max_steps : 0, c->buf_len, B, 0, 0, 0};
     HIPCHK(c, hipMemcpy(stp + sm.params, params, sizeof(params), hipMemcpyHostToDevice));

@@ -1,0 +1,19 @@
+// Argument block and launcher of the matrix-core window-causal attention (see attn16.hip).
+#pragma once
+#include "fast.h"
+
+struct AttnArgs {
+    const float* q;        // rotated queries fp32, row (b*W + j), head h at column h*128
+    int32_t ldq;
+    const bf16_t* kc;      // K cache [L][B][Hkv][planes][S][128]: bf16 hi plane, optional bf16 lo plane
+    const bf16_t* vc;      // V cache, transposed [L][B][Hkv][planes][128][S]
+    int32_t layer, B, H, Hkv, S, W, kvp;
+    const int32_t* n_state;   // committed length per sequence
+    float* out;            // [rows][ldo], head h at column h*128
+    int32_t ldo;
+    float* part;           // split partials
+    int32_t* cnt;          // one arrival counter per (sequence, head), zero between launches
+};
+
+size_t fc_attn16_part_bytes(int BH, int nsplit, int W);
+hipError_t fc_attn16(const AttnArgs& a, int Bact, int nsplit, hipStream_t st);

@@ -1,0 +1,251 @@
+// Window-causal attention on matrix cores (bf16 KV cache, head_dim 128).
+//
+// The queries of a step are the W window rows of a sequence; the keys are the committed cache
+// positions 0..n-1 plus the window positions n..n+W-1, row j seeing positions <= n+j -- the causal
+// mask that lets one forward do lossless and Jacobi decoding together (Sec. 4.3, Eq. 2/4).
+//
+// One workgroup (4 waves) per (sequence, query head, key split); waves take 32-key blocks round
+// robin.  Per block the wave computes S^T = K . Q^T with v_mfma_f32_16x16x32_bf16 (K rows as the
+// A operand, straight from the cache with 16-byte loads; Q as the B operand, bf16 hi + lo), a
+// running-max softmax in fp32, and O^T += V^T . P^T with V^T rows as the A operand (the V cache is
+// stored transposed, [Dh][positions], so these are 16-byte loads too) and P^T, which is exactly the
+// register layout the score tiles already have, as the B operand.  The two 16-key score tiles of a
+// block interleave keys (tile t row r <-> key 8*(r/4) + 4*t + r%4) so that a lane ends with 8
+// consecutive keys.  Waves are merged through LDS, key splits through a scratch buffer by the last
+// workgroup to arrive, always in index order, so results do not depend on timing.
+#include "attn16.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
+union Frag { u32x4_t u; bf16x8_t v; };
+
+__device__ inline uint32_t rne16(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ inline float up16(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ inline void split8(const float* v, Frag& hi, Frag& lo) {
+    uint32_t h[8], l[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { h[e] = rne16(v[e]); l[e] = rne16(v[e] - up16(h[e])); }
+    hi.u = (u32x4_t){h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+    lo.u = (u32x4_t){l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+}
+
+#define NEG_BIG (-1.0e30f)
+#define PART_FLOATS (8 * 64 * 4 + 128)   // per (bh, split, qt): O^T tiles, then m[64], l[64] per lane
+
+template <int QT, int KVP>
+__global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
+    extern __shared__ float lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int lm = lane & 15, g = lane >> 4;
+    const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H, kvh = h / (a.H / a.Hkv);
+    const int sp = blockIdx.y, nsp = gridDim.y;
+    const int n = a.n_state[b];
+    int T = n + a.W;
+    if (T > a.S) T = a.S;                                    // capacity guard (the host checks first)
+    const int NB = (T + 31) >> 5;
+    const int blk0 = (int)(((unsigned)sp * (unsigned)NB) / (unsigned)nsp);
+    const int blk1 = (int)(((unsigned)(sp + 1) * (unsigned)NB) / (unsigned)nsp);
+    const size_t plane = (size_t)a.S * 128;
+    const bf16_t* kbase = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + kvh) * KVP) * plane;
+    const bf16_t* vbase = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kvh) * KVP) * plane;
+
+    // Q as B operand: lane (row lm, dh 32*g + 8*s + e), hi and lo
+    Frag qh[QT][4], ql[QT][4];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        int j = qt * 16 + lm;
+        if (j >= a.W) j = a.W - 1;
+        const float* qr = a.q + (size_t)(b * a.W + j) * a.ldq + h * 128 + 32 * g;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            float4 x0 = *(const float4*)(qr + 8 * s), x1 = *(const float4*)(qr + 8 * s + 4);
+            float v[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+            split8(v, qh[qt][s], ql[qt][s]);
+        }
+    }
+
+    f32x4_t acc[QT][8];
+    float mrun[QT], lrun[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        mrun[qt] = NEG_BIG; lrun[qt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) acc[qt][dt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    }
+    const float scale = 0.08838834764831845f;   // 1/sqrt(128)
+
+    for (int blk = blk0 + wv; blk < blk1; blk += 4) {
+        const int kb = blk << 5;
+        // K tiles (A operand): tile t row r=lm <-> key kb + 8*(lm/4) + 4*t + lm%4 ; dh 32*g + 8*s..
+        Frag kf[KVP][2][4], vf[KVP][8];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            int key = kb + 8 * (lm >> 2) + 4 * t + (lm & 3);
+            if (key > a.S - 1) key = a.S - 1;
+#pragma unroll
+            for (int pl = 0; pl < KVP; ++pl) {
+                const u32x4_t* kp = (const u32x4_t*)(kbase + pl * plane + (size_t)key * 128 + 32 * g);
+#pragma unroll
+                for (int s = 0; s < 4; ++s) kf[pl][t][s].u = kp[s];
+            }
+        }
+        // V^T tiles (A operand): row 16*dt + lm, keys kb + 8*g .. +7
+        {
+            int k8 = kb + 8 * g;
+            if (k8 > a.S - 8) k8 = a.S - 8;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+                for (int pl = 0; pl < KVP; ++pl)
+                    vf[pl][dt].u = *(const u32x4_t*)(vbase + pl * plane + (size_t)(16 * dt + lm) * a.S + k8);
+        }
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            f32x4_t sc[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                sc[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][t][s].v, qh[qt][s].v, sc[t], 0, 0, 0);
+                    sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][t][s].v, ql[qt][s].v, sc[t], 0, 0, 0);
+                    if (KVP == 2)   // lo x lo is below fp32 resolution and is dropped
+                        sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[KVP - 1][t][s].v, qh[qt][s].v, sc[t], 0, 0, 0);
+                }
+            }
+            // lane: row j = qt*16 + lm, keys kb + 8*g + e  (e = 4*t + r)
+            const int j = qt * 16 + lm;
+            const int lastvis = n + (j < a.W ? j : a.W - 1);
+            float p[8];
+            float bm = NEG_BIG;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int key = kb + 8 * g + e;
+                const bool vis = key <= lastvis && key < T;
+                p[e] = vis ? sc[e >> 2][e & 3] * scale : NEG_BIG;
+                bm = fmaxf(bm, p[e]);
+            }
+            bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
+            bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+            const float mnew = fmaxf(mrun[qt], bm);
+            const float alpha = expf(mrun[qt] - mnew);
+            float ps = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int key = kb + 8 * g + e;
+                const bool vis = key <= lastvis && key < T;
+                p[e] = vis ? expf(p[e] - mnew) : 0.f;
+                ps += p[e];
+            }
+            mrun[qt] = mnew;
+            lrun[qt] = lrun[qt] * alpha + ps;
+            Frag ph, pl;
+            split8(p, ph, pl);
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                acc[qt][dt] *= alpha;
+                acc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[0][dt].v, ph.v, acc[qt][dt], 0, 0, 0);
+                acc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[0][dt].v, pl.v, acc[qt][dt], 0, 0, 0);
+                if (KVP == 2)
+                    acc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[KVP - 1][dt].v, ph.v, acc[qt][dt], 0, 0, 0);
+            }
+        }
+    }
+    // row sums over the 4 lanes of a row
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        lrun[qt] += __shfl_xor(lrun[qt], 16, 64);
+        lrun[qt] += __shfl_xor(lrun[qt], 32, 64);
+    }
+
+    // merge the 4 waves: waves 1..3 publish to LDS, wave 0 folds them in order
+    if (wv > 0) {
+        float* dst = lds + (size_t)(wv - 1) * QT * PART_FLOATS;
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) *(f32x4_t*)(dst + qt * PART_FLOATS + (dt * 64 + lane) * 4) = acc[qt][dt];
+            dst[qt * PART_FLOATS + 2048 + lane] = mrun[qt];
+            dst[qt * PART_FLOATS + 2112 + lane] = lrun[qt];
+        }
+    }
+    __syncthreads();
+    if (wv > 0) return;
+    auto fold = [&](const float* src, bool global) {
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            const float* s = src + qt * PART_FLOATS;
+            const float mo = s[2048 + lane], lo = s[2112 + lane];
+            const float mnew = fmaxf(mrun[qt], mo);
+            const float wa = expf(mrun[qt] - mnew), wb = expf(mo - mnew);
+            lrun[qt] = lrun[qt] * wa + lo * wb;
+            mrun[qt] = mnew;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                f32x4_t o = *(const f32x4_t*)(s + (dt * 64 + lane) * 4);
+                acc[qt][dt] = acc[qt][dt] * wa + o * wb;
+            }
+        }
+    };
+    for (int w2 = 1; w2 < 4; ++w2) fold(lds + (size_t)(w2 - 1) * QT * PART_FLOATS, false);
+
+    if (nsp > 1) {
+        float* mine = a.part + ((size_t)bh * nsp + sp) * QT * PART_FLOATS;
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) *(f32x4_t*)(mine + qt * PART_FLOATS + (dt * 64 + lane) * 4) = acc[qt][dt];
+            mine[qt * PART_FLOATS + 2048 + lane] = mrun[qt];
+            mine[qt * PART_FLOATS + 2112 + lane] = lrun[qt];
+        }
+        __threadfence();
+        int old = 0;
+        if (lane == 0) old = atomicAdd(a.cnt + bh, 1);
+        old = __shfl(old, 0, 64);
+        if (old != nsp - 1) return;
+        __threadfence();
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            mrun[qt] = NEG_BIG; lrun[qt] = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) acc[qt][dt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+        }
+        for (int s2 = 0; s2 < nsp; ++s2) fold(a.part + ((size_t)bh * nsp + s2) * QT * PART_FLOATS, true);
+        if (lane == 0) a.cnt[bh] = 0;
+    }
+    // out[row][h*128 + 16*dt + 4*g + r] = O / l
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const int j = qt * 16 + lm;
+        if (j < a.W) {
+            const float inv = 1.0f / lrun[qt];
+            float* o = a.out + (size_t)(b * a.W + j) * a.ldo + h * 128 + 4 * g;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) *(f32x4_t*)(o + 16 * dt) = acc[qt][dt] * inv;
+        }
+    }
+}
+
+size_t fc_attn16_part_bytes(int BH, int nsplit, int W) {
+    const int QT = W > 16 ? 2 : 1;
+    return (size_t)BH * nsplit * QT * PART_FLOATS * 4;
+}
+
+hipError_t fc_attn16(const AttnArgs& a, int Bact, int nsplit, hipStream_t st) {
+    if (a.W < 1 || a.W > 32 || nsplit < 1 || nsplit > FC_MAX_ATTN_SPLITS || Bact * a.H > FC_MAX_COUNTERS || a.S < 32)
+        return hipErrorInvalidValue;
+    dim3 grid(Bact * a.H, nsplit);
+    const size_t l1 = (size_t)3 * PART_FLOATS * 4, l2 = 2 * l1;
+    if (a.kvp == 2) {
+        if (a.W > 16) k_attn16<2, 2><<<grid, 256, l2, st>>>(a);
+        else k_attn16<1, 2><<<grid, 256, l1, st>>>(a);
+    } else if (a.kvp == 1) {
+        if (a.W > 16) k_attn16<2, 1><<<grid, 256, l2, st>>>(a);
+        else k_attn16<1, 1><<<grid, 256, l1, st>>>(a);
+    } else return hipErrorInvalidValue;
+    return hipGetLastError();
+}

@@ -59,7 +59,7 @@ enum { FLAG_ALL_DONE = 0, FLAG_ERROR = 1 };
 enum { PARAM_MAX_NEW = 0, PARAM_EOS = 1, PARAM_MAX_STEPS = 2, PARAM_BUF_LEN = 3, PARAM_B = 4 };
 
 struct WorkspaceMap {
-    size_t kc, vc;              // KV cache: K [L][B][Hkv][S][Dh], V transposed [L][B][Hkv][Dh][S]
+    size_t kc, vc;              // KV cache: K [L][B][Hkv][planes][S][Dh], V transposed [L][B][Hkv][planes][Dh][S]
     size_t rope_cos, rope_sin;  // fp32 [S][Dh/2]
     size_t x, nx, qkv, att, gu, h, logits, topv;
     size_t gemm_part, gemm_cnt, attn_part, attn_cnt, amax_part;
@@ -74,7 +74,14 @@ struct KernelDims {    // model + capacities as the kernels need them
     int32_t qkvN;      // (H + 2 Hkv) * Dh
     float eps;
     int32_t esz;       // bytes per weight / cache element
+    int32_t kvp;       // planes per cached value: bf16 models keep hi (+ lo) bf16 planes, fp32 models one fp32 plane
 };
+
+// element offset of plane 0 of one (layer, sequence, kv head) block of the K or V cache; plane p
+// follows at p * S * Dh.  K block is [S][Dh], V block is transposed [Dh][S].
+__host__ __device__ inline size_t kv_block(const KernelDims& kd, int layer, int b, int kh) {
+    return ((((size_t)layer * kd.B + b) * kd.Hkv + kh) * (size_t)kd.kvp) * (size_t)kd.S * kd.Dh;
+}
 
 int fc_build_maps(const fastcot_config* cfg, ModelMap* mm, WorkspaceMap* wm, KernelDims* kd);
 

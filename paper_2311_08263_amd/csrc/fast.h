@@ -1,8 +1,10 @@
-// MFMA (matrix-core) forward path for bf16 models: launch plan and entry point.
+// MFMA (matrix-core) forward path for bf16 models: launch plan and entry points.
 #pragma once
 #include "common.h"
 
 #define FC_MAX_COUNTERS 8192
+#define FC_MAX_SK 64          // largest cross-workgroup split of K
+#define FC_MAX_ATTN_SPLITS 16 // largest split of the key range across workgroups
 
 struct GemmPlan {      // how one weight-streaming GEMM is cut into workgroups
     int32_t ncg;       // column groups of 8 n-tiles (128 columns)
@@ -13,7 +15,7 @@ struct FastPlan {
     int32_t attn_splits;
 };
 struct FastArgs {
-    KernelDims kd;
+    KernelDims kd;     // kd.M = rows of this pass
     int Bact, lmhead;
     const ModelMap* mm;
     const WorkspaceMap* wm;
@@ -26,6 +28,8 @@ struct FastArgs {
     hipError_t (*prof_mark)(void*, int);
 };
 
+// true when the MFMA path covers this shape (else the caller uses the plain kernels)
+bool fc_fast_supported(const KernelDims& kd, int rows);
 void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t* attn_part_bytes);
 void fc_fast_plan(const KernelDims& kd, FastPlan* plan);
 hipError_t fc_fast_forward(const FastArgs& a);

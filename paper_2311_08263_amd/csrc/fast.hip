@@ -1,22 +1,163 @@
+// MFMA forward path for bf16 models: per layer five launches (QKV+RoPE+cache write, attention,
+// O-proj+residual, gate/up+SwiGLU, down+residual), then the LM head with fused argmax.
 #include <string.h>
-#include "fast.h"
-void fc_fast_scratch_sizes(const KernelDims& kd, size_t* g, size_t* a) { *g = 256; *a = 256; }
-void fc_fast_plan(const KernelDims& kd, FastPlan* plan) { memset(plan, 0, sizeof(*plan)); }
-hipError_t fc_fast_forward(const FastArgs& a) { return hipErrorNotSupported; }
 #include "kernels.h"
-__global__ void k_set_i32_(int32_t* p, int32_t v) { if (threadIdx.x == 0) *p = v; }
-size_t fc_attn_iso_scratch_bytes(int W, int H, int Dh) { return 256; }
+#include "gemm16.h"
+#include "attn16.h"
+
+enum { KK_EMBED = 0, KK_QKV = 2, KK_ATTN = 4, KK_O = 5, KK_GU = 6, KK_DOWN = 8, KK_LM = 9, KK_ARGMAX = 10 };
+
+bool fc_fast_supported(const KernelDims& kd, int rows) {
+    return kd.esz == 2 && kd.Dh == 128 && rows >= 1 && rows <= 32 && kd.W <= 32 && kd.d % 256 == 0 && kd.F % 256 == 0 &&
+           (kd.H * kd.Dh) % 256 == 0 && kd.S % 32 == 0 && kd.V % 16 == 0;
+}
+
+// K slices: between 1 and 4 units of 256 inputs each; enough workgroups to cover the chip twice.
+static int choose_sk(int K, int ncg) {
+    const int NU = K / 256;
+    int lo = (NU + 3) / 4, hi = NU < FC_MAX_SK ? NU : FC_MAX_SK;
+    if (lo < 1) lo = 1;
+    int first = 0;
+    for (int sk = lo; sk <= hi; ++sk) {
+        if (ncg * sk < 512) continue;
+        if (!first) first = sk;
+        if (NU % sk == 0) return sk;
+        if (sk > 2 * first) break;
+    }
+    return first ? first : hi;
+}
+
+void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
+    memset(p, 0, sizeof(*p));
+    auto mk = [&](int K, int N) { GemmPlan g; g.ncg = (N / 16 + 7) / 8; g.sk = K % 256 == 0 ? choose_sk(K, g.ncg) : 1; return g; };
+    p->qkv = mk(kd.d, kd.qkvN);
+    p->o = mk(kd.H * kd.Dh, kd.d);
+    p->gu = mk(kd.d, 2 * kd.F);
+    p->down = mk(kd.F, kd.d);
+    p->lm = mk(kd.d, kd.V);
+    int nb = (kd.S + 31) / 32, sp = (nb + 5) / 6;
+    if (sp > FC_MAX_ATTN_SPLITS) sp = FC_MAX_ATTN_SPLITS;
+    while (sp > 1 && kd.B * kd.H * sp > 2048) --sp;
+    p->attn_splits = sp < 1 ? 1 : sp;
+}
+
+void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t* attn_part_bytes) {
+    // partial tiles: (column groups x slices) x 8 waves x 2 row tiles x 1 KB, sized for the widest matrix
+    int nmax = 2 * kd.F;
+    if (kd.qkvN > nmax) nmax = kd.qkvN;
+    if (kd.V > nmax) nmax = kd.V;
+    const size_t ncg = (size_t)(nmax / 16 + 7) / 8;
+    *gemm_part_bytes = ncg * FC_MAX_SK * (8 * 2 * 1024 + 2 * 16 * 4) + 4096;
+    *attn_part_bytes = fc_attn16_part_bytes(kd.B * kd.H, FC_MAX_ATTN_SPLITS, kd.W) + 4096;
+}
+
+#define FLAUNCH(kind, call)                                                          \
+    do {                                                                             \
+        hipError_t e_;                                                               \
+        if (a.prof && (e_ = a.prof_mark(a.prof, kind)) != hipSuccess) return e_;     \
+        if ((e_ = (call)) != hipSuccess) return e_;                                  \
+        if (a.prof && (e_ = a.prof_mark(a.prof, -1)) != hipSuccess) return e_;       \
+    } while (0)
+
+hipError_t fc_fast_forward(const FastArgs& a) {
+    const KernelDims& kd = a.kd;
+    const ModelMap& mm = *a.mm; const WorkspaceMap& wm = *a.wm;
+    const int M = kd.M, d = kd.d, qd = kd.H * kd.Dh;
+    char* ws = a.ws; const char* wt = a.weights;
+    int32_t* stp = (int32_t*)(ws + wm.state);
+    float* x = (float*)(ws + wm.x); float* q = (float*)(ws + wm.qkv); float* att = (float*)(ws + wm.att);
+    float* h = (float*)(ws + wm.h);
+    Gemm16Args g; memset(&g, 0, sizeof(g));
+    g.M = M; g.eps = kd.eps; g.part = (float*)(ws + wm.gemm_part);
+    g.cnt = (int32_t*)(ws + wm.gemm_cnt);
+    g.n_state = stp + wm.st.n; g.cosT = (const float*)(ws + wm.rope_cos); g.sinT = (const float*)(ws + wm.rope_sin);
+    g.kc = (bf16_t*)(ws + wm.kc); g.vc = (bf16_t*)(ws + wm.vc);
+    g.H = kd.H; g.Hkv = kd.Hkv; g.B = kd.B; g.S = kd.S; g.Wn = kd.W; g.kvp = kd.kvp;
+    g.amax_val = (float*)(ws + wm.amax_part);
+    AttnArgs at; memset(&at, 0, sizeof(at));
+    at.q = q; at.ldq = qd; at.kc = g.kc; at.vc = g.vc; at.B = kd.B; at.H = kd.H; at.Hkv = kd.Hkv; at.S = kd.S; at.W = kd.W; at.kvp = kd.kvp;
+    at.n_state = g.n_state; at.out = att; at.ldo = qd; at.part = (float*)(ws + wm.attn_part); at.cnt = (int32_t*)(ws + wm.attn_cnt);
+
+    auto gemm = [&](int epi, const GemmPlan& pl, const void* W, int K, int N, const float* X, int ldx, const float* gain,
+                    float* out, int ldo) {
+        g.W = (const bf16_t*)W; g.K = K; g.NT = N / 16; g.sk = pl.sk; g.X = X; g.ldx = ldx; g.gain = gain; g.out = out; g.ldo = ldo;
+        // partial row sums live right after the partial tiles of this launch
+        g.sspart = g.part + (size_t)pl.ncg * pl.sk * 8 * (M > 16 ? 2 : 1) * 256;
+        return fc_gemm16(epi, g, pl.ncg, a.st);
+    };
+
+    FLAUNCH(KK_EMBED, fc_embed(wt + mm.emb_off, FASTCOT_BF16, stp + wm.st.win, x, M, d, kd.V, a.st));
+    for (int l = 0; l < kd.L; ++l) {
+        const char* lb = wt + mm.layers_off + (size_t)l * mm.layer_stride;
+        g.layer = l; at.layer = l;
+        FLAUNCH(KK_QKV, gemm(EPI_QKV, a.plan->qkv, lb + mm.qkv.off, d, kd.qkvN, x, d, (const float*)(lb + mm.g1_off), q, qd));
+        FLAUNCH(KK_ATTN, fc_attn16(at, a.Bact, a.plan->attn_splits, a.st));
+        FLAUNCH(KK_O, gemm(EPI_RESID, a.plan->o, lb + mm.o.off, qd, d, att, qd, nullptr, x, d));
+        FLAUNCH(KK_GU, gemm(EPI_SWIGLU, a.plan->gu, lb + mm.gu.off, d, 2 * kd.F, x, d, (const float*)(lb + mm.g2_off), h, kd.F));
+        FLAUNCH(KK_DOWN, gemm(EPI_RESID, a.plan->down, lb + mm.down.off, kd.F, d, h, kd.F, nullptr, x, d));
+    }
+    if (a.lmhead) {
+        const int stride = M > 16 ? 32 : 16;
+        g.amax_idx = (int32_t*)(g.amax_val + (size_t)a.plan->lm.ncg * stride);
+        FLAUNCH(KK_LM, gemm(EPI_LMHEAD, a.plan->lm, wt + mm.lm.off, d, kd.V, x, d, (const float*)(wt + mm.gf_off), a.dbg_logits, kd.V));
+        FLAUNCH(KK_ARGMAX, fc_argmax_final(g.amax_val, g.amax_idx, a.plan->lm.ncg, stride, M, stp + wm.st.o,
+                                           (float*)(ws + wm.topv), a.st));
+    }
+    return hipSuccess;
+}
+
+// ------------------------------------------------------------------ isolation launchers
+__global__ void k_set_i32(int32_t* p, int32_t v) { if (threadIdx.x == 0) *p = v; }
+
+static int iso_attn_splits(int S) {
+    int nb = (S + 31) / 32, sp = (nb + 7) / 8;
+    return sp < 1 ? 1 : (sp > FC_MAX_ATTN_SPLITS ? FC_MAX_ATTN_SPLITS : sp);
+}
+// scratch: [0,256) the committed length; [256, 256+4*H) counters; then split partials
+size_t fc_attn_iso_scratch_bytes(int W, int H, int Dh) {
+    return 256 + (((size_t)H * 4 + 255) & ~(size_t)255) + fc_attn16_part_bytes(H, FC_MAX_ATTN_SPLITS, W);
+}
 hipError_t fc_attn_iso(const float* q, const void* kc, const void* vc, int n, int W, int H, int Hkv, int Dh, int S,
                        int dt, float* out, void* scratch, hipStream_t st) {
-    KernelDims kd{}; kd.L = 1; kd.H = H; kd.Hkv = Hkv; kd.Dh = Dh; kd.B = 1; kd.S = S; kd.W = W; kd.M = W;
-    k_set_i32_<<<1, 64, 0, st>>>((int32_t*)scratch, n);
-    return fc_attn_plain(q, H * Dh, kc, vc, dt, kd, 0, (const int32_t*)scratch, out, st);
+    char* sc = (char*)scratch;
+    k_set_i32<<<1, 64, 0, st>>>((int32_t*)sc, n);
+    if (dt != FASTCOT_BF16 || Dh != 128 || W > 32 || S % 32 || H > FC_MAX_COUNTERS) {
+        KernelDims kd{}; kd.L = 1; kd.H = H; kd.Hkv = Hkv; kd.Dh = Dh; kd.B = 1; kd.S = S; kd.W = W; kd.M = W; kd.kvp = 1;
+        return fc_attn_plain(q, H * Dh, kc, vc, dt, kd, 0, (const int32_t*)sc, out, st);
+    }
+    AttnArgs at; memset(&at, 0, sizeof(at));
+    at.q = q; at.ldq = H * 128; at.kc = (const bf16_t*)kc; at.vc = (const bf16_t*)vc; at.layer = 0; at.B = 1; at.H = H;
+    at.Hkv = Hkv; at.S = S; at.W = W; at.kvp = 1; at.n_state = (const int32_t*)sc; at.out = out; at.ldo = H * 128;
+    at.cnt = (int32_t*)(sc + 256);
+    at.part = (float*)(sc + 256 + (((size_t)H * 4 + 255) & ~(size_t)255));
+    return fc_attn16(at, 1, iso_attn_splits(n + W), st);
 }
-size_t fc_lmhead_iso_scratch_bytes(int M, int d, int V) { return (size_t)M * V * 4 + 256; }
+
+// scratch: counters [ncg], winners [ncg][32] value + index, partial tiles
+size_t fc_lmhead_iso_scratch_bytes(int M, int d, int V) {
+    const size_t ncg = (size_t)(V / 16 + 7) / 8;
+    return ((ncg * 4 + 255) & ~(size_t)255) + ncg * 32 * 8 + 256 + ncg * FC_MAX_SK * (8 * 2 * 1024 + 128) + (size_t)M * V * 4;
+}
 hipError_t fc_lmhead_iso(const float* act, const void* packed, int M, int d, int V, int32_t* ids, float* top,
                          float* logits, void* scratch, hipStream_t st) {
-    float* lg = logits ? logits : (float*)scratch;
-    hipError_t e = fc_gemm_plain(packed, FASTCOT_BF16, d, V, V, act, d, lg, V, M, 0, st);
+    const int ncg = (V / 16 + 7) / 8;
+    char* sc = (char*)scratch;
+    const size_t cnt_bytes = ((size_t)ncg * 4 + 255) & ~(size_t)255;
+    if (M > 32 || d % 256) {
+        float* lg = logits ? logits : (float*)(sc + cnt_bytes + (size_t)ncg * 32 * 8 + 256 + (size_t)ncg * FC_MAX_SK * (8 * 2 * 1024 + 128));
+        hipError_t e = fc_gemm_plain(packed, FASTCOT_BF16, d, V, V, act, d, lg, V, M, 0, st);
+        if (e != hipSuccess) return e;
+        return fc_argmax_plain(lg, M, V, ids, top, st);
+    }
+    Gemm16Args g; memset(&g, 0, sizeof(g));
+    const int stride = M > 16 ? 32 : 16, sk = choose_sk(d, ncg);
+    g.W = (const bf16_t*)packed; g.K = d; g.NT = V / 16; g.sk = sk; g.X = act; g.ldx = d; g.M = M; g.gain = nullptr;
+    g.cnt = (int32_t*)sc;
+    g.amax_val = (float*)(sc + cnt_bytes); g.amax_idx = (int32_t*)(g.amax_val + (size_t)ncg * stride);
+    g.part = (float*)(sc + cnt_bytes + (size_t)ncg * 32 * 8 + 256);
+    g.sspart = g.part + (size_t)ncg * sk * 8 * (M > 16 ? 2 : 1) * 256;
+    g.out = logits; g.ldo = V;
+    hipError_t e = fc_gemm16(EPI_LMHEAD, g, ncg, st);
     if (e != hipSuccess) return e;
-    return fc_argmax_plain(lg, M, V, ids, top, st);
+    return fc_argmax_final(g.amax_val, g.amax_idx, ncg, stride, M, ids, top, st);
 }

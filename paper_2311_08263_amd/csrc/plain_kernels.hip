@@ -9,9 +9,18 @@ template <int DT> __device__ inline float wat(const void* W, size_t i) {
     if (DT == FASTCOT_F32) return ((const float*)W)[i];
     return bf16_to_f32(((const bf16_t*)W)[i]);
 }
-template <int DT> __device__ inline void wstore(void* W, size_t i, float v) {
-    if (DT == FASTCOT_F32) ((float*)W)[i] = v;
-    else ((bf16_t*)W)[i] = f32_to_bf16(v);
+// cached value: fp32 models one fp32 plane; bf16 models a bf16 hi plane plus (kvp == 2) a bf16 lo plane
+template <int DT> __device__ inline void kvstore(void* C, size_t i, size_t plane, int kvp, float v) {
+    if (DT == FASTCOT_F32) { ((float*)C)[i] = v; return; }
+    bf16_t hi = f32_to_bf16(v);
+    ((bf16_t*)C)[i] = hi;
+    if (kvp == 2) ((bf16_t*)C)[i + plane] = f32_to_bf16(v - bf16_to_f32(hi));
+}
+template <int DT> __device__ inline float kvload(const void* C, size_t i, size_t plane, int kvp) {
+    if (DT == FASTCOT_F32) return ((const float*)C)[i];
+    float v = bf16_to_f32(((const bf16_t*)C)[i]);
+    if (kvp == 2) v += bf16_to_f32(((const bf16_t*)C)[i + plane]);
+    return v;
 }
 
 // ------------------------------------------------------------------ embedding gather
@@ -98,6 +107,7 @@ __global__ void k_rope_cache(float* qkv, KernelDims kd, int layer, const int32_t
     int pos = n_state[b] + j;
     if (pos >= kd.S) return;  // capacity guard: never write outside the cache
     int half = kd.Dh / 2;
+    const size_t plane = (size_t)kd.S * kd.Dh;
     float* row = qkv + (size_t)m * kd.qkvN;
     int nrot = (kd.H + kd.Hkv) * half;
     for (int i = threadIdx.x; i < nrot; i += blockDim.x) {
@@ -109,16 +119,16 @@ __global__ void k_rope_cache(float* qkv, KernelDims kd, int layer, const int32_t
         if (hh < kd.H) { v[e] = ra; v[e + half] = rb; }
         else {
             int kh = hh - kd.H;
-            size_t base = ((((size_t)layer * kd.B + b) * kd.Hkv + kh) * kd.S + pos) * kd.Dh;
-            wstore<DT>(kc, base + e, ra);
-            wstore<DT>(kc, base + e + half, rb);
+            size_t base = kv_block(kd, layer, b, kh) + (size_t)pos * kd.Dh;
+            kvstore<DT>(kc, base + e, plane, kd.kvp, ra);
+            kvstore<DT>(kc, base + e + half, plane, kd.kvp, rb);
         }
     }
     const float* vrow = row + (size_t)(kd.H + kd.Hkv) * kd.Dh;
     for (int i = threadIdx.x; i < kd.Hkv * kd.Dh; i += blockDim.x) {
         int kh = i / kd.Dh, e = i % kd.Dh;
-        size_t base = ((((size_t)layer * kd.B + b) * kd.Hkv + kh) * kd.Dh + e) * kd.S + pos;
-        wstore<DT>(vc, base, vrow[i]);
+        size_t base = kv_block(kd, layer, b, kh) + (size_t)e * kd.S + pos;
+        kvstore<DT>(vc, base, plane, kd.kvp, vrow[i]);
     }
 }
 hipError_t fc_rope_cache_plain(float* qkv, const KernelDims& kd, int layer, const int32_t* n_state,
@@ -140,12 +150,12 @@ __global__ void k_attn_plain(const float* q, int ldq, const void* kc, const void
     if (last >= kd.S) last = kd.S - 1;
     int kh = h / (kd.H / kd.Hkv);
     const float* qv = q + (size_t)m * ldq + (size_t)h * kd.Dh;
-    size_t kbase = (((size_t)layer * kd.B + b) * kd.Hkv + kh) * (size_t)kd.S * kd.Dh;
+    const size_t kbase = kv_block(kd, layer, b, kh), plane = (size_t)kd.S * kd.Dh;
     float scale = 1.0f / sqrtf((float)kd.Dh);
     float mx = -3.0e38f;
     for (int t = threadIdx.x; t <= last; t += blockDim.x) {
         float s = 0;
-        for (int i = 0; i < kd.Dh; ++i) s += qv[i] * wat<DT>(kc, kbase + (size_t)t * kd.Dh + i);
+        for (int i = 0; i < kd.Dh; ++i) s += qv[i] * kvload<DT>(kc, kbase + (size_t)t * kd.Dh + i, plane, kd.kvp);
         s *= scale;
         sc[t] = s;
         mx = fmaxf(mx, s);
@@ -163,7 +173,7 @@ __global__ void k_attn_plain(const float* q, int ldq, const void* kc, const void
     for (int i = threadIdx.x; i < kd.Dh; i += blockDim.x) {
         size_t vb = kbase + (size_t)i * kd.S;   // transposed V: [Dh][S]
         float acc = 0;
-        for (int t = 0; t <= last; ++t) acc += sc[t] * wat<DT>(vc, vb + t);
+        for (int t = 0; t <= last; ++t) acc += sc[t] * kvload<DT>(vc, vb + t, plane, kd.kvp);
         out[(size_t)m * kd.H * kd.Dh + (size_t)h * kd.Dh + i] = acc / den;
     }
 }

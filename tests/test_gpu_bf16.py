@@ -1,0 +1,140 @@
+"""GPU parity of the matrix-core (bf16) path against the oracle on small Llama-shaped models and
+on the kernel-isolation shapes (window-causal attention with 32 heads x 128, cache 2048, 16 window
+queries; LM-head argmax of a 16x4096 activation against 4096x32000 weights).
+
+Bars: |dlogit| <= 2e-2 (the bf16 bar; measured values are printed and are far smaller), argmax
+equal wherever the oracle's top-1/top-2 margin exceeds 0.05, and the integer path (verified count,
+accepted ids, committed length, next window) bit-exact given the GPU's own argmax."""
+import numpy as np
+import pytest
+
+import oracle
+import synthgen
+from gpu_util import follow_steps, margins, say
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+# head_dim 128 models small enough for the oracle to follow in seconds; init std raised so that
+# logits are O(1) and attention is far from uniform
+SMALL = synthgen.ModelShape(3, 512, 4, 2, 128, 768, 2048, init_std=0.05)
+SMALL_MHA = synthgen.ModelShape(2, 256, 2, 2, 128, 512, 1024, init_std=0.06)
+
+
+@pytest.fixture(scope="module")
+def fc():
+    import paper_2311_08263_amd as m
+    return m
+
+
+def setup(fc, shape, B, S, W):
+    cfg = fc.Config.from_shape(shape, B, S, W)
+    packed = fc.load_synth_weights(cfg, shape)
+    return fc.Context(cfg, packed), oracle.model_from_synth(shape)
+
+
+@pytest.mark.parametrize("shape,B,W,P", [(SMALL, 1, 16, 45), (SMALL, 2, 16, 33), (SMALL_MHA, 1, 8, 20),
+                                         (SMALL, 1, 32, 70), (SMALL_MHA, 3, 5, 12)])
+def test_follow_mode_small_models(fc, shape, B, W, P):
+    say(f"bf16 follow shape d={shape.d_model} B={B} W={W} P={P}")
+    N = 48
+    S = ((P + N + 2 * W + 31) // 32) * 32
+    ctx, om = setup(fc, shape, B, S, W)
+    lens = [P - 3 * b for b in range(B)]
+    prompts = synthgen.prompts(B, P, shape.vocab, seed=21)
+    buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=22)
+    ctx.prefill(prompts, lens, buf)
+    r = follow_steps(ctx, om, prompts, lens, 6, TOL)
+    print(f"max |dlogit| {r['max_err']:.3e} over {r['rows']} rows ({r['low_margin_rows']} low-margin)")
+    assert r["max_err"] < 2e-3          # far inside the bf16 bar thanks to hi/lo activations
+
+
+def test_fast_path_matches_plain_path_and_oracle_stream(fc):
+    """Same model through the MFMA kernels and through the plain kernels: same tokens; and the
+    accepted stream is the oracle's greedy continuation up to the first low-margin row."""
+    shape, W, P, N = SMALL, 16, 40, 64
+    S = ((P + N + 2 * W + 31) // 32) * 32
+    ctx, om = setup(fc, shape, 1, S, W)
+    prompts = synthgen.prompts(1, P, shape.vocab, seed=31)
+    buf = synthgen.buffer_init(1, N + 2 * W, shape.vocab, seed=32)
+    outs = {}
+    for plain in (0, 1):
+        say(f"bf16 generate plain={plain}")
+        ctx.set_option(1, plain)
+        ctx.prefill(prompts, [P], buf)
+        outs[plain] = ctx.generate(N)
+    ref = om.jacobi_generate(prompts[0], buf[0], W, N)
+    # the oracle's own margins along its trajectory decide how far equality is required
+    ss = om.session(S)
+    ss.forward(prompts[0, :-1], 0, want_logits=False)
+    lg, _, _ = ss.forward(np.concatenate([prompts[0, -1:], ref["ids"][:-1]]), P - 1)
+    low = np.where(margins(lg) <= 0.05)[0]
+    upto = int(low[0]) if len(low) else N
+    for plain in (0, 1):
+        assert (outs[plain]["ids"][0, :upto] == ref["ids"][:upto]).all(), plain
+    if upto == N:
+        assert outs[0]["steps"][0] == ref["steps"] and (outs[0]["ids"][0] == outs[1]["ids"][0]).all()
+
+
+def test_deterministic_replay(fc):
+    shape, W, P, N = SMALL, 16, 30, 40
+    S = ((P + N + 2 * W + 31) // 32) * 32
+    ctx, _ = setup(fc, shape, 2, S, W)
+    prompts = synthgen.prompts(2, P, shape.vocab, seed=41)
+    buf = synthgen.buffer_init(2, N + 2 * W, shape.vocab, seed=42)
+    res = []
+    for graph in (1, 1, 0):
+        ctx.set_option(2, graph)
+        ctx.prefill(prompts, [P, P - 7], buf)
+        res.append(ctx.generate(N))
+    for r in res[1:]:
+        assert (r["ids"] == res[0]["ids"]).all() and (r["steps"] == res[0]["steps"]).all()
+
+
+@pytest.mark.parametrize("n,W,H,Hkv", [(2048, 16, 32, 32), (0, 16, 4, 4), (37, 5, 8, 2), (1000, 32, 8, 1), (2031, 16, 4, 4)])
+def test_attention_isolation(fc, n, W, H, Hkv):
+    """Kernel-isolation shape: K/V ~ N(0,1) in bf16, queries ~ N(0,1), causal inside the window."""
+    import torch
+    Dh, S = 128, 2080
+    say(f"attention isolation n={n} W={W} H={H} Hkv={Hkv}")
+    q = synthgen.normal_f32((W, H, Dh), 5, 1, 1.0, False)
+    kb = synthgen.normal_bf16((n + W, Hkv, Dh), 5, 2, 1.0)
+    vb = synthgen.normal_bf16((n + W, Hkv, Dh), 5, 3, 1.0)
+    ref = oracle.attention_window(q, synthgen.bf16_bits_to_f32(kb), synthgen.bf16_bits_to_f32(vb), n)
+    kc, vc = fc.kv_scatter(torch.from_numpy(kb.view(np.int16)).cuda().view(torch.bfloat16),
+                           torch.from_numpy(vb.view(np.int16)).cuda().view(torch.bfloat16), S)
+    out = fc.attn_window(torch.from_numpy(q).cuda(), kc, vc, n)
+    torch.cuda.synchronize()
+    err = np.abs(out.cpu().numpy() - ref).max()
+    print(f"attention max |d| {err:.3e}")
+    assert err < 1e-4
+    # garbage (finite) beyond the visible range must not matter: positions >= n+W are never read as visible
+    kc2, vc2 = kc.clone(), vc.clone()
+    kc2[:, n + W:, :] = 7.0
+    vc2[:, :, n + W:] = -9.0
+    out2 = fc.attn_window(torch.from_numpy(q).cuda(), kc2, vc2, n)
+    assert torch.equal(out, out2)
+
+
+@pytest.mark.parametrize("M,d,V", [(16, 4096, 32000), (5, 512, 2048), (32, 1024, 4096)])
+def test_lmhead_argmax_isolation(fc, M, d, V):
+    import torch
+    say(f"lm head isolation M={M} d={d} V={V}")
+    act = synthgen.normal_f32((M, d), 6, 1, 1.0, False)
+    wb = synthgen.normal_bf16((d, V), 6, 2, 0.02)
+    ref_logits, ref_ids = oracle.lmhead_argmax(act, wb, wdtype=1)
+    packed = fc.lmhead_pack(torch.from_numpy(wb.view(np.int16)).cuda().view(torch.bfloat16))
+    ids, top, logits = fc.lmhead_argmax(torch.from_numpy(act).cuda(), packed, V, want_logits=True)
+    torch.cuda.synchronize()
+    lg = logits.cpu().numpy()
+    err = np.abs(lg - ref_logits).max()
+    print(f"lm head max |dlogit| {err:.3e}")
+    assert err < 1e-3
+    ids = ids.cpu().numpy()
+    assert (ids == lg.argmax(-1)).all()                      # lowest index among equal maxima
+    clear = margins(ref_logits) > 2e-3
+    assert (ids[clear] == ref_ids[clear]).all()
+    assert np.allclose(top.cpu().numpy(), lg.max(-1), rtol=0, atol=0)
+    # without the debug logits the result is the same
+    ids2, _, _ = fc.lmhead_argmax(torch.from_numpy(act).cuda(), packed, V, want_logits=False)
+    assert (ids2.cpu().numpy() == ids).all()
