@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the FastCoT Jacobi decoding step on one MI355X.
+
+A "step" is one pass of the whole hot path: window fetch, embedding, all decoder layers (fused
+QKV + RoPE + cache write, window-causal attention, O-proj, gate/up + SwiGLU, down), final norm,
+LM head with fused argmax, verification, accept/commit and window shift, for one batch.
+
+Default workload: the Llama-2-7B-shaped bf16 model, batch 1, prompt 256, window 16, synthetic
+random-init weights and uniform random token ids (seeded, see synthgen).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+WORKLOADS = {
+    # name: (shape, batch, prompt, window, new tokens)
+    "7b": ("7b", 1, 256, 16, 256),
+    "70b": ("70b", 1, 512, 16, 128),
+    "13b": ("13b", 8, 1024, 32, 256),
+    "tiny": ("tiny", 1, 32, 8, 64),
+}
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def weight_bytes_per_step(s, esz):
+    per_layer = {"gemm_qkv": s.d_model * (s.q_dim + 2 * s.kv_dim), "gemm_o": s.q_dim * s.d_model,
+                 "gemm_gate_up": 2 * s.d_model * s.d_ffn, "gemm_down": s.d_ffn * s.d_model}
+    out = {k: v * esz for k, v in per_layer.items()}
+    out["lm_head"] = s.d_model * s.vocab * esz
+    return out
+
+
+def algorithmic_bytes(s, esz, B, W, n_committed):
+    """Bytes the method itself must move per step: every streamed weight once, the committed K and
+    V once (at the model's storage width), the window's K/V write, the embedding rows."""
+    wb = weight_bytes_per_step(s, esz)
+    weights = s.n_layers * (wb["gemm_qkv"] + wb["gemm_o"] + wb["gemm_gate_up"] + wb["gemm_down"]) + wb["lm_head"]
+    kv_read = sum(s.n_layers * 2 * n * s.kv_dim * esz for n in n_committed)
+    kv_write = s.n_layers * 2 * B * W * s.kv_dim * esz
+    emb = B * W * s.d_model * 4
+    return weights + kv_read + kv_write + emb
+
+
+def cpu_baseline(shape, W, log_fn):
+    """The oracle as it stands (fp32 build), timed on this host on a bounded sample."""
+    import oracle
+    import synthgen
+    P, steps = 32, 3
+    log_fn("cpu_baseline: building the oracle model (bf16-stored weights)")
+    om = oracle.model_from_synth(shape, real="f32", bf16_storage=(shape.dtype == "bf16"))
+    prompt = synthgen.prompts(1, P, shape.vocab)[0]
+    buf = synthgen.buffer_init(1, steps * W + 2 * W, shape.vocab)[0]
+    ss = om.session(P + (steps + 2) * W)
+    ss.forward(prompt[:-1], 0, want_logits=False)
+    n, g, newest, accepted = P - 1, 0, prompt[-1], 0
+    t0 = time.time()
+    for _ in range(steps):
+        w = np.concatenate([[newest], buf[g:g + W - 1]]).astype(np.int32)
+        _, o, _ = ss.forward(w, n, want_logits=False)
+        K = oracle.verify(w, o)
+        buf[g:g + W] = o
+        newest = o[K]
+        n += K + 1
+        g += K + 1
+        accepted += K + 1
+    dt = time.time() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": accepted / dt, "unit": "accepted tokens/s", "ms_per_step": 1e3 * dt / steps, "cores": cores,
+            "kind": "oracle",
+            "sample": f"{steps} Jacobi steps of the fp32 oracle, batch 1, window {W}, context {P - 1}..{n}, same model shape"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="7b", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-iters", type=int, default=3)
+    ap.add_argument("--plain", action="store_true", help="time the plain kernels instead of the MFMA path")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU; --gpus above 1 is not supported "
+                 "(sequences are independent: a multi-GPU run would shard the batch, see DESIGN.md)")
+
+    import torch
+    import synthgen
+    import paper_2311_08263_amd as fc
+
+    shape_name, B, P, W, N = WORKLOADS[args.workload]
+    shape = synthgen.SHAPES[shape_name]
+    esz = 4 if shape.dtype == "f32" else 2
+    K, Wm = args.steps, args.warmup
+    # room for the worst case of W accepted tokens per step
+    max_seq = min(16000, ((P + W * (K + Wm + 2) + 2 * W + 31) // 32) * 32)
+    max_seq = max(max_seq, ((P + N + 2 * W + 31) // 32) * 32)
+    cfg = fc.Config.from_shape(shape, B, max_seq, W)
+    t0 = time.time()
+    log(f"workload {args.workload}: building synthetic weights ({shape.n_params_streamed() * esz / 1e9:.2f} GB streamed per step)")
+    packed = fc.load_synth_weights(cfg, shape)
+    ctx = fc.Context(cfg, packed)
+    if args.plain:
+        ctx.set_option(1, 1)
+    log(f"model resident after {time.time() - t0:.1f}s; max_seq {max_seq}")
+    prompts = synthgen.prompts(B, P, shape.vocab)
+    lens = [P] * B
+    buf_len = min(max_seq, W * (K + Wm + 2) + 2 * W)
+    buf = synthgen.buffer_init(B, max(buf_len, N + 2 * W), shape.vocab)
+
+    # ---- accepted tokens/s on the paper-shaped job: generate N tokens from the prompt
+    ctx.prefill(prompts, lens, buf)
+    ctx.generate(min(N, 4 * W))                        # warm (graph capture, caches)
+    ctx.prefill(prompts, lens, buf)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    out = ctx.generate(N)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    gen_ms = ctx.step_times()
+    gen_steps = int(out["steps"].max())
+    tok_s = float(out["len"].sum()) / gen_s
+    log(f"generate: {int(out['len'].sum())} tokens in {gen_steps} steps, {gen_s * 1e3:.1f} ms, "
+        f"median step {np.median(gen_ms):.3f} ms")
+
+    # ---- exactly K timed steps after Wm warm-up steps (state continues, inputs resident)
+    ctx.prefill(prompts, lens, buf)
+    for _ in range(Wm):
+        ctx.step(sync=False)
+    ctx.stream.synchronize()
+    torch.cuda.synchronize()
+    n_before = ctx.state()["n"].copy()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        ctx.step(sync=False)
+    ctx.stream.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    st = ctx.state()
+    ms_per_step = 1e3 * dt / K
+    accepted_timed = int((st["n"] - n_before).sum())
+    n_mid = (n_before + st["n"]) / 2.0
+    alg = algorithmic_bytes(shape, esz, B, W, n_mid)
+    step_gbs = alg / (ms_per_step * 1e-3) / 1e9
+    log(f"timed: {K} steps, {ms_per_step:.3f} ms/step, accepted {accepted_timed}, "
+        f"algorithmic {alg / 1e9:.3f} GB/step -> {step_gbs:.0f} GB/s ({100 * step_gbs / HBM_PEAK_GBS:.1f}% of 8 TB/s)")
+
+    # ---- per-kernel launch durations (HIP events on the context's stream), dominant kernel roofline
+    prof = ctx.profile_step(args.profile_iters)
+    wb = weight_bytes_per_step(shape, esz)
+    table = []
+    for kind, (ms, cnt) in prof.items():
+        b = wb.get(kind)
+        table.append((kind, ms, cnt, b))
+        log(f"kernel {kind:14s} {cnt:4d}/step  {ms * 1e3:9.2f} us" + (f"  {b / (ms * 1e-3) / 1e9:7.0f} GB/s" if b else ""))
+    dom = max((t for t in table if t[3]), key=lambda t: t[1] * t[2])
+    achieved = dom[3] / (dom[1] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom[0], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": dom[3], "avg_launch_ms": round(dom[1], 5),
+                "step_algorithmic_bytes": int(alg), "step_frac": round(step_gbs / HBM_PEAK_GBS, 4)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(shape, W, log)
+        log(f"cpu_baseline: {cpu['ms_per_step']:.0f} ms/step on {cpu['cores']} threads")
+
+    rec = {
+        "metric": "ms per Jacobi step + accepted tokens/s, 7B-shaped bf16, window 16; % HBM roofline",
+        "value": round(tok_s, 2), "unit": "accepted tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"llama2-{shape_name}-shaped random-init, batch {B}, prompt {P}, window {W}, "
+                               f"{N} new tokens, greedy", "batch": B, "prompt": P, "window": W, "new_tokens": N,
+                   "kernels": "plain" if args.plain else "mfma"},
+        "generate": {"tokens": int(out["len"].sum()), "steps": gen_steps, "wall_ms": round(gen_s * 1e3, 2),
+                     "median_step_ms": round(float(np.median(gen_ms)), 4),
+                     "accepted_per_step": round(float(out["len"].sum()) / max(gen_steps, 1) / B, 3)},
+        "hbm_roofline_pct_step": round(100 * step_gbs / HBM_PEAK_GBS, 2),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(rec), flush=True)
+
+
+if __name__ == "__main__":
+    main()

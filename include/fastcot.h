@@ -129,7 +129,12 @@ int fastcot_debug_logits(fastcot_ctx* ctx, float* d_logits);
  * FASTCOT_OPT_KV_PLANES (bf16 models): 2 (default) keeps every cached K/V value as a bf16 hi +
  * bf16 lo pair (4 bytes, ~16 mantissa bits); 1 keeps the hi plane only (2 bytes, plain bf16).
  * Changing it invalidates the sequences: call fastcot_prefill again. */
-enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLANES = 3 };
+enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLANES = 3,
+       /* launch-shape tuning of the MFMA path (defaults are chosen from the model shape): K slices
+        * per column group of the QKV / O / gate-up / down / LM-head GEMMs, key-range splits of
+        * the attention kernel */
+       FASTCOT_OPT_SK_QKV = 16, FASTCOT_OPT_SK_O = 17, FASTCOT_OPT_SK_GU = 18, FASTCOT_OPT_SK_DOWN = 19,
+       FASTCOT_OPT_SK_LM = 20, FASTCOT_OPT_ATTN_SPLITS = 21 };
 int fastcot_set_option(fastcot_ctx* ctx, int32_t option, int32_t value);
 
 /* Wall time of the steps of the last fastcot_generate, measured with HIP events on the

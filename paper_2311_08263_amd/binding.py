@@ -76,6 +76,9 @@ def lib():
     if _lib is None:
         if not os.path.exists(_build.SO):
             _build.build()
+        # PyTorch ships its own HIP runtime; load it first so that the library binds to the same
+        # one (two runtimes in a process do not see each other's device state)
+        import torch  # noqa: F401
         L = ctypes.CDLL(_build.SO)
         for name, (res, args) in SYMBOLS.items():
             fn = getattr(L, name)      # AttributeError = the library does not export the symbol

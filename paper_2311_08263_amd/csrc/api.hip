@@ -245,6 +245,17 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
         if (c->cfg.dtype != FASTCOT_BF16 || (value != 1 && value != 2)) return fail(c, FASTCOT_EINVAL, "KV planes: 1 or 2, bf16 models only%s");
         c->kd.kvp = value; c->prefilled = 0;      // the cache layout changes: a new prefill is required
     }
+    else if (option >= FASTCOT_OPT_SK_QKV && option <= FASTCOT_OPT_SK_LM) {
+        GemmPlan* gp[5] = {&c->plan.qkv, &c->plan.o, &c->plan.gu, &c->plan.down, &c->plan.lm};
+        const int Ks[5] = {c->kd.d, c->kd.H * c->kd.Dh, c->kd.d, c->kd.F, c->kd.d};
+        const int NU = Ks[option - FASTCOT_OPT_SK_QKV] / 256;
+        if (value < 1 || value > FC_MAX_SK || value > NU || (NU + value - 1) / value > 4)
+            return fail(c, FASTCOT_EINVAL, "split-K out of range: slices must hold 1..4 units of 256 inputs%s");
+        gp[option - FASTCOT_OPT_SK_QKV]->sk = value;
+    } else if (option == FASTCOT_OPT_ATTN_SPLITS) {
+        if (value < 1 || value > FC_MAX_ATTN_SPLITS) return fail(c, FASTCOT_EINVAL, "attention splits out of range%s");
+        c->plan.attn_splits = value;
+    }
     else return fail(c, FASTCOT_EINVAL, "unknown option%s");
     drop_graph(c);
     return 0;

@@ -14,6 +14,7 @@
 // consecutive keys.  Waves are merged through LDS, key splits through a scratch buffer by the last
 // workgroup to arrive, always in index order, so results do not depend on timing.
 #include "attn16.h"
+#include "xwg.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
@@ -179,14 +180,19 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
             const float* s = src + qt * PART_FLOATS;
-            const float mo = s[2048 + lane], lo = s[2112 + lane];
+            const float mo = global ? ld_agent_f32(s + 2048 + lane) : s[2048 + lane];
+            const float lo = global ? ld_agent_f32(s + 2112 + lane) : s[2112 + lane];
             const float mnew = fmaxf(mrun[qt], mo);
             const float wa = expf(mrun[qt] - mnew), wb = expf(mo - mnew);
             lrun[qt] = lrun[qt] * wa + lo * wb;
             mrun[qt] = mnew;
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) {
-                f32x4_t o = *(const f32x4_t*)(s + (dt * 64 + lane) * 4);
+                f32x4_t o;
+                if (global) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) o[r] = ld_agent_f32(s + (dt * 64 + lane) * 4 + r);
+                } else o = *(const f32x4_t*)(s + (dt * 64 + lane) * 4);
                 acc[qt][dt] = acc[qt][dt] * wa + o * wb;
             }
         }
@@ -198,16 +204,17 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) *(f32x4_t*)(mine + qt * PART_FLOATS + (dt * 64 + lane) * 4) = acc[qt][dt];
-            mine[qt * PART_FLOATS + 2048 + lane] = mrun[qt];
-            mine[qt * PART_FLOATS + 2112 + lane] = lrun[qt];
+            for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) st_agent_f32(mine + qt * PART_FLOATS + (dt * 64 + lane) * 4 + r, acc[qt][dt][r]);
+            st_agent_f32(mine + qt * PART_FLOATS + 2048 + lane, mrun[qt]);
+            st_agent_f32(mine + qt * PART_FLOATS + 2112 + lane, lrun[qt]);
         }
-        __threadfence();
+        wait_vmem_done();
         int old = 0;
-        if (lane == 0) old = atomicAdd(a.cnt + bh, 1);
+        if (lane == 0) old = arrive_agent(a.cnt + bh);
         old = __shfl(old, 0, 64);
         if (old != nsp - 1) return;
-        __threadfence();
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
             mrun[qt] = NEG_BIG; lrun[qt] = 0.f;
@@ -215,7 +222,7 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
             for (int dt = 0; dt < 8; ++dt) acc[qt][dt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
         }
         for (int s2 = 0; s2 < nsp; ++s2) fold(a.part + ((size_t)bh * nsp + s2) * QT * PART_FLOATS, true);
-        if (lane == 0) a.cnt[bh] = 0;
+        if (lane == 0) st_agent_i32(a.cnt + bh, 0);
     }
     // out[row][h*128 + 16*dt + 4*g + r] = O / l
 #pragma unroll

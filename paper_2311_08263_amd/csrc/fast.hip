@@ -12,19 +12,19 @@ bool fc_fast_supported(const KernelDims& kd, int rows) {
            (kd.H * kd.Dh) % 256 == 0 && kd.S % 32 == 0 && kd.V % 16 == 0;
 }
 
-// K slices: between 1 and 4 units of 256 inputs each; enough workgroups to cover the chip twice.
+// K slices per column group: about 500 workgroups in all (two per CU, one round), slices of 2..4
+// units of 256 inputs where the shape allows (measured on the 7B shape: fewer, fatter slices beat
+// many thin ones because every slice pays the fixed cost of the cross-workgroup fix-up).
 static int choose_sk(int K, int ncg) {
     const int NU = K / 256;
-    int lo = (NU + 3) / 4, hi = NU < FC_MAX_SK ? NU : FC_MAX_SK;
+    int lo = (NU + 3) / 4, hi = NU / 2;
     if (lo < 1) lo = 1;
-    int first = 0;
-    for (int sk = lo; sk <= hi; ++sk) {
-        if (ncg * sk < 512) continue;
-        if (!first) first = sk;
-        if (NU % sk == 0) return sk;
-        if (sk > 2 * first) break;
-    }
-    return first ? first : hi;
+    if (hi < lo) hi = lo;
+    if (hi > FC_MAX_SK) hi = FC_MAX_SK;
+    int sk = (500 + ncg / 2) / ncg;
+    if (sk < lo) sk = lo;
+    if (sk > hi) sk = hi;
+    return sk;
 }
 
 void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
@@ -35,7 +35,7 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     p->gu = mk(kd.d, 2 * kd.F);
     p->down = mk(kd.F, kd.d);
     p->lm = mk(kd.d, kd.V);
-    int nb = (kd.S + 31) / 32, sp = (nb + 5) / 6;
+    int nb = (kd.S + 31) / 32, sp = (nb + 7) / 8;
     if (sp > FC_MAX_ATTN_SPLITS) sp = FC_MAX_ATTN_SPLITS;
     while (sp > 1 && kd.B * kd.H * sp > 2048) --sp;
     p->attn_splits = sp < 1 ? 1 : sp;

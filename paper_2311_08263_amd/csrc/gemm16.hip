@@ -16,6 +16,7 @@
 // commutes with the GEMM as a per-row factor; the gain is applied while staging), rotary
 // embedding + KV-cache write, residual add, SwiGLU, or the LM head's per-row argmax.
 #include "gemm16.h"
+#include "xwg.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
@@ -159,33 +160,56 @@ __global__ __launch_bounds__(512) void k_gemm16(Gemm16Args a) {
 
     // 4. cross-workgroup split-K: ordered fix-up by the last workgroup of the column group
     if (sk > 1) {
-        f32x4_t* mypart = (f32x4_t*)a.part + (((size_t)(cg * sk + ks) * 8 + w) * MT) * 64 + lane;
+        float* mypart = a.part + ((((size_t)(cg * sk + ks) * 8 + w) * MT) * 64 + lane) * 4;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) mypart[mt * 64] = acc[mt];
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) st_agent_f32(mypart + mt * 256 + r, acc[mt][r]);
         float* sspart = a.sspart + (size_t)(cg * sk + ks) * (MT * 16);
-        if (tid < MT * 16) sspart[tid] = lds_rs[tid];
-        __threadfence();
+        if (tid < MT * 16) st_agent_f32(sspart + tid, lds_rs[tid]);
+        wait_vmem_done();
         __syncthreads();
-        if (tid == 0) {
-            int old = atomicAdd(a.cnt + cg, 1);
-            *lds_flag = (old == sk - 1);
-        }
+        if (tid == 0) *lds_flag = (arrive_agent(a.cnt + cg) == sk - 1);
         __syncthreads();
         if (!*lds_flag) return;
-        __threadfence();
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < sk; ++s) {
-            const f32x4_t* p = (const f32x4_t*)a.part + (((size_t)(cg * sk + s) * 8 + w) * MT) * 64 + lane;
+        // all loads of a batch of slices are issued before the first add: one memory round trip per
+        // batch instead of one per slice; the adds stay in slice order
+        for (int s0 = 0; s0 < sk; s0 += 8) {
+            float pv[8][MT][4];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt] += __builtin_nontemporal_load(p + mt * 64);
+            for (int s = 0; s < 8; ++s)
+                if (s0 + s < sk) {
+                    const float* p = a.part + ((((size_t)(cg * sk + s0 + s) * 8 + w) * MT) * 64 + lane) * 4;
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) pv[s][mt][r] = ld_agent_f32(p + mt * 256 + r);
+                }
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+                if (s0 + s < sk) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[mt][r] += pv[s][mt][r];
+                }
         }
         if (tid < MT * 16) {
             float s = 0.f;
-            for (int q = 0; q < sk; ++q) s += __builtin_nontemporal_load(a.sspart + (size_t)(cg * sk + q) * (MT * 16) + tid);
+            for (int q0 = 0; q0 < sk; q0 += 16) {
+                float sv[16];
+#pragma unroll
+                for (int q = 0; q < 16; ++q)
+                    if (q0 + q < sk) sv[q] = ld_agent_f32(a.sspart + (size_t)(cg * sk + q0 + q) * (MT * 16) + tid);
+#pragma unroll
+                for (int q = 0; q < 16; ++q)
+                    if (q0 + q < sk) s += sv[q];
+            }
             lds_rs[tid] = s;
         }
-        if (tid == 0) a.cnt[cg] = 0;    // ready for the next launch
+        if (tid == 0) st_agent_i32(a.cnt + cg, 0);    // ready for the next launch
         __syncthreads();
     } else {
         __syncthreads();                // every wave is past its LDS reads before the region is reused

@@ -1,0 +1,26 @@
+// Cross-workgroup hand-off without cache-wide fences.
+//
+// The split-K and split-KV fix-ups pass small partial results between workgroups that may run
+// on different XCDs (each XCD has its own L2).  A full agent-scope fence would write back and
+// invalidate a whole L2 per call.  Instead the partial data itself is moved with agent-scope
+// (device-coherent) stores and loads, the producer waits until its stores have completed before
+// it bumps the arrival counter (a device-scope atomic), and the consumer reads only after it has
+// seen the final count.  No spinning anywhere: the last workgroup to arrive does the merge.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+__device__ inline void st_agent_f32(float* p, float v) {
+    __hip_atomic_store((uint32_t*)p, __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float ld_agent_f32(const float* p) {
+    return __uint_as_float(__hip_atomic_load((const uint32_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ inline void st_agent_i32(int32_t* p, int32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline int32_t arrive_agent(int32_t* counter) {
+    return __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// all earlier vector-memory operations of this wave (the agent-scope stores above) have completed
+__device__ inline void wait_vmem_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
