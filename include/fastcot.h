@@ -128,14 +128,26 @@ int fastcot_debug_logits(fastcot_ctx* ctx, float* d_logits);
  * stream cannot be captured.
  * FASTCOT_OPT_KV_PLANES (bf16 models): 2 (default) keeps every cached K/V value as a bf16 hi +
  * bf16 lo pair (4 bytes, ~16 mantissa bits); 1 keeps the hi plane only (2 bytes, plain bf16).
- * Changing it invalidates the sequences: call fastcot_prefill again. */
-enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLANES = 3,
+ * Changing it invalidates the sequences: call fastcot_prefill again.
+ * FASTCOT_OPT_PERSISTENT = 1 runs a step of a bf16 model with at most 16 rows as one persistent
+ * kernel (one workgroup per compute unit, grid barriers between stages, weight tiles prefetched
+ * across stages); 0 (default) launches one kernel per stage.  The persistent kernel is correct but
+ * currently slower than the per-stage kernels. */
+enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLANES = 3, FASTCOT_OPT_PERSISTENT = 4,
        /* launch-shape tuning of the MFMA path (defaults are chosen from the model shape): K slices
         * per column group of the QKV / O / gate-up / down / LM-head GEMMs, key-range splits of
         * the attention kernel */
        FASTCOT_OPT_SK_QKV = 16, FASTCOT_OPT_SK_O = 17, FASTCOT_OPT_SK_GU = 18, FASTCOT_OPT_SK_DOWN = 19,
-       FASTCOT_OPT_SK_LM = 20, FASTCOT_OPT_ATTN_SPLITS = 21 };
+       FASTCOT_OPT_SK_LM = 20, FASTCOT_OPT_ATTN_SPLITS = 21,
+       /* debug: run only the first `value` stages of a forward (per layer: QKV, attention, O,
+        * gate/up, down); negative = all */
+       FASTCOT_OPT_DEBUG_STAGES = 30 };
 int fastcot_set_option(fastcot_ctx* ctx, int32_t option, int32_t value);
+
+/* Debug: copies `count` floats of an activation buffer of the last forward to the host after
+ * synchronising: what = 0 residual stream [rows][d_model], 1 rotated queries (MFMA path: [rows][H*Dh]),
+ * 2 attention output [rows][H*Dh], 3 MLP hidden [rows][d_ffn]. */
+int fastcot_debug_read(fastcot_ctx* ctx, int32_t what, float* host, size_t count);
 
 /* Wall time of the steps of the last fastcot_generate, measured with HIP events on the
  * context's stream: ms[i] for step i, up to cap entries; *n_steps = steps taken. */

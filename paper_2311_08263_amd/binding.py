@@ -57,6 +57,7 @@ SYMBOLS = {
     "fastcot_get_state": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp]),
     "fastcot_debug_logits": (ctypes.c_int, [vp, vp]),
     "fastcot_set_option": (ctypes.c_int, [vp, i32, i32]),
+    "fastcot_debug_read": (ctypes.c_int, [vp, i32, vp, sz]),
     "fastcot_step_times": (ctypes.c_int, [vp, vp, i32, vp]),
     "fastcot_profile_step": (ctypes.c_int, [vp, i32, vp, vp]),
     "fastcot_kernel_name": (ctypes.c_char_p, [i32]),
@@ -243,6 +244,11 @@ class Context:
             _check(lib().fastcot_debug_logits(self.h, None), self.h)
             self._dbg = None
         return self._dbg
+
+    def debug_read(self, what: int, rows: int, cols: int) -> np.ndarray:
+        out = np.zeros((rows, cols), dtype=np.float32)
+        _check(lib().fastcot_debug_read(self.h, what, out.ctypes.data, out.size), self.h)
+        return out
 
     def step_times(self) -> np.ndarray:
         n = i32(0)

@@ -8,6 +8,7 @@
 #include <vector>
 #include "kernels.h"
 #include "fast.h"
+#include "persist.h"
 
 static thread_local char g_err[512] = "";
 
@@ -22,7 +23,7 @@ struct fastcot_ctx {
     int Bact;            // sequences of the current run
     int prefilled, generated;
     int buf_len;
-    int opt_plain, opt_graph;
+    int opt_plain, opt_graph, opt_persist, dbg_stop;
     float* dbg_logits;
     hipGraphExec_t graph_exec;
     hipGraph_t graph;
@@ -54,7 +55,7 @@ static int fail(fastcot_ctx* c, int code, const char* fmt, const char* a = "", l
 
 static const char* kKernelNames[FASTCOT_N_KERNEL_KINDS] = {
     "embed", "rmsnorm", "gemm_qkv", "rope_cache", "attention", "gemm_o", "gemm_gate_up", "swiglu",
-    "gemm_down", "lm_head", "argmax", "accept_commit", "attn_combine", "reserved13", "reserved14", "reserved15"};
+    "gemm_down", "lm_head", "argmax", "accept_commit", "attn_combine", "persistent_step", "reserved14", "reserved15"};
 enum { KK_EMBED = 0, KK_RMSNORM, KK_QKV, KK_ROPE, KK_ATTN, KK_O, KK_GU, KK_SWIGLU, KK_DOWN, KK_LM, KK_ARGMAX, KK_ACCEPT };
 
 extern "C" const char* fastcot_kernel_name(int32_t kind) {
@@ -113,7 +114,7 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
         size_t cache = (size_t)k.L * k.B * k.Hkv * k.kvp * k.S * k.Dh * esz;
         wm->kc = take(cache); wm->vc = take(cache);
         wm->rope_cos = take((size_t)k.S * (k.Dh / 2) * 4); wm->rope_sin = take((size_t)k.S * (k.Dh / 2) * 4);
-        wm->x = take(M * d * 4); wm->nx = take(M * d * 4); wm->qkv = take(M * k.qkvN * 4);
+        wm->x = take(M * d * 4); wm->nx = take(M * d * 4); wm->qkv = take(M * k.qkvN * 4); wm->qrot = take(M * qd * 4);
         wm->att = take(M * qd * 4); wm->gu = take(M * 2 * F * 4); wm->h = take(M * F * 4);
         wm->logits = take(M * k.V * 4); wm->topv = take(M * 4);
         fc_fast_scratch_sizes(k, &wm->gemm_part_bytes, &wm->attn_part_bytes);
@@ -166,8 +167,8 @@ extern "C" int fastcot_pack_tensor(const fastcot_config* cfg, int32_t tensor, in
             e = src ? fc_copy_bytes(dst, src, (size_t)d * 4, st) : fc_fill_f32(dst, d, 1.0f, st);
             break;
         }
-        case FASTCOT_T_WQ: e = fc_pack(src, dt, d, qd, lbase, mm.qkv, 0, 0, st); break;
-        case FASTCOT_T_WK: e = fc_pack(src, dt, d, kvd, lbase, mm.qkv, qd, 0, st); break;
+        case FASTCOT_T_WQ: e = fc_pack(src, dt, d, qd, lbase, mm.qkv, 0, 3 + kd.Dh, st); break;
+        case FASTCOT_T_WK: e = fc_pack(src, dt, d, kvd, lbase, mm.qkv, qd, 3 + kd.Dh, st); break;
         case FASTCOT_T_WV: e = fc_pack(src, dt, d, kvd, lbase, mm.qkv, qd + kvd, 0, st); break;
         case FASTCOT_T_WO: e = fc_pack(src, dt, qd, d, lbase, mm.o, 0, 0, st); break;
         case FASTCOT_T_WG: e = fc_pack(src, dt, d, kd.F, lbase, mm.gu, 0, 1, st); break;
@@ -193,7 +194,7 @@ extern "C" int fastcot_init(const fastcot_config* cfg, const void* d_packed, voi
     if (workspace_bytes < c->wm.total) { delete c; return fail(nullptr, FASTCOT_ECAPACITY, "workspace too small%s"); }
     c->cfg = *cfg; c->weights = (const char*)d_packed; c->ws = (char*)d_workspace; c->st = (hipStream_t)hip_stream;
     c->Bact = 0; c->prefilled = 0; c->generated = 0; c->buf_len = 0;
-    c->opt_plain = (cfg->dtype == FASTCOT_F32); c->opt_graph = 1; c->dbg_logits = nullptr;
+    c->opt_plain = (cfg->dtype == FASTCOT_F32); c->opt_graph = 1; c->opt_persist = 0; c->dbg_stop = -1; c->dbg_logits = nullptr;
     c->graph_exec = nullptr; c->graph = nullptr; c->graph_valid = 0; c->prof_on = 0; c->prof_used = 0;
     c->pinned = nullptr; c->err[0] = 0;
     fc_fast_plan(c->kd, &c->plan);
@@ -241,6 +242,8 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
         if (!value && c->cfg.dtype == FASTCOT_F32) return fail(c, FASTCOT_EINVAL, "fp32 models only have the plain kernels%s");
         c->opt_plain = value != 0;
     } else if (option == FASTCOT_OPT_GRAPH) c->opt_graph = value != 0;
+    else if (option == FASTCOT_OPT_PERSISTENT) c->opt_persist = value != 0;
+    else if (option == FASTCOT_OPT_DEBUG_STAGES) c->dbg_stop = value;
     else if (option == FASTCOT_OPT_KV_PLANES) {
         if (c->cfg.dtype != FASTCOT_BF16 || (value != 1 && value != 2)) return fail(c, FASTCOT_EINVAL, "KV planes: 1 or 2, bf16 models only%s");
         c->kd.kvp = value; c->prefilled = 0;      // the cache layout changes: a new prefill is required
@@ -299,9 +302,9 @@ static int forward_plain(fastcot_ctx* c, int lmhead) {
         const char* lb = wt + c->mm.layers_off + (size_t)l * c->mm.layer_stride;
         LAUNCH(c, KK_RMSNORM, fc_rmsnorm_plain(x, (const float*)(lb + c->mm.g1_off), nx, M, d, kd.eps, c->st));
         LAUNCH(c, KK_QKV, fc_gemm_plain(lb + c->mm.qkv.off, dt, d, c->mm.qkv.NP, kd.qkvN, nx, d, qkv, kd.qkvN, M, 0, c->st));
-        LAUNCH(c, KK_ROPE, fc_rope_cache_plain(qkv, kd, l, stp + sm.n, (const float*)(ws + c->wm.rope_cos),
+        LAUNCH(c, KK_ROPE, fc_rope_cache_plain(qkv, (float*)(ws + c->wm.qrot), kd, l, stp + sm.n, (const float*)(ws + c->wm.rope_cos),
                                                (const float*)(ws + c->wm.rope_sin), ws + c->wm.kc, ws + c->wm.vc, dt, c->st));
-        LAUNCH(c, KK_ATTN, fc_attn_plain(qkv, kd.qkvN, ws + c->wm.kc, ws + c->wm.vc, dt, kd, l, stp + sm.n, att, c->st));
+        LAUNCH(c, KK_ATTN, fc_attn_plain((const float*)(ws + c->wm.qrot), qd, ws + c->wm.kc, ws + c->wm.vc, dt, kd, l, stp + sm.n, att, c->st));
         LAUNCH(c, KK_O, fc_gemm_plain(lb + c->mm.o.off, dt, qd, c->mm.o.NP, d, att, qd, x, d, M, 1, c->st));
         LAUNCH(c, KK_RMSNORM, fc_rmsnorm_plain(x, (const float*)(lb + c->mm.g2_off), nx, M, d, kd.eps, c->st));
         LAUNCH(c, KK_GU, fc_gemm_plain(lb + c->mm.gu.off, dt, d, c->mm.gu.NP, 2 * kd.F, nx, d, gu, 2 * kd.F, M, 0, c->st));
@@ -317,20 +320,36 @@ static int forward_plain(fastcot_ctx* c, int lmhead) {
     return 0;
 }
 
-static int forward(fastcot_ctx* c, int lmhead) {
+static bool use_persist(const fastcot_ctx* c) {
+    return !c->opt_plain && c->opt_persist && fc_persist_supported(c->kd, c->Bact * c->kd.W);
+}
+
+static int forward(fastcot_ctx* c, int lmhead, int do_accept = 0) {
     if (c->opt_plain || !fc_fast_supported(c->kd, c->Bact * c->kd.W)) return forward_plain(c, lmhead);
     FastArgs a;
     a.kd = c->kd; a.kd.M = c->Bact * c->kd.W; a.Bact = c->Bact;
     a.mm = &c->mm; a.wm = &c->wm; a.weights = c->weights; a.ws = c->ws; a.dbg_logits = c->dbg_logits;
     a.plan = &c->plan; a.st = c->st; a.lmhead = lmhead;
+    a.dbg_stop = c->dbg_stop;
     a.prof = c->prof_on ? c : nullptr;
     a.prof_mark = c->prof_on ? [](void* p, int kind) { return prof_mark((fastcot_ctx*)p, kind); } : nullptr;
-    hipError_t e = fc_fast_forward(a);
-    if (e != hipSuccess) return fail(c, FASTCOT_EHIP, "fast forward failed: %s", hipGetErrorString(e));
+    hipError_t e = use_persist(c) ? fc_persist_step(a, do_accept, a.prof, a.prof_mark) : fc_fast_forward(a);
+    if (e != hipSuccess) return fail(c, FASTCOT_EHIP, "forward launch failed: %s", hipGetErrorString(e));
+    return 0;
+}
+
+// the persistent kernel's grid barrier gave up (the grid was not co-resident): report it
+static int check_abort(fastcot_ctx* c) {
+    if (!use_persist(c)) return 0;
+    int32_t flag = 0;
+    hipError_t e = hipMemcpy(&flag, (int32_t*)(c->ws + c->wm.gemm_cnt) + FC_MAX_COUNTERS - 7, 4, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(c, FASTCOT_EHIP, "HIP error '%s' reading the barrier state", hipGetErrorString(e));
+    if (flag) return fail(c, FASTCOT_EHIP, "grid barrier of the persistent step kernel timed out%s");
     return 0;
 }
 
 static int step_body(fastcot_ctx* c) {
+    if (use_persist(c)) return forward(c, 1, 1);      // accept/commit is the kernel's last stage
     int rc = forward(c, 1);
     if (rc) return rc;
     LAUNCH(c, KK_ACCEPT, fc_accept_commit(state_ptr(c), c->wm.st, c->Bact, c->kd.W, c->kd.S, c->st));
@@ -400,6 +419,7 @@ extern "C" int fastcot_prefill(fastcot_ctx* c, int32_t B, const int32_t* prompts
         HIPCHK(c, fc_prefill_advance(stp, sm, B, kd.W, kd.S, ch, ch == nch - 1, c->st));
     }
     HIPCHK(c, hipStreamSynchronize(c->st));
+    { int rc = check_abort(c); if (rc) return rc; }
     c->prefilled = 1;
     return 0;
 }
@@ -422,6 +442,7 @@ extern "C" int fastcot_jacobi_step(fastcot_ctx* c, int32_t* n_accepted, int32_t*
         if (accepted) for (int j = 0; j < W; ++j) accepted[(size_t)b * W + j] = (j <= K[b]) ? o[(size_t)b * W + j] : -1;
     }
     if (window_next) HIPCHK(c, hipMemcpy(window_next, stp + sm.win, (size_t)B * W * 4, hipMemcpyDeviceToHost));
+    { int rc2 = check_abort(c); if (rc2) return rc2; }
     int32_t flags[2];
     HIPCHK(c, hipMemcpy(flags, stp + sm.flags, 8, hipMemcpyDeviceToHost));
     if (flags[FLAG_ERROR]) return fail(c, FASTCOT_ECAPACITY, "a sequence ran out of cache or buffer capacity%s");
@@ -486,6 +507,7 @@ extern "C" int fastcot_generate(fastcot_ctx* c, int32_t max_new, int32_t max_ste
         HIPCHK(c, hipMemcpyAsync(c->pinned + B, stp + sm.done, (size_t)B * 4, hipMemcpyDeviceToHost, c->st));
         HIPCHK(c, hipMemcpyAsync(c->pinned + 2 * B, stp + sm.flags, 8, hipMemcpyDeviceToHost, c->st));
         HIPCHK(c, hipStreamSynchronize(c->st));
+        { int rc = check_abort(c); if (rc) return rc; }
         all_done = c->pinned[2 * B + FLAG_ALL_DONE] != 0;
         for (int b = 0; b < B; ++b) { hg[b] = c->pinned[b]; hdone[b] = c->pinned[B + b]; }
         if (c->pinned[2 * B + FLAG_ERROR]) return fail(c, FASTCOT_ECAPACITY, "a sequence ran out of cache or buffer capacity%s");
@@ -552,5 +574,24 @@ extern "C" int fastcot_profile_step(fastcot_ctx* c, int32_t iters, float* mean_m
         mean_ms[k] = cnt[k] ? (float)(sum[k] / cnt[k]) : 0.f;
         launches_per_step[k] = (int32_t)(cnt[k] / iters);
     }
+    return 0;
+}
+
+// ------------------------------------------------------------------ debug read-back of activations
+extern "C" int fastcot_debug_read(fastcot_ctx* c, int32_t what, float* host, size_t count) {
+    if (!c || !host) return fail(c, FASTCOT_EINVAL, "NULL argument%s");
+    const size_t M = (size_t)c->kd.B * c->kd.W;
+    size_t off, cap;
+    switch (what) {
+        case 0: off = c->wm.x; cap = M * c->kd.d; break;
+        case 1: off = c->wm.qkv; cap = M * c->kd.qkvN; break;
+        case 2: off = c->wm.att; cap = M * c->kd.H * c->kd.Dh; break;
+        case 3: off = c->wm.h; cap = M * c->kd.F; break;
+        case 4: off = c->wm.logits; cap = M * c->kd.V; break;     // plain-path logits buffer (trace data in FC_TRACE builds)
+        default: return fail(c, FASTCOT_EINVAL, "unknown buffer%s");
+    }
+    if (count > cap) return fail(c, FASTCOT_ECAPACITY, "count exceeds the buffer%s");
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    HIPCHK(c, hipMemcpy(host, c->ws + off, count * 4, hipMemcpyDeviceToHost));
     return 0;
 }

@@ -34,9 +34,22 @@ __host__ __device__ inline size_t frag_index(int32_t K, int32_t k, int32_t n) {
     return ((size_t)(nt * (size_t)KT + kt) * 64 + lane) * 8 + (k & 7);
 }
 
-// column order of the fused gate/up matrix: 16-column blocks alternate gate, up
+// Column order inside the fused matrices.  Outputs that an epilogue must combine sit in the same
+// 16-column MFMA tile, 8 columns apart, so that the two values end up in lanes l and l^32 of one
+// wave: gate and up of a feature (SwiGLU), and the rotary pair (i, i + Dh/2) of a head.
 __host__ __device__ inline int32_t gu_col(int32_t feature, int32_t is_up) {
-    return ((feature >> 4) << 5) + (is_up << 4) + (feature & 15);
+    return ((feature >> 3) << 4) + (is_up << 3) + (feature & 7);
+}
+// position of element i of a head inside the head's Dh packed columns
+__host__ __device__ inline int32_t head_col(int32_t i, int32_t Dh) {
+    const int32_t half = Dh >> 1, lo = i < half ? i : i - half;
+    return ((lo >> 3) << 4) + ((i < half ? 0 : 1) << 3) + (lo & 7);
+}
+// canonical fused QKV column (head-major, natural order inside a head) -> packed column;
+// v heads (columns from v_begin on) keep the natural order
+__host__ __device__ inline int32_t qkv_col(int32_t c, int32_t Dh, int32_t v_begin) {
+    if (c >= v_begin) return c;
+    return (c / Dh) * Dh + head_col(c % Dh, Dh);
 }
 
 struct ModelMap {
@@ -61,7 +74,7 @@ enum { PARAM_MAX_NEW = 0, PARAM_EOS = 1, PARAM_MAX_STEPS = 2, PARAM_BUF_LEN = 3,
 struct WorkspaceMap {
     size_t kc, vc;              // KV cache: K [L][B][Hkv][planes][S][Dh], V transposed [L][B][Hkv][planes][Dh][S]
     size_t rope_cos, rope_sin;  // fp32 [S][Dh/2]
-    size_t x, nx, qkv, att, gu, h, logits, topv;
+    size_t x, nx, qkv, qrot, att, gu, h, logits, topv;
     size_t gemm_part, gemm_cnt, attn_part, attn_cnt, amax_part;
     size_t state;
     size_t total;

@@ -26,6 +26,7 @@ struct FastArgs {
     hipStream_t st;
     void* prof;
     hipError_t (*prof_mark)(void*, int);
+    int dbg_stop;      // debug: number of stages to run (5 per layer), < 0 = all
 };
 
 // true when the MFMA path covers this shape (else the caller uses the plain kernels)

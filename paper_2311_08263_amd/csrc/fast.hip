@@ -4,6 +4,7 @@
 #include "kernels.h"
 #include "gemm16.h"
 #include "attn16.h"
+#include "persist.h"
 
 enum { KK_EMBED = 0, KK_QKV = 2, KK_ATTN = 4, KK_O = 5, KK_GU = 6, KK_DOWN = 8, KK_LM = 9, KK_ARGMAX = 10 };
 
@@ -48,6 +49,7 @@ void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t
     if (kd.V > nmax) nmax = kd.V;
     const size_t ncg = (size_t)(nmax / 16 + 7) / 8;
     *gemm_part_bytes = ncg * FC_MAX_SK * (8 * 2 * 1024 + 2 * 16 * 4) + 4096;
+    if (*gemm_part_bytes < fc_persist_part_bytes(kd)) *gemm_part_bytes = fc_persist_part_bytes(kd);
     *attn_part_bytes = fc_attn16_part_bytes(kd.B * kd.H, FC_MAX_ATTN_SPLITS, kd.W) + 4096;
 }
 
@@ -87,15 +89,23 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     };
 
     FLAUNCH(KK_EMBED, fc_embed(wt + mm.emb_off, FASTCOT_BF16, stp + wm.st.win, x, M, d, kd.V, a.st));
+    int nstage = 0;
+#define DBG_STOP() do { if (a.dbg_stop >= 0 && nstage++ >= a.dbg_stop) return hipSuccess; } while (0)
     for (int l = 0; l < kd.L; ++l) {
         const char* lb = wt + mm.layers_off + (size_t)l * mm.layer_stride;
         g.layer = l; at.layer = l;
+        DBG_STOP();
         FLAUNCH(KK_QKV, gemm(EPI_QKV, a.plan->qkv, lb + mm.qkv.off, d, kd.qkvN, x, d, (const float*)(lb + mm.g1_off), q, qd));
+        DBG_STOP();
         FLAUNCH(KK_ATTN, fc_attn16(at, a.Bact, a.plan->attn_splits, a.st));
+        DBG_STOP();
         FLAUNCH(KK_O, gemm(EPI_RESID, a.plan->o, lb + mm.o.off, qd, d, att, qd, nullptr, x, d));
+        DBG_STOP();
         FLAUNCH(KK_GU, gemm(EPI_SWIGLU, a.plan->gu, lb + mm.gu.off, d, 2 * kd.F, x, d, (const float*)(lb + mm.g2_off), h, kd.F));
+        DBG_STOP();
         FLAUNCH(KK_DOWN, gemm(EPI_RESID, a.plan->down, lb + mm.down.off, kd.F, d, h, kd.F, nullptr, x, d));
     }
+    if (a.dbg_stop >= 0 && nstage >= a.dbg_stop) return hipSuccess;
     if (a.lmhead) {
         const int stride = M > 16 ? 32 : 16;
         g.amax_idx = (int32_t*)(g.amax_val + (size_t)a.plan->lm.ncg * stride);

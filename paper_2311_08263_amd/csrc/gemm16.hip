@@ -234,26 +234,21 @@ __global__ __launch_bounds__(512) void k_gemm16(Gemm16Args a) {
             }
         }
     } else if (EPI == EPI_SWIGLU) {
-        float4* ex = (float4*)smem;     // [pair][mt][lane]
-        if (active && (w & 1)) {
+        // a tile holds gate features f0..f0+7 in columns 0..7 and their up values in columns 8..15:
+        // the partner of lane l is lane l ^ 32
+        if (!active) return;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                ex[((w >> 1) * MT + mt) * 64 + lane] = make_float4(acc[mt][0] * rs[mt], acc[mt][1] * rs[mt], acc[mt][2] * rs[mt], acc[mt][3] * rs[mt]);
-        }
-        __syncthreads();
-        if (active && !(w & 1)) {
+        for (int mt = 0; mt < MT; ++mt) {
+            const int m = mt * 16 + lm;
+            float4 h;
+            float* hp = &h.x;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int m = mt * 16 + lm;
-                if (m < a.M) {
-                    float4 u = ex[((w >> 1) * MT + mt) * 64 + lane];
-                    float gx = acc[mt][0] * rs[mt], gy = acc[mt][1] * rs[mt], gz = acc[mt][2] * rs[mt], gw = acc[mt][3] * rs[mt];
-                    float4 h;
-                    h.x = gx / (1.0f + expf(-gx)) * u.x; h.y = gy / (1.0f + expf(-gy)) * u.y;
-                    h.z = gz / (1.0f + expf(-gz)) * u.z; h.w = gw / (1.0f + expf(-gw)) * u.w;
-                    *(float4*)(a.out + (size_t)m * a.ldo + (nt >> 1) * 16 + 4 * g4) = h;
-                }
+            for (int r = 0; r < 4; ++r) {
+                const float mine = acc[mt][r] * rs[mt];
+                const float other = __shfl_xor(mine, 32, 64);
+                hp[r] = mine / (1.0f + expf(-mine)) * other;       // meaningful in the gate lanes (g4 < 2)
             }
+            if (g4 < 2 && m < a.M) *(float4*)(a.out + (size_t)m * a.ldo + nt * 8 + 4 * g4) = h;
         }
     } else if (EPI == EPI_QKV) {
         // column group = one head of 128 (q heads, then k heads, then v heads)
@@ -261,7 +256,8 @@ __global__ __launch_bounds__(512) void k_gemm16(Gemm16Args a) {
         if (active) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                *(float4*)(ex + (size_t)(mt * 16 + lm) * 132 + w * 16 + 4 * g4) =
+                // q/k heads: tile w holds elements 8w..8w+7 and their rotary partners 64+8w..; v heads: natural
+                *(float4*)(ex + (size_t)(mt * 16 + lm) * 132 + (cg < a.H + a.Hkv ? (g4 < 2 ? 8 * w + 4 * g4 : 64 + 8 * w + 4 * (g4 - 2)) : w * 16 + 4 * g4)) =
                     make_float4(acc[mt][0] * rs[mt], acc[mt][1] * rs[mt], acc[mt][2] * rs[mt], acc[mt][3] * rs[mt]);
         }
         __syncthreads();

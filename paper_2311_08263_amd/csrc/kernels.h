@@ -7,7 +7,7 @@ hipError_t fc_embed(const void* emb, int dt, const int32_t* win, float* x, int M
 hipError_t fc_rmsnorm_plain(const float* x, const float* g, float* out, int M, int d, float eps, hipStream_t st);
 hipError_t fc_gemm_plain(const void* W, int dt, int K, int NP, int N, const float* X, int ldx, float* Y, int ldy,
                          int M, int accumulate, hipStream_t st);
-hipError_t fc_rope_cache_plain(float* qkv, const KernelDims& kd, int layer, const int32_t* n_state,
+hipError_t fc_rope_cache_plain(const float* qkv, float* qrot, const KernelDims& kd, int layer, const int32_t* n_state,
                                const float* cosT, const float* sinT, void* kc, void* vc, int dt, hipStream_t st);
 hipError_t fc_attn_plain(const float* q, int ldq, const void* kc, const void* vc, int dt, const KernelDims& kd,
                          int layer, const int32_t* n_state, float* out, hipStream_t st);
@@ -22,7 +22,7 @@ hipError_t fc_accept_commit(int32_t* state, const StateMap& sm, int B, int W, in
 
 // ---- weight packing
 hipError_t fc_pack(const void* src, int dt, int rows, int cols, void* dst_base, const FusedMat& fm, int col_off,
-                   int gate_up /*0 none, 1 gate, 2 up*/, hipStream_t st);
+                   int mode /*0 natural, 1 gate, 2 up, 3 + Dh: q/k heads of Dh*/, hipStream_t st);
 hipError_t fc_fill_f32(float* dst, size_t n, float v, hipStream_t st);
 hipError_t fc_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t st);
 hipError_t fc_kv_scatter(const void* k, const void* v, int S_in, int Hkv, int Dh, int S, int dt, void* kc, void* vc,

@@ -98,26 +98,29 @@ hipError_t fc_gemm_plain(const void* W, int dt, int K, int NP, int N, const floa
 }
 
 // ------------------------------------------------------------------ rotary embedding + KV-cache write
-// Row m = b*W + j sits at absolute position n[b] + j.  q heads are rotated in place; k heads are
-// rotated and stored to the K cache, v heads stored to the transposed V cache.
+// Row m = b*W + j sits at absolute position n[b] + j.  The GEMM output row is in packed column
+// order (head_col); rotated q goes to qrot in natural order, k heads are rotated and stored to the
+// K cache, v heads stored to the transposed V cache.
 template <int DT>
-__global__ void k_rope_cache(float* qkv, KernelDims kd, int layer, const int32_t* n_state, const float* cosT,
-                             const float* sinT, void* kc, void* vc) {
+__global__ void k_rope_cache(const float* qkv, float* qrot, KernelDims kd, int layer, const int32_t* n_state,
+                             const float* cosT, const float* sinT, void* kc, void* vc) {
     int m = blockIdx.x, b = m / kd.W, j = m % kd.W;
     int pos = n_state[b] + j;
     if (pos >= kd.S) return;  // capacity guard: never write outside the cache
     int half = kd.Dh / 2;
     const size_t plane = (size_t)kd.S * kd.Dh;
-    float* row = qkv + (size_t)m * kd.qkvN;
+    const float* row = qkv + (size_t)m * kd.qkvN;
     int nrot = (kd.H + kd.Hkv) * half;
     for (int i = threadIdx.x; i < nrot; i += blockDim.x) {
         int hh = i / half, e = i % half;
         float c = cosT[(size_t)pos * half + e], s = sinT[(size_t)pos * half + e];
-        float* v = row + (size_t)hh * kd.Dh;
-        float a = v[e], bb = v[e + half];
+        const float* v = row + (size_t)hh * kd.Dh;
+        float a = v[head_col(e, kd.Dh)], bb = v[head_col(e + half, kd.Dh)];
         float ra = a * c - bb * s, rb = bb * c + a * s;
-        if (hh < kd.H) { v[e] = ra; v[e + half] = rb; }
-        else {
+        if (hh < kd.H) {
+            float* q = qrot + (size_t)m * kd.H * kd.Dh + (size_t)hh * kd.Dh;
+            q[e] = ra; q[e + half] = rb;
+        } else {
             int kh = hh - kd.H;
             size_t base = kv_block(kd, layer, b, kh) + (size_t)pos * kd.Dh;
             kvstore<DT>(kc, base + e, plane, kd.kvp, ra);
@@ -131,10 +134,10 @@ __global__ void k_rope_cache(float* qkv, KernelDims kd, int layer, const int32_t
         kvstore<DT>(vc, base, plane, kd.kvp, vrow[i]);
     }
 }
-hipError_t fc_rope_cache_plain(float* qkv, const KernelDims& kd, int layer, const int32_t* n_state,
+hipError_t fc_rope_cache_plain(const float* qkv, float* qrot, const KernelDims& kd, int layer, const int32_t* n_state,
                                const float* cosT, const float* sinT, void* kc, void* vc, int dt, hipStream_t st) {
-    if (dt == FASTCOT_F32) k_rope_cache<FASTCOT_F32><<<kd.M, 256, 0, st>>>(qkv, kd, layer, n_state, cosT, sinT, kc, vc);
-    else k_rope_cache<FASTCOT_BF16><<<kd.M, 256, 0, st>>>(qkv, kd, layer, n_state, cosT, sinT, kc, vc);
+    if (dt == FASTCOT_F32) k_rope_cache<FASTCOT_F32><<<kd.M, 256, 0, st>>>(qkv, qrot, kd, layer, n_state, cosT, sinT, kc, vc);
+    else k_rope_cache<FASTCOT_BF16><<<kd.M, 256, 0, st>>>(qkv, qrot, kd, layer, n_state, cosT, sinT, kc, vc);
     return hipGetLastError();
 }
 
@@ -228,23 +231,24 @@ hipError_t fc_argmax_plain(const float* logits, int M, int V, int32_t* ids, floa
 }
 
 // ------------------------------------------------------------------ packing
-// canonical [rows][cols] -> fused matrix columns col_off + map(c); gate_up selects the interleave.
+// canonical [rows][cols] -> fused matrix columns; mode selects the column map: 0 natural at col_off,
+// 1 / 2 gate / up interleave, 3 + Dh rotary-pair order inside heads of Dh columns (q and k heads).
 template <int DT>
-__global__ void k_pack(const void* src, int rows, int cols, void* dst, FusedMat fm, int col_off, int gate_up) {
+__global__ void k_pack(const void* src, int rows, int cols, void* dst, FusedMat fm, int col_off, int mode) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (size_t)rows * cols) return;
     int k = (int)(i / cols), c = (int)(i % cols);
-    int n = gate_up ? gu_col(c, gate_up - 1) : col_off + c;
+    int n = mode == 0 ? col_off + c : (mode <= 2 ? gu_col(c, mode - 1) : qkv_col(col_off + c, mode - 3, 0x7fffffff));
     char* base = (char*)dst + fm.off;
     if (DT == FASTCOT_F32) ((float*)base)[(size_t)k * fm.NP + n] = ((const float*)src)[i];
     else ((bf16_t*)base)[frag_index(fm.K, k, n)] = ((const bf16_t*)src)[i];
 }
 hipError_t fc_pack(const void* src, int dt, int rows, int cols, void* dst_base, const FusedMat& fm, int col_off,
-                   int gate_up, hipStream_t st) {
+                   int mode, hipStream_t st) {
     size_t n = (size_t)rows * cols;
     unsigned blocks = (unsigned)((n + 255) / 256);
-    if (dt == FASTCOT_F32) k_pack<FASTCOT_F32><<<blocks, 256, 0, st>>>(src, rows, cols, dst_base, fm, col_off, gate_up);
-    else k_pack<FASTCOT_BF16><<<blocks, 256, 0, st>>>(src, rows, cols, dst_base, fm, col_off, gate_up);
+    if (dt == FASTCOT_F32) k_pack<FASTCOT_F32><<<blocks, 256, 0, st>>>(src, rows, cols, dst_base, fm, col_off, mode);
+    else k_pack<FASTCOT_BF16><<<blocks, 256, 0, st>>>(src, rows, cols, dst_base, fm, col_off, mode);
     return hipGetLastError();
 }
 

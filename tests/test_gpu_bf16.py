@@ -33,13 +33,17 @@ def setup(fc, shape, B, S, W):
     return fc.Context(cfg, packed), oracle.model_from_synth(shape)
 
 
+@pytest.mark.parametrize("persistent", [0, 1])
 @pytest.mark.parametrize("shape,B,W,P", [(SMALL, 1, 16, 45), (SMALL, 2, 16, 33), (SMALL_MHA, 1, 8, 20),
                                          (SMALL, 1, 32, 70), (SMALL_MHA, 3, 5, 12)])
-def test_follow_mode_small_models(fc, shape, B, W, P):
-    say(f"bf16 follow shape d={shape.d_model} B={B} W={W} P={P}")
+def test_follow_mode_small_models(fc, shape, B, W, P, persistent):
+    if persistent and B * W > 16:
+        pytest.skip("the persistent kernel covers at most 16 rows per step")
+    say(f"bf16 follow shape d={shape.d_model} B={B} W={W} P={P} persistent={persistent}")
     N = 48
     S = ((P + N + 2 * W + 31) // 32) * 32
     ctx, om = setup(fc, shape, B, S, W)
+    ctx.set_option(4, persistent)
     lens = [P - 3 * b for b in range(B)]
     prompts = synthgen.prompts(B, P, shape.vocab, seed=21)
     buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=22)
