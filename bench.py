@@ -166,7 +166,11 @@ def main():
         b = wb.get(kind)
         table.append((kind, ms, cnt, b))
         log(f"kernel {kind:14s} {cnt:4d}/step  {ms * 1e3:9.2f} us" + (f"  {b / (ms * 1e-3) / 1e9:7.0f} GB/s" if b else ""))
-    dom = max((t for t in table if t[3]), key=lambda t: t[1] * t[2])
+    cands = [t for t in table if t[3]]
+    if not cands:      # persistent kernel: the whole step is one launch
+        ms, cnt = prof["persistent_step"]
+        cands = [("persistent_step", ms, cnt, int(alg))]
+    dom = max(cands, key=lambda t: t[1] * t[2])
     achieved = dom[3] / (dom[1] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom[0], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,

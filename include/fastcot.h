@@ -139,6 +139,11 @@ enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLAN
         * the attention kernel */
        FASTCOT_OPT_SK_QKV = 16, FASTCOT_OPT_SK_O = 17, FASTCOT_OPT_SK_GU = 18, FASTCOT_OPT_SK_DOWN = 19,
        FASTCOT_OPT_SK_LM = 20, FASTCOT_OPT_ATTN_SPLITS = 21,
+       /* workgroups of the column-owner GEMM for QKV / O / gate-up / down / LM head (each owns
+        * at most 8 tiles of 16 columns); 0 selects the split-K kernel for that GEMM */
+       FASTCOT_OPT_NW_QKV = 22, FASTCOT_OPT_NW_O = 23, FASTCOT_OPT_NW_GU = 24, FASTCOT_OPT_NW_DOWN = 25,
+       FASTCOT_OPT_NW_LM = 26,
+       FASTCOT_OPT_CO_SINGLE = 27,   /* 1: one weight batch in flight per wave (two workgroups per CU) */
        /* debug: run only the first `value` stages of a forward (per layer: QKV, attention, O,
         * gate/up, down); negative = all */
        FASTCOT_OPT_DEBUG_STAGES = 30 };

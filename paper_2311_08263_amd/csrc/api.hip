@@ -120,7 +120,7 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
         fc_fast_scratch_sizes(k, &wm->gemm_part_bytes, &wm->attn_part_bytes);
         wm->gemm_part = take(wm->gemm_part_bytes); wm->gemm_cnt = take(FC_MAX_COUNTERS * 4);
         wm->attn_part = take(wm->attn_part_bytes); wm->attn_cnt = take(FC_MAX_COUNTERS * 4);
-        wm->amax_part = take((M > 32 ? M : 32) * (size_t)((k.V + 127) / 128) * 8);
+        wm->amax_part = take((size_t)(k.V / 16 + 8) * 32 * 8);     // winners per column group / per workgroup
         StateMap s; int w = 0;
         auto ti = [&](int words) { int o = w; w += (words + 3) & ~3; return o; };
         s.n = ti(k.B); s.g = ti(k.B); s.done = ti(k.B); s.steps = ti(k.B); s.newest = ti(k.B); s.lastK = ti(k.B);
@@ -255,7 +255,14 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
         if (value < 1 || value > FC_MAX_SK || value > NU || (NU + value - 1) / value > 4)
             return fail(c, FASTCOT_EINVAL, "split-K out of range: slices must hold 1..4 units of 256 inputs%s");
         gp[option - FASTCOT_OPT_SK_QKV]->sk = value;
-    } else if (option == FASTCOT_OPT_ATTN_SPLITS) {
+    } else if (option >= FASTCOT_OPT_NW_QKV && option <= FASTCOT_OPT_NW_LM) {
+        const int nts[5] = {c->kd.qkvN / 16, c->kd.d / 16, 2 * c->kd.F / 16, c->kd.d / 16, c->kd.V / 16};
+        const int NT = nts[option - FASTCOT_OPT_NW_QKV];
+        if (value < 0 || value > NT || (value > 0 && (NT + value - 1) / value > 8))
+            return fail(c, FASTCOT_EINVAL, "workgroups of the column-owner GEMM: 0 (split-K kernel) or NT/8 .. NT%s");
+        c->plan.nw[option - FASTCOT_OPT_NW_QKV] = value;
+    } else if (option == FASTCOT_OPT_CO_SINGLE) c->plan.co_single = value != 0;
+    else if (option == FASTCOT_OPT_ATTN_SPLITS) {
         if (value < 1 || value > FC_MAX_ATTN_SPLITS) return fail(c, FASTCOT_EINVAL, "attention splits out of range%s");
         c->plan.attn_splits = value;
     }

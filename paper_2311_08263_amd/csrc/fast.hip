@@ -5,6 +5,7 @@
 #include "gemm16.h"
 #include "attn16.h"
 #include "persist.h"
+#include "gemmco.h"
 
 enum { KK_EMBED = 0, KK_QKV = 2, KK_ATTN = 4, KK_O = 5, KK_GU = 6, KK_DOWN = 8, KK_LM = 9, KK_ARGMAX = 10 };
 
@@ -40,6 +41,13 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     if (sp > FC_MAX_ATTN_SPLITS) sp = FC_MAX_ATTN_SPLITS;
     while (sp > 1 && kd.B * kd.H * sp > 2048) --sp;
     p->attn_splits = sp < 1 ? 1 : sp;
+    // column-owner kernel: workgroups per GEMM (one per CU where the matrix allows)
+    const int nts[5] = {kd.qkvN / 16, kd.d / 16, 2 * kd.F / 16, kd.d / 16, kd.V / 16};
+    // measured on the 7B shape: one workgroup per CU, one weight batch in flight per wave; the O
+    // projection (few columns, short K) is faster through the split-K kernel
+    for (int i = 0; i < 5; ++i) p->nw[i] = fc_gemmco_grid(nts[i]);
+    p->nw[1] = 0;
+    p->co_single = 1;
 }
 
 void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t* attn_part_bytes) {
@@ -80,8 +88,20 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     at.q = q; at.ldq = qd; at.kc = g.kc; at.vc = g.vc; at.B = kd.B; at.H = kd.H; at.Hkv = kd.Hkv; at.S = kd.S; at.W = kd.W; at.kvp = kd.kvp;
     at.n_state = g.n_state; at.out = att; at.ldo = qd; at.part = (float*)(ws + wm.attn_part); at.cnt = (int32_t*)(ws + wm.attn_cnt);
 
+    GemmCoArgs co; memset(&co, 0, sizeof(co));
+    co.M = M; co.eps = kd.eps; co.n_state = g.n_state; co.cosT = g.cosT; co.sinT = g.sinT; co.kc = g.kc; co.vc = g.vc;
+    co.H = kd.H; co.Hkv = kd.Hkv; co.B = kd.B; co.S = kd.S; co.Wn = kd.W; co.kvp = kd.kvp;
+    co.amax_val = g.amax_val; co.single_buffer = a.plan->co_single;
+    int gi = 0;        // which GEMM of the plan
     auto gemm = [&](int epi, const GemmPlan& pl, const void* W, int K, int N, const float* X, int ldx, const float* gain,
                     float* out, int ldo) {
+        const int nw = M <= 16 ? a.plan->nw[gi] : 0;      // workgroups of the column-owner kernel, 0 = split-K kernel
+        if (nw > 0) {
+            co.W = (const bf16_t*)W; co.K = K; co.NT = N / 16; co.X = X; co.ldx = ldx; co.gain = gain; co.out = out; co.ldo = ldo;
+            co.layer = g.layer;
+            co.amax_idx = (int32_t*)(co.amax_val + (size_t)nw * 16);
+            return fc_gemmco(epi, co, nw, a.st);
+        }
         g.W = (const bf16_t*)W; g.K = K; g.NT = N / 16; g.sk = pl.sk; g.X = X; g.ldx = ldx; g.gain = gain; g.out = out; g.ldo = ldo;
         // partial row sums live right after the partial tiles of this launch
         g.sspart = g.part + (size_t)pl.ncg * pl.sk * 8 * (M > 16 ? 2 : 1) * 256;
@@ -95,22 +115,29 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         const char* lb = wt + mm.layers_off + (size_t)l * mm.layer_stride;
         g.layer = l; at.layer = l;
         DBG_STOP();
+        gi = 0;
         FLAUNCH(KK_QKV, gemm(EPI_QKV, a.plan->qkv, lb + mm.qkv.off, d, kd.qkvN, x, d, (const float*)(lb + mm.g1_off), q, qd));
         DBG_STOP();
         FLAUNCH(KK_ATTN, fc_attn16(at, a.Bact, a.plan->attn_splits, a.st));
         DBG_STOP();
+        gi = 1;
         FLAUNCH(KK_O, gemm(EPI_RESID, a.plan->o, lb + mm.o.off, qd, d, att, qd, nullptr, x, d));
         DBG_STOP();
+        gi = 2;
         FLAUNCH(KK_GU, gemm(EPI_SWIGLU, a.plan->gu, lb + mm.gu.off, d, 2 * kd.F, x, d, (const float*)(lb + mm.g2_off), h, kd.F));
         DBG_STOP();
+        gi = 3;
         FLAUNCH(KK_DOWN, gemm(EPI_RESID, a.plan->down, lb + mm.down.off, kd.F, d, h, kd.F, nullptr, x, d));
     }
     if (a.dbg_stop >= 0 && nstage >= a.dbg_stop) return hipSuccess;
     if (a.lmhead) {
         const int stride = M > 16 ? 32 : 16;
-        g.amax_idx = (int32_t*)(g.amax_val + (size_t)a.plan->lm.ncg * stride);
+        const int nwlm = M <= 16 ? a.plan->nw[4] : 0;
+        const int nwin = nwlm > 0 ? nwlm : a.plan->lm.ncg;    // partial winners to reduce
+        g.amax_idx = (int32_t*)(g.amax_val + (size_t)nwin * stride);
+        gi = 4;
         FLAUNCH(KK_LM, gemm(EPI_LMHEAD, a.plan->lm, wt + mm.lm.off, d, kd.V, x, d, (const float*)(wt + mm.gf_off), a.dbg_logits, kd.V));
-        FLAUNCH(KK_ARGMAX, fc_argmax_final(g.amax_val, g.amax_idx, a.plan->lm.ncg, stride, M, stp + wm.st.o,
+        FLAUNCH(KK_ARGMAX, fc_argmax_final(g.amax_val, g.amax_idx, nwin, stride, M, stp + wm.st.o,
                                            (float*)(ws + wm.topv), a.st));
     }
     return hipSuccess;
@@ -158,6 +185,16 @@ hipError_t fc_lmhead_iso(const float* act, const void* packed, int M, int d, int
         hipError_t e = fc_gemm_plain(packed, FASTCOT_BF16, d, V, V, act, d, lg, V, M, 0, st);
         if (e != hipSuccess) return e;
         return fc_argmax_plain(lg, M, V, ids, top, st);
+    }
+    if (M <= 16) {
+        GemmCoArgs co; memset(&co, 0, sizeof(co));
+        const int nwg = fc_gemmco_grid(V / 16), nw = nwg;
+        co.W = (const bf16_t*)packed; co.K = d; co.NT = V / 16; co.X = act; co.ldx = d; co.M = M; co.out = logits; co.ldo = V;
+        co.amax_val = (float*)(sc + cnt_bytes + (size_t)ncg * 32 * 8 + 256);      // the partial-tile area is free here
+        co.amax_idx = (int32_t*)(co.amax_val + (size_t)nwg * 16);
+        hipError_t e = fc_gemmco(EPI_LMHEAD, co, nw, st);
+        if (e != hipSuccess) return e;
+        return fc_argmax_final(co.amax_val, co.amax_idx, nwg, 16, M, ids, top, st);
     }
     Gemm16Args g; memset(&g, 0, sizeof(g));
     const int stride = M > 16 ? 32 : 16, sk = choose_sk(d, ncg);

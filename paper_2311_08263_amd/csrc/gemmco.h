@@ -1,0 +1,24 @@
+// Argument block and launcher of the column-owner weight-streaming GEMM (see gemmco.hip).
+#pragma once
+#include "gemm16.h"
+
+struct GemmCoArgs {
+    const bf16_t* W;       // fused matrix in fragment order
+    int32_t K, NT;         // inputs (multiple of 256), n-tiles
+    const float* X;        // activations fp32 [M][ldx]
+    int32_t ldx, M;
+    const float* gain;     // RMSNorm gain [K]; NULL = no norm in front of this GEMM
+    float eps;
+    float* out;            // RESID: residual stream (+=); SWIGLU: hidden [M][F]; QKV: q [M][H*128]; LMHEAD: logits or NULL
+    int32_t ldo;
+    const int32_t* n_state; const float* cosT; const float* sinT;
+    bf16_t* kc; bf16_t* vc;
+    int32_t layer, H, Hkv, B, S, Wn, kvp;
+    float* amax_val; int32_t* amax_idx;   // LM head: winners per workgroup [workgroups][16]
+    int32_t single_buffer; // one batch in flight per wave (fewer registers: two workgroups per CU) instead of two
+};
+
+// G workgroups; workgroup i owns n-tiles [i*NT/G, (i+1)*NT/G), at most 8; fc_gemmco_grid picks one
+// workgroup per CU (all resident, one round) unless the matrix is wider than 8 n-tiles per CU
+int fc_gemmco_grid(int NT);
+hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st);

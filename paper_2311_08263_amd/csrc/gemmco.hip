@@ -1,0 +1,319 @@
+// Column-owner weight-streaming bf16 GEMM for up to 16 activation rows.
+//
+// A workgroup of 8 waves owns NW n-tiles (16 output columns each) over the whole of K; wave w
+// takes the w-th eighth of K.  No workgroup ever needs another workgroup's result: the eight
+// partial tiles meet in LDS, then waves 0..NW-1 each finish one tile and run the fused epilogue.
+// Compared with slicing K across workgroups this trades the global hand-off (partial tiles through
+// memory, an atomic counter, a second pass by the last arriver) for more activation reads out of
+// L2: every workgroup reads all 16 x K activations, straight into registers in MFMA B-fragment
+// order (lane = row % 16 + 16 * k-octet: two 16-byte loads per k-tile), converts them to a bf16
+// hi + lo pair and reuses each fragment for its NW weight tiles.  Weights stream HBM -> VGPR once,
+// in MFMA fragment order, KB k-tiles x NW n-tiles per batch.
+#include "gemmco.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
+union Frag { u32x4_t u; bf16x8_t v; };
+
+__device__ inline uint32_t rne16(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ inline float up16(uint32_t b) { return __uint_as_float(b << 16); }
+
+// One batch = KB k-tiles: the wave's weight tiles for its n-tiles and its activation octets.
+template <int NW, int KB> struct Batch {
+    u32x4_t wt[NW][KB];
+    float4 xa[KB][2];
+};
+
+template <int EPI, int NW, int KB, bool DB>
+__global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
+    extern __shared__ float lds[];
+    f32x4_t* lds_part = (f32x4_t*)lds;                  // [8 waves][NW][64 lanes]
+    float* lds_ss = lds + 8 * NW * 256;                 // [8][16]
+    float* lds_amv = lds_ss + 8 * 16;                   // [8][16]
+    int* lds_ami = (int*)(lds_amv + 8 * 16);            // [8][16]
+    float* lds_gain = (float*)(lds_ami + 8 * 16);       // [K] (only with a norm in front)
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int lm = lane & 15, g4 = lane >> 4;
+    // workgroup i owns n-tiles [i*NT/G, (i+1)*NT/G): at most NW of them
+    const int G = gridDim.x;
+    const int nt0 = (int)(((unsigned)blockIdx.x * (unsigned)a.NT) / (unsigned)G);
+    const int nt1 = (int)(((unsigned)(blockIdx.x + 1) * (unsigned)a.NT) / (unsigned)G);
+    const int KT = a.K >> 5, KTw = KT >> 3;
+    const int kt_begin = w * KTw, kt_end = kt_begin + KTw;
+    const int nb = (KTw + KB - 1) / KB;
+    const int row = lm < a.M ? lm : a.M - 1;            // rows past M repeat a valid row; never written
+    const float* xr = a.X + (size_t)row * a.ldx + 8 * g4;
+    const u32x4_t* wbase = (const u32x4_t*)a.W + lane;
+
+    // All loads are unconditional (a conditionally loaded register batch would be copied, and a copy
+    // waits for every load in flight): past the end of the slice, or for n-tiles this workgroup does
+    // not own, the address falls back to the first tile of the matrix (cached), and the activations
+    // of such k-tiles are zeroed at use.
+    auto load = [&](Batch<NW, KB>& b, int ib) {
+#pragma unroll
+        for (int t = 0; t < KB; ++t) {
+            const int kt = kt_begin + ib * KB + t;
+            const bool kv = ib < nb && kt < kt_end;
+#pragma unroll
+            for (int j = 0; j < NW; ++j) {
+                const bool v = kv && nt0 + j < nt1;
+                b.wt[j][t] = __builtin_nontemporal_load(wbase + (v ? ((size_t)(nt0 + j) * KT + kt) * 64 : 0));
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < KB; ++t) {
+            const int kt = kt_begin + ib * KB + t;
+            const int kc = (ib < nb && kt < kt_end) ? kt : kt_begin;
+            b.xa[t][0] = *(const float4*)(xr + kc * 32);
+            b.xa[t][1] = *(const float4*)(xr + kc * 32 + 4);
+        }
+    };
+
+    f32x4_t acc[NW];
+#pragma unroll
+    for (int j = 0; j < NW; ++j) acc[j] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    float ss = 0.f;
+
+    auto compute = [&](const Batch<NW, KB>& b, int ib) {
+#pragma unroll
+        for (int t = 0; t < KB; ++t) {
+            const int kt = kt_begin + ib * KB + t;
+            const float keep = (ib < nb && kt < kt_end) ? 1.0f : 0.0f;
+            float v[8] = {b.xa[t][0].x, b.xa[t][0].y, b.xa[t][0].z, b.xa[t][0].w, b.xa[t][1].x, b.xa[t][1].y, b.xa[t][1].z, b.xa[t][1].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { v[e] *= keep; ss += v[e] * v[e]; }
+            if (a.gain) {
+                const int kc = keep != 0.0f ? kt : kt_begin;
+                const float4 g0 = *(const float4*)(lds_gain + kc * 32 + 8 * g4), g1 = *(const float4*)(lds_gain + kc * 32 + 8 * g4 + 4);
+                v[0] *= g0.x; v[1] *= g0.y; v[2] *= g0.z; v[3] *= g0.w; v[4] *= g1.x; v[5] *= g1.y; v[6] *= g1.z; v[7] *= g1.w;
+            }
+            uint32_t h[8], l[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { h[e] = rne16(v[e]); l[e] = rne16(v[e] - up16(h[e])); }
+            Frag hi, lo;
+            hi.u = (u32x4_t){h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+            lo.u = (u32x4_t){l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+#pragma unroll
+            for (int j = 0; j < NW; ++j) {
+                Frag wf; wf.u = b.wt[j][t];
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, hi.v, acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, lo.v, acc[j], 0, 0, 0);
+            }
+        }
+    };
+
+    // two batches in flight per wave: the next one is requested before the current one is used
+    // (DB = false keeps one batch per wave in flight and fewer registers, so that two workgroups
+    // share a CU and overlap each other's phases instead)
+    Batch<NW, KB> A;
+    load(A, 0);
+    if (DB) {
+        Batch<NW, KB> B;
+        load(B, 1);
+        if (a.gain) {       // the norm gain goes through LDS once per workgroup
+            for (int i = tid * 4; i < a.K; i += 512 * 4) *(float4*)(lds_gain + i) = *(const float4*)(a.gain + i);
+            __syncthreads();
+        }
+        for (int ib = 0; ib < nb; ib += 2) {
+            compute(A, ib);
+            load(A, ib + 2);
+            compute(B, ib + 1);
+            load(B, ib + 3);
+        }
+    } else {
+        if (a.gain) {
+            for (int i = tid * 4; i < a.K; i += 512 * 4) *(float4*)(lds_gain + i) = *(const float4*)(a.gain + i);
+            __syncthreads();
+        }
+        for (int ib = 0; ib < nb; ++ib) {
+            compute(A, ib);
+            load(A, ib + 1);
+        }
+    }
+
+    // the eight K slices meet in LDS
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (g4 == 0) lds_ss[w * 16 + lm] = ss;
+#pragma unroll
+    for (int j = 0; j < NW; ++j) lds_part[(w * NW + j) * 64 + lane] = acc[j];
+    __syncthreads();
+
+    // waves 0..NW-1 finish one tile each: lane holds row lm, columns nt*16 + 4*g4 + r
+    const int nt = nt0 + w;
+    const bool fin = w < NW && nt < nt1;
+    f32x4_t v = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    float rs = 1.0f;
+    if (fin) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v += lds_part[(q * NW + w) * 64 + lane];
+        if (a.gain) {
+            float s = 0.f;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) s += lds_ss[q * 16 + lm];
+            rs = 1.0f / sqrtf(s / (float)a.K + a.eps);
+        }
+        v *= rs;
+    }
+    const int m = lm;
+    if (EPI == EPI_RESID) {
+        if (fin && m < a.M) {
+            f32x4_t* o = (f32x4_t*)(a.out + (size_t)m * a.ldo + nt * 16 + 4 * g4);
+            *o = *o + v;
+        }
+    } else if (EPI == EPI_SWIGLU) {
+        // columns 0..7 of a tile: gate of features 8*nt..; columns 8..15: their up values (lane ^ 32)
+        if (fin) {
+            f32x4_t h;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float other = __shfl_xor(v[r], 32, 64);
+                h[r] = v[r] / (1.0f + expf(-v[r])) * other;
+            }
+            if (g4 < 2 && m < a.M) *(f32x4_t*)(a.out + (size_t)m * a.ldo + nt * 8 + 4 * g4) = h;
+        }
+    } else if (EPI == EPI_QKV) {
+        // q/k heads: tile t of a head holds elements 8t..8t+7 (columns 0..7) and their rotary partners
+        // 64+8t.. (columns 8..15, lane ^ 32); v heads are in natural order
+        if (fin) {
+            const int hh = nt >> 3, t = nt & 7;
+            const int b = m / a.Wn, j = m % a.Wn;
+            const int pos = m < a.M ? a.n_state[b] + j : a.S;
+            const bool ok = m < a.M && pos < a.S;               // capacity guard
+            const size_t plane = (size_t)a.S * 128;
+            if (hh < a.H + a.Hkv) {
+                const int i0 = 8 * t + 4 * (g4 & 1);            // element index within the half
+                f32x4_t r;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float other = __shfl_xor(v[e], 32, 64);
+                    const float c = ok ? a.cosT[(size_t)pos * 64 + i0 + e] : 1.0f;
+                    const float s = ok ? a.sinT[(size_t)pos * 64 + i0 + e] : 0.0f;
+                    r[e] = g4 < 2 ? v[e] * c - other * s : v[e] * c + other * s;
+                }
+                const int el = (g4 < 2 ? 0 : 64) + i0;          // element index within the head
+                if (ok) {
+                    if (hh < a.H) *(f32x4_t*)(a.out + (size_t)m * a.ldo + hh * 128 + el) = r;
+                    else {
+                        bf16_t* kr = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + (hh - a.H)) * a.kvp) * plane + (size_t)pos * 128 + el;
+                        uint32_t h[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) h[e] = rne16(r[e]);
+                        *(uint2*)kr = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                        if (a.kvp == 2) {
+                            uint32_t l[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) l[e] = rne16(r[e] - up16(h[e]));
+                            *(uint2*)(kr + plane) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+                        }
+                    }
+                }
+            } else if (ok) {
+                const int kh = hh - a.H - a.Hkv;
+                bf16_t* vr = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + (size_t)(16 * t + 4 * g4) * a.S + pos;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t h0 = rne16(v[e]);
+                    vr[(size_t)e * a.S] = (bf16_t)h0;
+                    if (a.kvp == 2) vr[(size_t)e * a.S + plane] = (bf16_t)rne16(v[e] - up16(h0));
+                }
+            }
+        }
+    } else if (EPI == EPI_LMHEAD) {
+        float best = -3.0e38f; int bi = 0x7fffffff;
+        if (fin) {
+            const int n0 = nt * 16 + 4 * g4;
+            if (a.out && m < a.M) *(f32x4_t*)(a.out + (size_t)m * a.ldo + n0) = v;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) if (v[r] > best) { best = v[r]; bi = n0 + r; }
+#pragma unroll
+            for (int o = 16; o <= 32; o <<= 1) {
+                const float ov = __shfl_xor(best, o, 64); const int oi = __shfl_xor(bi, o, 64);
+                if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+            }
+        }
+        if (g4 == 0) { lds_amv[w * 16 + lm] = best; lds_ami[w * 16 + lm] = bi; }
+        __syncthreads();
+        if (tid < 16) {
+            float bv = lds_amv[tid]; int bx = lds_ami[tid];
+#pragma unroll
+            for (int q = 1; q < 8; ++q) {
+                const float ov = lds_amv[q * 16 + tid]; const int oi = lds_ami[q * 16 + tid];
+                if (ov > bv || (ov == bv && oi < bx)) { bv = ov; bx = oi; }
+            }
+            a.amax_val[(size_t)blockIdx.x * 16 + tid] = bv;
+            a.amax_idx[(size_t)blockIdx.x * 16 + tid] = bx;
+        }
+    }
+}
+
+static int g_cus = 0;
+static int num_cus() {
+    if (!g_cus) {
+        int dev = 0; hipDeviceProp_t p;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess) g_cus = p.multiProcessorCount;
+        if (g_cus <= 0) g_cus = 256;
+    }
+    return g_cus;
+}
+
+// grid: one workgroup per CU unless that would give a workgroup more than 8 n-tiles
+int fc_gemmco_grid(int NT) {
+    int G = num_cus();
+    if (G > NT) G = NT;
+    while ((NT + G - 1) / G > 8) G += num_cus();
+    return G;
+}
+
+template <int EPI, int NW, int KB, bool DB>
+static hipError_t launch_k(const GemmCoArgs& a, int G, hipStream_t st) {
+    const size_t lds = (size_t)8 * NW * 1024 + 3 * 8 * 16 * 4 + (a.gain ? (size_t)a.K * 4 : 0) + 64;
+    static bool raised = false;
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute((const void*)k_gemmco<EPI, NW, KB, DB>, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    if (lds > 150 * 1024) return hipErrorInvalidValue;
+    k_gemmco<EPI, NW, KB, DB><<<G, 512, lds, st>>>(a);
+    return hipGetLastError();
+}
+template <int EPI>
+static hipError_t launch_epi(const GemmCoArgs& a, int G, hipStream_t st) {
+    const int nw = (a.NT + G - 1) / G;           // most n-tiles any workgroup owns
+    if (a.single_buffer) {
+        switch (nw) {
+            case 1: return launch_k<EPI, 1, 8, false>(a, G, st);
+            case 2: return launch_k<EPI, 2, 4, false>(a, G, st);
+            case 3: return launch_k<EPI, 3, 4, false>(a, G, st);
+            case 4: return launch_k<EPI, 4, 4, false>(a, G, st);
+            case 5: case 6: return launch_k<EPI, 6, 2, false>(a, G, st);
+            case 7: case 8: return launch_k<EPI, 8, 2, false>(a, G, st);
+        }
+        return hipErrorInvalidValue;
+    }
+    switch (nw) {
+        case 1: return launch_k<EPI, 1, 6, true>(a, G, st);
+        case 2: return launch_k<EPI, 2, 4, true>(a, G, st);
+        case 3: return launch_k<EPI, 3, 3, true>(a, G, st);
+        case 4: return launch_k<EPI, 4, 2, true>(a, G, st);
+        case 5: case 6: return launch_k<EPI, 6, 2, true>(a, G, st);
+        case 7: case 8: return launch_k<EPI, 8, 1, true>(a, G, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st) {
+    if (a.M < 1 || a.M > 16 || a.K % 256 || a.NT < 1 || G < 1 || G > a.NT || (a.NT + G - 1) / G > 8) return hipErrorInvalidValue;
+    switch (epi) {
+        case EPI_RESID: return launch_epi<EPI_RESID>(a, G, st);
+        case EPI_SWIGLU: return launch_epi<EPI_SWIGLU>(a, G, st);
+        case EPI_QKV: return launch_epi<EPI_QKV>(a, G, st);
+        case EPI_LMHEAD: return launch_epi<EPI_LMHEAD>(a, G, st);
+    }
+    return hipErrorInvalidValue;
+}
