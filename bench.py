@@ -22,6 +22,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain
+# copy kernel of known size (profiles/hbm_traffic_7b_w16.md); None where no counter run exists
+MEASURED_TRAFFIC = {("7b", "gemm_gate_up"): 183.4e6}
 WORKLOADS = {
     # name: (shape, batch, prompt, window, new tokens)
     "7b": ("7b", 1, 256, 16, 256),
@@ -92,6 +95,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-iters", type=int, default=3)
     ap.add_argument("--plain", action="store_true", help="time the plain kernels instead of the MFMA path")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device-to-device copy of 512 MiB (the known-size kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus above 1 is not supported "
@@ -158,6 +163,14 @@ def main():
     log(f"timed: {K} steps, {ms_per_step:.3f} ms/step, accepted {accepted_timed}, "
         f"algorithmic {alg / 1e9:.3f} GB/step -> {step_gbs:.0f} GB/s ({100 * step_gbs / HBM_PEAK_GBS:.1f}% of 8 TB/s)")
 
+    if args.calibrate_copy:
+        src = torch.ones(512 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        log("calibration copy: 536870912 bytes read, 536870912 bytes written")
+
     # ---- per-kernel launch durations (HIP events on the context's stream), dominant kernel roofline
     prof = ctx.profile_step(args.profile_iters)
     wb = weight_bytes_per_step(shape, esz)
@@ -173,7 +186,7 @@ def main():
     dom = max(cands, key=lambda t: t[1] * t[2])
     achieved = dom[3] / (dom[1] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom[0], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((args.workload, dom[0])),
                 "bytes_per_launch": dom[3], "avg_launch_ms": round(dom[1], 5),
                 "step_algorithmic_bytes": int(alg), "step_frac": round(step_gbs / HBM_PEAK_GBS, 4)}
 

@@ -46,7 +46,7 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     // measured on the 7B shape: one workgroup per CU, one weight batch in flight per wave; the O
     // projection (few columns, short K) is faster through the split-K kernel
     for (int i = 0; i < 5; ++i) p->nw[i] = fc_gemmco_grid(nts[i]);
-    p->nw[1] = 0;
+    if (nts[1] < 512) p->nw[1] = 0;     // fewer than two n-tiles per CU
     p->co_single = 1;
 }
 
