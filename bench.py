@@ -22,6 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain
 # copy kernel of known size (profiles/hbm_traffic_7b_w16.md); None where no counter run exists
 MEASURED_TRAFFIC = {("7b", "gemm_gate_up"): 183.4e6}
@@ -189,6 +190,16 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((args.workload, dom[0])),
                 "bytes_per_launch": dom[3], "avg_launch_ms": round(dom[1], 5),
                 "step_algorithmic_bytes": int(alg), "step_frac": round(step_gbs / HBM_PEAK_GBS, 4)}
+    if B * W > 32 and not args.plain:
+        # many rows: the GEMMs sit on the matrix-core side of the ridge (2 * rows flops per weight element
+        # against 2 bytes).  Algorithmic flops = 2 * rows * K * N of the dominant GEMM; the kernel issues
+        # twice that because activations enter as bf16 hi + lo.
+        flops = 2.0 * B * W * dom[3] / esz
+        tf = flops / (dom[1] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": dom[0], "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "flops_per_launch": flops, "issued_flops_per_launch": 2 * flops, "avg_launch_ms": round(dom[1], 5),
+                    "step_algorithmic_bytes": int(alg), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4)}
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -120,7 +120,10 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
         fc_fast_scratch_sizes(k, &wm->gemm_part_bytes, &wm->attn_part_bytes);
         wm->gemm_part = take(wm->gemm_part_bytes); wm->gemm_cnt = take(FC_MAX_COUNTERS * 4);
         wm->attn_part = take(wm->attn_part_bytes); wm->attn_cnt = take(FC_MAX_COUNTERS * 4);
-        wm->amax_part = take((size_t)(k.V / 16 + 8) * 32 * 8);     // winners per column group / per workgroup
+        {
+            size_t am = (size_t)(k.V / 16 + 8) * 32 * 8, am2 = (size_t)(k.V / 256 + 1) * ((M + 15) / 16 * 16) * 8;
+            wm->amax_part = take(am > am2 ? am : am2);
+        }     // winners per column group / per workgroup
         StateMap s; int w = 0;
         auto ti = [&](int words) { int o = w; w += (words + 3) & ~3; return o; };
         s.n = ti(k.B); s.g = ti(k.B); s.done = ti(k.B); s.steps = ti(k.B); s.newest = ti(k.B); s.lastK = ti(k.B);

@@ -6,11 +6,12 @@
 #include "attn16.h"
 #include "persist.h"
 #include "gemmco.h"
+#include "gemm256.h"
 
 enum { KK_EMBED = 0, KK_QKV = 2, KK_ATTN = 4, KK_O = 5, KK_GU = 6, KK_DOWN = 8, KK_LM = 9, KK_ARGMAX = 10 };
 
 bool fc_fast_supported(const KernelDims& kd, int rows) {
-    return kd.esz == 2 && kd.Dh == 128 && rows >= 1 && rows <= 32 && kd.W <= 32 && kd.d % 256 == 0 && kd.F % 256 == 0 &&
+    return kd.esz == 2 && kd.Dh == 128 && rows >= 1 && kd.W <= 32 && kd.d % 256 == 0 && kd.F % 256 == 0 &&
            (kd.H * kd.Dh) % 256 == 0 && kd.S % 32 == 0 && kd.V % 16 == 0;
 }
 
@@ -39,7 +40,7 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     p->lm = mk(kd.d, kd.V);
     int nb = (kd.S + 31) / 32, sp = (nb + 7) / 8;
     if (sp > FC_MAX_ATTN_SPLITS) sp = FC_MAX_ATTN_SPLITS;
-    while (sp > 1 && kd.B * kd.H * sp > 2048) --sp;
+    while (sp > 1 && kd.B * kd.H * sp > 768) --sp;     // measured (batch 8, 40 heads): 2 splits best, 6 are 40% slower
     p->attn_splits = sp < 1 ? 1 : sp;
     // column-owner kernel: workgroups per GEMM (one per CU where the matrix allows)
     const int nts[5] = {kd.qkvN / 16, kd.d / 16, 2 * kd.F / 16, kd.d / 16, kd.V / 16};
@@ -58,6 +59,11 @@ void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t
     const size_t ncg = (size_t)(nmax / 16 + 7) / 8;
     *gemm_part_bytes = ncg * FC_MAX_SK * (8 * 2 * 1024 + 2 * 16 * 4) + 4096;
     if (*gemm_part_bytes < fc_persist_part_bytes(kd)) *gemm_part_bytes = fc_persist_part_bytes(kd);
+    // many-row path: the split activations of one GEMM (widest input) live in the same scratch
+    int kmax = kd.F > kd.d ? kd.F : kd.d;
+    if (kd.H * kd.Dh > kmax) kmax = kd.H * kd.Dh;
+    const size_t big = fc_split_bytes(kd.M, kmax) + (size_t)FC_GEMM256_MAX_SK * kd.M * kd.d * 4 + 4096;
+    if (*gemm_part_bytes < big) *gemm_part_bytes = big;
     *attn_part_bytes = fc_attn16_part_bytes(kd.B * kd.H, FC_MAX_ATTN_SPLITS, kd.W) + 4096;
 }
 
@@ -92,6 +98,12 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     co.M = M; co.eps = kd.eps; co.n_state = g.n_state; co.cosT = g.cosT; co.sinT = g.sinT; co.kc = g.kc; co.vc = g.vc;
     co.H = kd.H; co.Hkv = kd.Hkv; co.B = kd.B; co.S = kd.S; co.Wn = kd.W; co.kvp = kd.kvp;
     co.amax_val = g.amax_val; co.single_buffer = a.plan->co_single;
+    Gemm256Args big; memset(&big, 0, sizeof(big));
+    big.M = M; big.n_state = g.n_state; big.cosT = g.cosT; big.sinT = g.sinT; big.kc = g.kc; big.vc = g.vc;
+    big.H = kd.H; big.Hkv = kd.Hkv; big.B = kd.B; big.S = kd.S; big.Wn = kd.W; big.kvp = kd.kvp;
+    big.amax_stride = (M + 15) / 16 * 16;
+    big.part = (float*)(ws + wm.gemm_part + ((fc_split_bytes(kd.M, kd.F > qd ? (kd.F > d ? kd.F : d) : (qd > d ? qd : d)) + 255) & ~(size_t)255));
+    big.amax_val = g.amax_val; big.amax_idx = (int32_t*)(g.amax_val + (size_t)((kd.V / 16 + 15) / 16) * big.amax_stride);
     int gi = 0;        // which GEMM of the plan
     auto gemm = [&](int epi, const GemmPlan& pl, const void* W, int K, int N, const float* X, int ldx, const float* gain,
                     float* out, int ldo) {
@@ -102,7 +114,17 @@ hipError_t fc_fast_forward(const FastArgs& a) {
             co.amax_idx = (int32_t*)(co.amax_val + (size_t)nw * 16);
             return fc_gemmco(epi, co, nw, a.st);
         }
-        g.W = (const bf16_t*)W; g.K = K; g.NT = N / 16; g.sk = pl.sk; g.X = X; g.ldx = ldx; g.gain = gain; g.out = out; g.ldo = ldo;
+        if (M > 32) {        // matrix-core bound: activations split once, tiles of 64 rows x 256 columns
+            bf16_t* af = (bf16_t*)(ws + wm.gemm_part);
+            hipError_t e = fc_split(X, ldx, M, K, gain, kd.eps, af, a.st);
+            if (e != hipSuccess) return e;
+            big.sk = epi == EPI_RESID ? fc_gemm256_sk(M, K, N / 16) : 1;
+            big.W = (const bf16_t*)W; big.K = K; big.NT = N / 16; big.AF = af; big.out = out; big.ldo = ldo; big.layer = g.layer;
+            return fc_gemm256(epi, big, a.st);
+        }
+        // split-K kernel, at most 32 rows
+        g.W = (const bf16_t*)W; g.K = K; g.NT = N / 16; g.sk = pl.sk; g.ldx = ldx; g.gain = gain; g.ldo = ldo;
+        g.M = M; g.m0 = 0; g.X = X; g.out = out;
         // partial row sums live right after the partial tiles of this launch
         g.sspart = g.part + (size_t)pl.ncg * pl.sk * 8 * (M > 16 ? 2 : 1) * 256;
         return fc_gemm16(epi, g, pl.ncg, a.st);
@@ -137,8 +159,12 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         g.amax_idx = (int32_t*)(g.amax_val + (size_t)nwin * stride);
         gi = 4;
         FLAUNCH(KK_LM, gemm(EPI_LMHEAD, a.plan->lm, wt + mm.lm.off, d, kd.V, x, d, (const float*)(wt + mm.gf_off), a.dbg_logits, kd.V));
-        FLAUNCH(KK_ARGMAX, fc_argmax_final(g.amax_val, g.amax_idx, nwin, stride, M, stp + wm.st.o,
-                                           (float*)(ws + wm.topv), a.st));
+        if (M <= 32)
+            FLAUNCH(KK_ARGMAX, fc_argmax_final(g.amax_val, g.amax_idx, nwin, stride, M, stp + wm.st.o,
+                                               (float*)(ws + wm.topv), a.st));
+        else
+            FLAUNCH(KK_ARGMAX, fc_argmax_final(big.amax_val, big.amax_idx, (kd.V / 16 + 15) / 16, big.amax_stride, M,
+                                               stp + wm.st.o, (float*)(ws + wm.topv), a.st));
     }
     return hipSuccess;
 }

@@ -9,7 +9,8 @@ struct Gemm16Args {
     int32_t K, NT;         // inputs, n-tiles (columns / 16)
     int32_t sk;            // K slices per column group
     const float* X;        // activations fp32 [M][ldx]
-    int32_t ldx, M;
+    int32_t ldx, M;        // M rows in this launch (<= 32); X and out already point at the first of them
+    int32_t m0;            // index of that first row in the step (row m0 + m belongs to sequence (m0 + m) / W)
     const float* gain;     // RMSNorm gain [K]; NULL = no norm in front of this GEMM
     float eps;
     float* part;           // split-K partial tiles

@@ -267,7 +267,7 @@ __global__ __launch_bounds__(512) void k_gemm16(Gemm16Args a) {
             for (int idx = tid; idx < MT * 16 * 64; idx += 512) {
                 const int m = idx >> 6, i = idx & 63;
                 if (m >= a.M) continue;
-                const int b = m / a.Wn, j = m % a.Wn;
+                const int b = (a.m0 + m) / a.Wn, j = (a.m0 + m) % a.Wn;
                 const int pos = a.n_state[b] + j;
                 if (pos >= a.S) continue;                       // capacity guard
                 const float c = a.cosT[(size_t)pos * 64 + i], s = a.sinT[(size_t)pos * 64 + i];
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(512) void k_gemm16(Gemm16Args a) {
             for (int idx = tid; idx < MT * 16 * 128; idx += 512) {
                 const int m = (idx & 15) + 16 * (idx >> 11), e = (idx >> 4) & 127;
                 if (m >= a.M) continue;
-                const int b = m / a.Wn, j = m % a.Wn;
+                const int b = (a.m0 + m) / a.Wn, j = (a.m0 + m) % a.Wn;
                 const int pos = a.n_state[b] + j;
                 if (pos >= a.S) continue;
                 bf16_t* vr = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + (size_t)e * a.S + pos;

@@ -1,0 +1,26 @@
+// Argument block and launchers of the many-row bf16 GEMM (see gemm256.hip).
+#pragma once
+#include "gemm16.h"
+
+struct Gemm256Args {
+    const bf16_t* W;       // fused matrix in fragment order
+    int32_t K, NT;         // inputs (multiple of 256), n-tiles
+    const bf16_t* AF;      // activations as bf16 hi + lo B-fragments [row tile][k-tile][hi|lo][64 lanes][8] (fc_split)
+    int32_t M;             // rows
+    float* out;            // RESID: residual stream (+=); SWIGLU: hidden [M][F]; QKV: q [M][H*128]; LMHEAD: logits or NULL
+    int32_t ldo;
+    const int32_t* n_state; const float* cosT; const float* sinT;
+    bf16_t* kc; bf16_t* vc;
+    int32_t layer, H, Hkv, B, S, Wn, kvp;
+    float* amax_val; int32_t* amax_idx;   // LM head: winners per column block of 256 [column blocks][amax_stride]
+    int32_t amax_stride;
+    int32_t sk;            // K slices (RESID only when > 1: partial tiles to `part`, then added in slice order)
+    float* part;           // [sk][M][NT*16] fp32
+};
+#define FC_GEMM256_MAX_SK 8
+int fc_gemm256_sk(int M, int K, int NT);   // slices that fill the chip for a matrix with few columns
+
+// X [M][ldx] fp32 -> AF; gain != NULL applies RMSNorm (fp32 statistics over the K inputs) first
+hipError_t fc_split(const float* X, int ldx, int M, int K, const float* gain, float eps, bf16_t* AF, hipStream_t st);
+static inline size_t fc_split_bytes(int M, int K) { return (size_t)((M + 15) / 16) * 16 * K * 4; }
+hipError_t fc_gemm256(int epi, const Gemm256Args& a, hipStream_t st);

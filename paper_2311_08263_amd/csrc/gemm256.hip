@@ -1,0 +1,322 @@
+// bf16 GEMM for steps with many rows (batch x window up to a few hundred): out = act . W with the
+// weights in MFMA fragment order and the activations pre-split into bf16 hi + lo fragments.
+//
+// At 256 rows the step is no longer a pure weight stream: 2 x 256 x params x 2 (hi, lo) flops per
+// step put it on the matrix-core side of the ridge.  Tiling: a workgroup of 4 waves computes 64
+// rows x 256 columns; wave w owns 4 n-tiles (64 columns) for all 4 row tiles (16 accumulator
+// tiles), so every activation fragment read from LDS feeds 4 MFMAs and every weight fragment (read
+// straight from global memory, 4 k-tiles ahead) feeds 8.  Activation fragments of 4 k-tiles at a
+// time are copied global -> LDS by the whole workgroup, double buffered (2 x 32 KB), one barrier per
+// stage.  The four workgroups of a column block re-read the same weights: HBM sees them once, the
+// repeats come from L2: workgroup ids are mapped so that the row blocks of one column block run on
+// the same XCD (ids that are equal mod 8 share an XCD and its L2), back to back.  Matrices with few
+// columns (O and down projections) are also split along K so that the launch fills the chip; the
+// slices store partial tiles and k_resid_reduce adds them to the residual stream in slice order.
+//
+// k_split prepares the activations: optional RMSNorm (row statistics in fp32, gain applied), then
+// bf16 hi + lo, stored in B-fragment order [row tile][k-tile][hi|lo][lane][8].
+#include "gemm256.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
+union Frag { u32x4_t u; bf16x8_t v; };
+
+__device__ inline uint32_t rne16(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ inline float up16(uint32_t b) { return __uint_as_float(b << 16); }
+
+// ------------------------------------------------------------------ activation split (+ RMSNorm)
+// grid (row tiles of 16 rows, K chunks); X [M][K] fp32 -> AF [MT][KT][2][64][8] bf16.  With a gain every
+// workgroup computes the statistics of its 16 rows over the whole row (the rows sit in L2) and then
+// converts its own K chunk.
+__global__ __launch_bounds__(512) void k_split(const float* X, int ldx, int M, int K, const float* gain, float eps,
+                                               bf16_t* AF) {
+    __shared__ float red[8][16];
+    __shared__ float rs[16];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int lm = lane & 15, g4 = lane >> 4;
+    const int mt = blockIdx.x, KT = K >> 5;
+    const int kt_lo = (int)((unsigned)KT * blockIdx.y / gridDim.y), kt_hi = (int)((unsigned)KT * (blockIdx.y + 1) / gridDim.y);
+    const int row = mt * 16 + lm < M ? mt * 16 + lm : M - 1;
+    const float* xr = X + (size_t)row * ldx + 8 * g4;
+    float scale = 1.0f;
+    if (gain) {
+        float ss = 0.f;
+        for (int kt = w; kt < KT; kt += 8) {
+            const float4 a = *(const float4*)(xr + kt * 32), b = *(const float4*)(xr + kt * 32 + 4);
+            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+        }
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (g4 == 0) red[w][lm] = ss;
+        __syncthreads();
+        if (tid < 16) {
+            float s = 0.f;
+            for (int q = 0; q < 8; ++q) s += red[q][tid];
+            rs[tid] = 1.0f / sqrtf(s / (float)K + eps);
+        }
+        __syncthreads();
+        scale = rs[lm];
+    }
+    u32x4_t* dst = (u32x4_t*)AF + (size_t)mt * KT * 2 * 64 + lane;
+    for (int kt = kt_lo + w; kt < kt_hi; kt += 8) {
+        const float4 a = *(const float4*)(xr + kt * 32), b = *(const float4*)(xr + kt * 32 + 4);
+        float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        if (gain) {
+            const float4 g0 = *(const float4*)(gain + kt * 32 + 8 * g4), g1 = *(const float4*)(gain + kt * 32 + 8 * g4 + 4);
+            const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = v[e] * scale * g[e];
+        }
+        uint32_t h[8], l[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { h[e] = rne16(v[e]); l[e] = rne16(v[e] - up16(h[e])); }
+        dst[(size_t)kt * 128] = (u32x4_t){h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+        dst[(size_t)kt * 128 + 64] = (u32x4_t){l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+    }
+}
+
+hipError_t fc_split(const float* X, int ldx, int M, int K, const float* gain, float eps, bf16_t* AF, hipStream_t st) {
+    if (M < 1 || K % 256) return hipErrorInvalidValue;
+    const int MT = (M + 15) / 16;
+    int kc = (512 + MT - 1) / MT;                       // about 512 workgroups, at least 8 k-tiles each
+    if (kc > K / 256) kc = K / 256;
+    k_split<<<dim3(MT, kc), 512, 0, st>>>(X, ldx, M, K, gain, eps, AF);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ the GEMM
+template <int EPI>
+__global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
+    __shared__ u32x4_t stage[2][4][4][2][64];           // [buffer][k-tile][row tile][hi|lo][lane]: 2 x 32 KB
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int lm = lane & 15, g4 = lane >> 4;
+    const int KT = a.K >> 5, NS = KT >> 2, MT = (a.M + 15) >> 4;
+    // id -> (XCD x, sequence number q on that XCD) -> row block q % nrb of unit 8 * (q / nrb) + x
+    const int nrb = (MT + 3) >> 2, ncb = (a.NT + 15) >> 4;
+    const int xq = blockIdx.x >> 3, unit = (xq / nrb) * 8 + (blockIdx.x & 7), rb = xq % nrb;
+    if (unit >= ncb * a.sk) return;                      // grid padding (whole workgroup leaves together)
+    const int cb = unit / a.sk, ks = unit % a.sk;
+    const int s_lo = (int)((unsigned)NS * (unsigned)ks / (unsigned)a.sk), s_hi = (int)((unsigned)NS * (unsigned)(ks + 1) / (unsigned)a.sk);
+    const int nt0 = cb * 16 + 4 * w;                     // this wave's 4 n-tiles
+    const int mt0 = rb * 4;
+    const u32x4_t* AFp = (const u32x4_t*)a.AF;
+    const u32x4_t* Wp = (const u32x4_t*)a.W + lane;
+
+    // stage copy: 32 fragments of 1 KB per stage, 8 x 16 bytes per thread
+    auto stage_load = [&](u32x4_t (&r)[8], int s) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int idx = tid + 256 * i, f = idx >> 6, ln = idx & 63;
+            const int ktl = f >> 3, mtl = (f >> 1) & 3, part = f & 1;
+            const int mt = mt0 + mtl < MT ? mt0 + mtl : MT - 1;
+            r[i] = AFp[(((size_t)mt * KT + 4 * s + ktl) * 2 + part) * 64 + ln];
+        }
+    };
+    auto stage_store = [&](const u32x4_t (&r)[8], int buf) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int idx = tid + 256 * i, f = idx >> 6, ln = idx & 63;
+            stage[buf][f >> 3][(f >> 1) & 3][f & 1][ln] = r[i];
+        }
+    };
+    auto wload = [&](u32x4_t (&wt)[4], int kt) {
+        const int kc = kt < KT ? kt : KT - 1;                 // past the end: re-read the last k-tile (never used)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int nt = nt0 + j < a.NT ? nt0 + j : a.NT - 1;
+            wt[j] = Wp[((size_t)nt * KT + kc) * 64];
+        }
+    };
+
+    f32x4_t acc[4][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int m = 0; m < 4; ++m) acc[j][m] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+
+    u32x4_t sr[8];
+    u32x4_t W0[4], W1[4], W2[4], W3[4];
+    stage_load(sr, s_lo);
+    wload(W0, 4 * s_lo); wload(W1, 4 * s_lo + 1); wload(W2, 4 * s_lo + 2); wload(W3, 4 * s_lo + 3);
+    stage_store(sr, 0);
+    __syncthreads();
+
+#define STEP(WSET, U)                                                                               \
+    do {                                                                                            \
+        Frag ah[4], al[4];                                                                          \
+        _Pragma("unroll") for (int m = 0; m < 4; ++m) { ah[m].u = stage[buf][U][m][0][lane]; al[m].u = stage[buf][U][m][1][lane]; } \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                             \
+            Frag wf; wf.u = WSET[j];                                                                \
+            _Pragma("unroll") for (int m = 0; m < 4; ++m) {                                         \
+                acc[j][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, ah[m].v, acc[j][m], 0, 0, 0); \
+                acc[j][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, al[m].v, acc[j][m], 0, 0, 0); \
+            }                                                                                       \
+        }                                                                                           \
+        wload(WSET, 4 * s + U + 4);                                                                 \
+    } while (0)
+
+    int buf = 0;
+    for (int s = s_lo; s < s_hi; ++s) {
+        stage_load(sr, s + 1 < s_hi ? s + 1 : s);        // next stage's activations travel while this one is used
+        STEP(W0, 0);
+        STEP(W1, 1);
+        STEP(W2, 2);
+        STEP(W3, 3);
+        stage_store(sr, buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+#undef STEP
+
+    // ---- epilogue: acc[j][m]: rows (mt0 + m) * 16 + lm, columns (nt0 + j) * 16 + 4 * g4 + r
+    float best[4]; int bidx[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) { best[m] = -3.0e38f; bidx[m] = 0x7fffffff; }
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const int row = (mt0 + m) * 16 + lm;
+        const bool rok = mt0 + m < MT && row < a.M;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int nt = nt0 + j;
+            const bool ok = rok && nt < a.NT;
+            const f32x4_t v = acc[j][m];
+            if (EPI == EPI_RESID) {
+                if (ok) {
+                    if (a.sk > 1) *(f32x4_t*)(a.part + ((size_t)ks * a.M + row) * (a.NT * 16) + nt * 16 + 4 * g4) = v;
+                    else {
+                        f32x4_t* o = (f32x4_t*)(a.out + (size_t)row * a.ldo + nt * 16 + 4 * g4);
+                        *o = *o + v;
+                    }
+                }
+            } else if (EPI == EPI_SWIGLU) {
+                f32x4_t h;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float other = __shfl_xor(v[r], 32, 64);
+                    h[r] = v[r] / (1.0f + expf(-v[r])) * other;
+                }
+                if (ok && g4 < 2) *(f32x4_t*)(a.out + (size_t)row * a.ldo + nt * 8 + 4 * g4) = h;
+            } else if (EPI == EPI_QKV) {
+                const int hh = nt >> 3, t = nt & 7;
+                const int b = rok ? row / a.Wn : 0, jj = rok ? row % a.Wn : 0;
+                const int pos = rok ? a.n_state[b] + jj : a.S;
+                const bool pk = ok && pos < a.S;                 // capacity guard
+                const size_t plane = (size_t)a.S * 128;
+                if (hh < a.H + a.Hkv) {
+                    const int i0 = 8 * t + 4 * (g4 & 1);
+                    f32x4_t rr;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float other = __shfl_xor(v[e], 32, 64);
+                        const float c = pk ? a.cosT[(size_t)pos * 64 + i0 + e] : 1.0f;
+                        const float s = pk ? a.sinT[(size_t)pos * 64 + i0 + e] : 0.0f;
+                        rr[e] = g4 < 2 ? v[e] * c - other * s : v[e] * c + other * s;
+                    }
+                    const int el = (g4 < 2 ? 0 : 64) + i0;
+                    if (pk) {
+                        if (hh < a.H) *(f32x4_t*)(a.out + (size_t)row * a.ldo + hh * 128 + el) = rr;
+                        else {
+                            bf16_t* kr = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + (hh - a.H)) * a.kvp) * plane + (size_t)pos * 128 + el;
+                            uint32_t h[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) h[e] = rne16(rr[e]);
+                            *(uint2*)kr = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                            if (a.kvp == 2) {
+                                uint32_t l[4];
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) l[e] = rne16(rr[e] - up16(h[e]));
+                                *(uint2*)(kr + plane) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+                            }
+                        }
+                    }
+                } else if (pk) {
+                    const int kh = hh - a.H - a.Hkv;
+                    bf16_t* vr = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + (size_t)(16 * t + 4 * g4) * a.S + pos;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t h0 = rne16(v[e]);
+                        vr[(size_t)e * a.S] = (bf16_t)h0;
+                        if (a.kvp == 2) vr[(size_t)e * a.S + plane] = (bf16_t)rne16(v[e] - up16(h0));
+                    }
+                }
+            } else if (EPI == EPI_LMHEAD) {
+                const int n0 = nt * 16 + 4 * g4;
+                if (ok && a.out) *(f32x4_t*)(a.out + (size_t)row * a.ldo + n0) = v;
+                if (nt < a.NT) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) if (v[r] > best[m]) { best[m] = v[r]; bidx[m] = n0 + r; }
+                }
+            }
+        }
+    }
+    if (EPI == EPI_LMHEAD) {
+        // winner per row over this workgroup's 256 columns: lanes of a row, then the 4 waves (the
+        // stage buffers are free after the last barrier of the main loop)
+        float (*amv)[64] = (float (*)[64])&stage[0][0][0][0][0];
+        int (*ami)[64] = (int (*)[64])&stage[1][0][0][0][0];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+#pragma unroll
+            for (int o = 16; o <= 32; o <<= 1) {
+                const float ov = __shfl_xor(best[m], o, 64); const int oi = __shfl_xor(bidx[m], o, 64);
+                if (ov > best[m] || (ov == best[m] && oi < bidx[m])) { best[m] = ov; bidx[m] = oi; }
+            }
+            if (g4 == 0) { amv[w][m * 16 + lm] = best[m]; ami[w][m * 16 + lm] = bidx[m]; }
+        }
+        __syncthreads();
+        if (tid < 64) {
+            float bv = amv[0][tid]; int bx = ami[0][tid];
+            for (int q = 1; q < 4; ++q)
+                if (amv[q][tid] > bv || (amv[q][tid] == bv && ami[q][tid] < bx)) { bv = amv[q][tid]; bx = ami[q][tid]; }
+            const int row = mt0 * 16 + tid;
+            if (row < a.M) {
+                a.amax_val[(size_t)cb * a.amax_stride + row] = bv;
+                a.amax_idx[(size_t)cb * a.amax_stride + row] = bx;
+            }
+        }
+    }
+}
+
+// out[m][n] += part[0][m][n] + part[1][m][n] + ... (slice order: the result does not depend on timing)
+__global__ __launch_bounds__(256) void k_resid_reduce(const float* part, int sk, int M, int N, float* out, int ldo) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x, n4 = N >> 2;
+    if (i >= (size_t)M * n4) return;
+    const int m = (int)(i / n4), c = (int)(i % n4) * 4;
+    f32x4_t s = *(const f32x4_t*)(part + (size_t)m * N + c);
+    for (int k = 1; k < sk; ++k) s = s + *(const f32x4_t*)(part + ((size_t)k * M + m) * N + c);
+    f32x4_t* o = (f32x4_t*)(out + (size_t)m * ldo + c);
+    *o = *o + s;
+}
+
+int fc_gemm256_sk(int M, int K, int NT) {
+    const int nwg = ((NT + 15) / 16) * (((M + 15) / 16 + 3) / 4), NS = K / 128;
+    if (nwg >= 200) return 1;
+    int sk = (480 + nwg - 1) / nwg;
+    if (sk > FC_GEMM256_MAX_SK) sk = FC_GEMM256_MAX_SK;
+    if (sk > NS / 2) sk = NS / 2;
+    return sk < 1 ? 1 : sk;
+}
+
+hipError_t fc_gemm256(int epi, const Gemm256Args& a, hipStream_t st) {
+    if (a.M < 1 || a.K % 256 || a.NT < 1 || a.sk < 1 || a.sk > FC_GEMM256_MAX_SK || a.sk > a.K / 128) return hipErrorInvalidValue;
+    if (a.sk > 1 && (epi != EPI_RESID || !a.part)) return hipErrorInvalidValue;
+    const int nrb = ((a.M + 15) / 16 + 3) / 4, units = ((a.NT + 15) / 16) * a.sk;
+    dim3 grid((unsigned)((units + 7) / 8) * 8 * nrb);
+    switch (epi) {
+        case EPI_RESID: k_gemm256<EPI_RESID><<<grid, 256, 0, st>>>(a); break;
+        case EPI_SWIGLU: k_gemm256<EPI_SWIGLU><<<grid, 256, 0, st>>>(a); break;
+        case EPI_QKV: k_gemm256<EPI_QKV><<<grid, 256, 0, st>>>(a); break;
+        case EPI_LMHEAD: k_gemm256<EPI_LMHEAD><<<grid, 256, 0, st>>>(a); break;
+        default: return hipErrorInvalidValue;
+    }
+    if (a.sk > 1) {
+        const size_t n = (size_t)a.M * (a.NT * 4);
+        k_resid_reduce<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a.part, a.sk, a.M, a.NT * 16, a.out, a.ldo);
+    }
+    return hipGetLastError();
+}
