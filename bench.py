@@ -87,6 +87,58 @@ def cpu_baseline(shape, W, log_fn):
             "sample": f"{steps} Jacobi steps of the fp32 oracle, batch 1, window {W}, context {P - 1}..{n}, same model shape"}
 
 
+def time_launches(torch, fn, n):
+    """Mean microseconds of n launches of fn(i) on torch's current stream (events around the batch)."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(3):
+        fn(i)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(n):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return 1e3 * e0.elapsed_time(e1) / n
+
+
+def extras(torch, fc, synthgen, packed, log_fn):
+    """Secondary measurements: the device's plain streaming-read rate and the two kernels in isolation
+    (window attention over a 2048-token cache; LM head + argmax), cache-cold by rotating buffer sets."""
+    out = {}
+    nbytes = min(packed.numel(), 8 << 30)
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    us = time_launches(torch, lambda i: fc.stream_read(packed[:nbytes], sink), 5)
+    out["stream_read_ceiling"] = {"bytes": int(nbytes), "us": round(us, 1), "GB/s": round(nbytes / us / 1e3, 0)}
+    log_fn(f"plain streaming read of {nbytes / 1e9:.2f} GB: {us:.0f} us -> {nbytes / us / 1e3:.0f} GB/s")
+    # attention alone: 32 heads x 128, 2048 committed positions + 16 window rows, bf16 cache (one plane)
+    n, W, H, Dh, S = 2048, 16, 32, 128, 2080
+    sets = []
+    for r in range(3):
+        k = torch.from_numpy(synthgen.normal_bf16((n + W, H, Dh), 7, 2 * r, 1.0).view(np.int16)).cuda().view(torch.bfloat16)
+        v = torch.from_numpy(synthgen.normal_bf16((n + W, H, Dh), 7, 2 * r + 1, 1.0).view(np.int16)).cuda().view(torch.bfloat16)
+        sets.append(fc.kv_scatter(k, v, S))
+    q = torch.from_numpy(synthgen.normal_f32((W, H, Dh), 7, 9, 1.0, False)).cuda()
+    scratch = torch.zeros(fc.lib().fastcot_attn_scratch_bytes(W, H, Dh), dtype=torch.uint8, device="cuda")
+    us = time_launches(torch, lambda i: fc.attn_window(q, *sets[i % 3], n, scratch), 120)
+    kvb = 2 * (n + W) * H * Dh * 2
+    out["attention_isolated"] = {"keys": n + W, "rows": W, "heads": H, "us": round(us, 2), "kv_bytes": kvb,
+                                 "GB/s": round(kvb / us / 1e3, 0), "frac_of_8TBs": round(kvb / us / 1e3 / HBM_PEAK_GBS, 4)}
+    log_fn(f"attention alone ({n + W} keys, {W} rows, {H} heads): {us:.1f} us, {kvb / us / 1e3:.0f} GB/s")
+    del sets
+    # LM head + argmax alone: 16 x 4096 activations, 4096 x 32000 weights, three weight copies in rotation
+    M, d, V = 16, 4096, 32000
+    wl = [fc.lmhead_pack(torch.from_numpy(synthgen.normal_bf16((d, V), 8, r, 0.02).view(np.int16)).cuda().view(torch.bfloat16))
+          for r in range(3)]
+    act = torch.from_numpy(synthgen.normal_f32((M, d), 8, 9, 1.0, False)).cuda()
+    scr = torch.zeros(fc.lib().fastcot_lmhead_scratch_bytes(M, d, V), dtype=torch.uint8, device="cuda")
+    us = time_launches(torch, lambda i: fc.lmhead_argmax(act, wl[i % 3], V, False, scr), 120)
+    wb = d * V * 2
+    out["lm_head_isolated"] = {"rows": M, "d": d, "vocab": V, "us": round(us, 2), "weight_bytes": wb,
+                               "GB/s": round(wb / us / 1e3, 0), "frac_of_8TBs": round(wb / us / 1e3 / HBM_PEAK_GBS, 4)}
+    log_fn(f"LM head + argmax alone ({M} x {d} x {V}): {us:.1f} us, {wb / us / 1e3:.0f} GB/s")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -96,6 +148,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-iters", type=int, default=3)
     ap.add_argument("--plain", action="store_true", help="time the plain kernels instead of the MFMA path")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the secondary measurements (streaming-read ceiling, isolated attention and LM head, perfect draft)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device-to-device copy of 512 MiB (the known-size kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -130,8 +184,11 @@ def main():
     # ---- accepted tokens/s on the paper-shaped job: generate N tokens from the prompt
     ctx.prefill(prompts, lens, buf)
     ctx.generate(min(N, 4 * W))                        # warm (graph capture, caches)
+    torch.cuda.synchronize()
+    t0 = time.time()
     ctx.prefill(prompts, lens, buf)
     torch.cuda.synchronize()
+    prefill_ms = 1e3 * (time.time() - t0)
     t0 = time.time()
     out = ctx.generate(N)
     torch.cuda.synchronize()
@@ -139,8 +196,26 @@ def main():
     gen_ms = ctx.step_times()
     gen_steps = int(out["steps"].max())
     tok_s = float(out["len"].sum()) / gen_s
-    log(f"generate: {int(out['len'].sum())} tokens in {gen_steps} steps, {gen_s * 1e3:.1f} ms, "
-        f"median step {np.median(gen_ms):.3f} ms")
+    log(f"prefill {prefill_ms:.1f} ms; generate: {int(out['len'].sum())} tokens in {gen_steps} steps, {gen_s * 1e3:.1f} ms, "
+        f"step median {np.median(gen_ms):.3f} p10 {np.percentile(gen_ms, 10):.3f} p90 {np.percentile(gen_ms, 90):.3f} ms")
+
+    # ---- the other extreme of the accept path: a buffer that already holds the greedy continuation
+    # (every draft verifies, W tokens per step); the model's own accepted stream is that continuation
+    perfect = None
+    if not args.no_extras:
+        pbuf = buf.copy()
+        pbuf[:, :N] = out["ids"][:, :N]
+        ctx.prefill(prompts, lens, pbuf)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        pout = ctx.generate(N)
+        torch.cuda.synchronize()
+        ps = time.time() - t0
+        perfect = {"tokens": int(pout["len"].sum()), "steps": int(pout["steps"].max()), "wall_ms": round(ps * 1e3, 2),
+                   "tokens_per_s": round(float(pout["len"].sum()) / ps, 1),
+                   "accepted_per_step": round(float(pout["len"].sum()) / max(int(pout["steps"].max()), 1) / B, 3),
+                   "same_tokens": bool((pout["ids"][:, :N] == out["ids"][:, :N]).all())}
+        log(f"perfect draft: {perfect['tokens']} tokens in {perfect['steps']} steps, {perfect['tokens_per_s']:.0f} tokens/s")
 
     # ---- exactly K timed steps after Wm warm-up steps (state continues, inputs resident)
     ctx.prefill(prompts, lens, buf)
@@ -201,6 +276,9 @@ def main():
                     "flops_per_launch": flops, "issued_flops_per_launch": 2 * flops, "avg_launch_ms": round(dom[1], 5),
                     "step_algorithmic_bytes": int(alg), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4)}
 
+    extra = None
+    if not args.no_extras and not args.plain and shape.dtype == "bf16":
+        extra = extras(torch, fc, synthgen, packed, log)
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(shape, W, log)
@@ -217,9 +295,14 @@ def main():
                    "kernels": "plain" if args.plain else "mfma"},
         "generate": {"tokens": int(out["len"].sum()), "steps": gen_steps, "wall_ms": round(gen_s * 1e3, 2),
                      "median_step_ms": round(float(np.median(gen_ms)), 4),
+                     "p10_step_ms": round(float(np.percentile(gen_ms, 10)), 4),
+                     "p90_step_ms": round(float(np.percentile(gen_ms, 90)), 4),
+                     "prefill_ms": round(prefill_ms, 2),
                      "accepted_per_step": round(float(out["len"].sum()) / max(gen_steps, 1) / B, 3)},
         "hbm_roofline_pct_step": round(100 * step_gbs / HBM_PEAK_GBS, 2),
+        "perfect_draft": perfect,
         "roofline": roofline,
+        "secondary": extra,
         "cpu_baseline": cpu,
     }
     print(json.dumps(rec), flush=True)

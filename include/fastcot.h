@@ -143,6 +143,8 @@ enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLAN
         * at most 8 tiles of 16 columns); 0 selects the split-K kernel for that GEMM */
        FASTCOT_OPT_NW_QKV = 22, FASTCOT_OPT_NW_O = 23, FASTCOT_OPT_NW_GU = 24, FASTCOT_OPT_NW_DOWN = 25,
        FASTCOT_OPT_NW_LM = 26,
+       FASTCOT_OPT_ATTN_BLOCKS = 28, /* key blocks of 32 positions per attention workgroup: of the launched
+                                      * splits, ceil(blocks / value) work on a sequence, the rest exit */
        FASTCOT_OPT_CO_SINGLE = 27,   /* 1: one weight batch in flight per wave (two workgroups per CU) */
        /* debug: run only the first `value` stages of a forward (per layer: QKV, attention, O,
         * gate/up, down); negative = all */
@@ -170,7 +172,8 @@ const char* fastcot_kernel_name(int32_t kind);
  *
  * Window-causal attention (Eq. 2 conditioning as a mask): q device fp32 [W][H][Dh] (already
  * rotated); k_cache / vt_cache in the library's single-plane cache layout for one sequence, K as
- * [Hkv][max_seq][Dh] and V transposed as [Hkv][Dh][max_seq], elements of `dtype`, positions
+ * [Hkv][max_seq][Dh] and V transposed in blocks of 32 positions as [Hkv][max_seq/32][Dh][32] (position p
+ * of element e at ((p/32)*Dh + e)*32 + p%32; max_seq a multiple of 32), elements of `dtype`, positions
  * 0..n+W-1 filled; row j attends positions 0..n+j.  out device fp32 [W][H*Dh].  scratch: device,
  * fastcot_attn_scratch_bytes() bytes, zeroed once by the caller before first use.
  * fastcot_kv_scatter writes canonical k, v (device, [S][Hkv][Dh], `dtype`) into that layout. */
@@ -180,6 +183,12 @@ int fastcot_kv_scatter(const void* d_k, const void* d_v, int32_t S, int32_t Hkv,
 int fastcot_attn_window(const float* d_q, const void* d_k_cache, const void* d_vt_cache, int32_t n, int32_t W,
                         int32_t H, int32_t Hkv, int32_t Dh, int32_t max_seq, int32_t dtype, float* d_out,
                         void* d_scratch, void* hip_stream);
+
+/* Measurement aid: one plain streaming read of `bytes` (multiple of 16) device bytes at d_src (16-byte
+ * aligned); d_sink16 is a 16-byte device scratch the kernel may write.  Timed by the caller, it gives the
+ * read bandwidth the device delivers to the simplest kernel: a second denominator beside the published
+ * HBM peak. */
+int fastcot_stream_read(const void* d_src, size_t bytes, void* d_sink16, void* hip_stream);
 
 /* LM head fused with argmax (Eq. 1/2, lowest id on ties): act device fp32 [M][d] (already
  * normalised), packed W_lm as written by fastcot_lmhead_pack from canonical bf16 [d][V];

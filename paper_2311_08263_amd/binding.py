@@ -62,6 +62,7 @@ SYMBOLS = {
     "fastcot_profile_step": (ctypes.c_int, [vp, i32, vp, vp]),
     "fastcot_kernel_name": (ctypes.c_char_p, [i32]),
     "fastcot_attn_scratch_bytes": (sz, [i32, i32, i32]),
+    "fastcot_stream_read": (ctypes.c_int, [vp, ctypes.c_size_t, vp, vp]),
     "fastcot_kv_scatter": (ctypes.c_int, [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]),
     "fastcot_attn_window": (ctypes.c_int, [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]),
     "fastcot_lmhead_packed_bytes": (sz, [i32, i32]),
@@ -266,12 +267,15 @@ class Context:
 
 # ---------------------------------------------------------------------------- kernel isolation
 def kv_scatter(k, v, max_seq: int):
-    """k, v: device tensors [S, Hkv, Dh] (bf16 or fp32) -> (k_cache [Hkv,max_seq,Dh], vt_cache [Hkv,Dh,max_seq])."""
+    """k, v: device tensors [S, Hkv, Dh] (bf16 or fp32) -> (k_cache [Hkv,max_seq,Dh], vt_cache [Hkv,max_seq/32,Dh,32]);
+    max_seq must be a multiple of 32."""
     torch = _torch()
     S, Hkv, Dh = k.shape
     dt = 0 if k.dtype == torch.float32 else 1
     kc = torch.zeros(Hkv, max_seq, Dh, dtype=k.dtype, device="cuda")
-    vc = torch.zeros(Hkv, Dh, max_seq, dtype=k.dtype, device="cuda")
+    if max_seq % 32:
+        raise ValueError("max_seq must be a multiple of 32")
+    vc = torch.zeros(Hkv, max_seq // 32, Dh, 32, dtype=k.dtype, device="cuda")
     _check(lib().fastcot_kv_scatter(k.data_ptr(), v.data_ptr(), S, Hkv, Dh, max_seq, dt, kc.data_ptr(), vc.data_ptr(),
                                     _stream_ptr()))
     return kc, vc
@@ -289,6 +293,16 @@ def attn_window(q, kc, vc, n: int, scratch=None):
     _check(lib().fastcot_attn_window(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), n, W, H, Hkv, Dh, max_seq, dt,
                                      out.data_ptr(), scratch.data_ptr(), _stream_ptr()))
     return out
+
+
+def stream_read(buf, sink=None):
+    """One plain streaming read over the device tensor `buf` on torch's current stream."""
+    torch = _torch()
+    if sink is None:
+        sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    nbytes = (buf.numel() * buf.element_size()) // 16 * 16
+    _check(lib().fastcot_stream_read(buf.data_ptr(), nbytes, sink.data_ptr(), _stream_ptr()))
+    return nbytes
 
 
 def lmhead_pack(w_bf16):

@@ -268,6 +268,9 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
     else if (option == FASTCOT_OPT_ATTN_SPLITS) {
         if (value < 1 || value > FC_MAX_ATTN_SPLITS) return fail(c, FASTCOT_EINVAL, "attention splits out of range%s");
         c->plan.attn_splits = value;
+    } else if (option == FASTCOT_OPT_ATTN_BLOCKS) {
+        if (value < 1 || value > 4096) return fail(c, FASTCOT_EINVAL, "attention blocks per workgroup out of range%s");
+        c->plan.attn_bpw = value;
     }
     else return fail(c, FASTCOT_EINVAL, "unknown option%s");
     drop_graph(c);

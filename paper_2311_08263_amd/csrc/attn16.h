@@ -13,6 +13,7 @@ struct AttnArgs {
     int32_t ldo;
     float* part;           // split partials
     int32_t* cnt;          // one arrival counter per (sequence, head), zero between launches
+    int32_t bpw;           // key blocks (of 32) per workgroup that decide how many of the launched splits are used
 };
 
 size_t fc_attn16_part_bytes(int BH, int nsplit, int W);

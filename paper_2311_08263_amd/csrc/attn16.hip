@@ -43,11 +43,16 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int lm = lane & 15, g = lane >> 4;
     const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H, kvh = h / (a.H / a.Hkv);
-    const int sp = blockIdx.y, nsp = gridDim.y;
+    const int sp = blockIdx.y, nsp_max = gridDim.y;
     const int n = a.n_state[b];
     int T = n + a.W;
     if (T > a.S) T = a.S;                                    // capacity guard (the host checks first)
     const int NB = (T + 31) >> 5;
+    // splits actually used: about a.bpw key blocks per workgroup (the launch provides nsp_max for the
+    // longest context; every workgroup of this (sequence, head) derives the same number from n)
+    int nsp = (NB + a.bpw - 1) / a.bpw;
+    if (nsp > nsp_max) nsp = nsp_max;
+    if (sp >= nsp) return;
     const int blk0 = (int)(((unsigned)sp * (unsigned)NB) / (unsigned)nsp);
     const int blk1 = (int)(((unsigned)(sp + 1) * (unsigned)NB) / (unsigned)nsp);
     const size_t plane = (size_t)a.S * 128;
@@ -79,10 +84,13 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
     }
     const float scale = 0.08838834764831845f;   // 1/sqrt(128)
 
-    for (int blk = blk0 + wv; blk < blk1; blk += 4) {
+    // one 32-key block: K tiles and V^T tiles of block `blk` into registers
+    struct KV { Frag kf[KVP][2][4], vf[KVP][8]; };
+    auto load = [&](KV& r, int blk_want) {
+        const int blk = blk_want < NB ? blk_want : NB - 1;       // past the end: a valid block, never used
         const int kb = blk << 5;
+        Frag (&kf)[KVP][2][4] = r.kf; Frag (&vf)[KVP][8] = r.vf;
         // K tiles (A operand): tile t row r=lm <-> key kb + 8*(lm/4) + 4*t + lm%4 ; dh 32*g + 8*s..
-        Frag kf[KVP][2][4], vf[KVP][8];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             int key = kb + 8 * (lm >> 2) + 4 * t + (lm & 3);
@@ -95,15 +103,16 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
             }
         }
         // V^T tiles (A operand): row 16*dt + lm, keys kb + 8*g .. +7
-        {
-            int k8 = kb + 8 * g;
-            if (k8 > a.S - 8) k8 = a.S - 8;
+        // (the V cache is transposed in blocks of 32 positions: block blk is 128 rows of 32 keys, contiguous)
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt)
+        for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
-                for (int pl = 0; pl < KVP; ++pl)
-                    vf[pl][dt].u = *(const u32x4_t*)(vbase + pl * plane + (size_t)(16 * dt + lm) * a.S + k8);
-        }
+            for (int pl = 0; pl < KVP; ++pl)
+                vf[pl][dt].u = *(const u32x4_t*)(vbase + pl * plane + ((size_t)blk * 128 + 16 * dt + lm) * 32 + 8 * g);
+    };
+    auto compute = [&](const KV& r, int blk) {
+        const int kb = blk << 5;
+        const Frag (&kf)[KVP][2][4] = r.kf; const Frag (&vf)[KVP][8] = r.vf;
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
             f32x4_t sc[2];
@@ -155,6 +164,24 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
                     acc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[KVP - 1][dt].v, ph.v, acc[qt][dt], 0, 0, 0);
             }
         }
+    };
+    // two register sets: the next block of this wave travels while the current one is used
+    {
+        KV ra, rb;
+        int blk = blk0 + wv;
+        if (blk < blk1) {
+            load(ra, blk);
+            for (;;) {
+                load(rb, blk + 4);
+                compute(ra, blk);
+                blk += 4;
+                if (blk >= blk1) break;
+                load(ra, blk + 4);
+                compute(rb, blk);
+                blk += 4;
+                if (blk >= blk1) break;
+            }
+        }
     }
     // row sums over the 4 lanes of a row
 #pragma unroll
@@ -200,7 +227,7 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
     for (int w2 = 1; w2 < 4; ++w2) fold(lds + (size_t)(w2 - 1) * QT * PART_FLOATS, false);
 
     if (nsp > 1) {
-        float* mine = a.part + ((size_t)bh * nsp + sp) * QT * PART_FLOATS;
+        float* mine = a.part + ((size_t)bh * nsp_max + sp) * QT * PART_FLOATS;
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
 #pragma unroll
@@ -221,7 +248,7 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) acc[qt][dt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
         }
-        for (int s2 = 0; s2 < nsp; ++s2) fold(a.part + ((size_t)bh * nsp + s2) * QT * PART_FLOATS, true);
+        for (int s2 = 0; s2 < nsp; ++s2) fold(a.part + ((size_t)bh * nsp_max + s2) * QT * PART_FLOATS, true);
         if (lane == 0) st_agent_i32(a.cnt + bh, 0);
     }
     // out[row][h*128 + 16*dt + 4*g + r] = O / l
@@ -243,7 +270,7 @@ size_t fc_attn16_part_bytes(int BH, int nsplit, int W) {
 }
 
 hipError_t fc_attn16(const AttnArgs& a, int Bact, int nsplit, hipStream_t st) {
-    if (a.W < 1 || a.W > 32 || nsplit < 1 || nsplit > FC_MAX_ATTN_SPLITS || Bact * a.H > FC_MAX_COUNTERS || a.S < 32)
+    if (a.W < 1 || a.W > 32 || nsplit < 1 || nsplit > FC_MAX_ATTN_SPLITS || Bact * a.H > FC_MAX_COUNTERS || a.S < 32 || a.S % 32 || a.bpw < 1)
         return hipErrorInvalidValue;
     dim3 grid(Bact * a.H, nsplit);
     const size_t l1 = (size_t)3 * PART_FLOATS * 4, l2 = 2 * l1;

@@ -72,7 +72,7 @@ enum { FLAG_ALL_DONE = 0, FLAG_ERROR = 1 };
 enum { PARAM_MAX_NEW = 0, PARAM_EOS = 1, PARAM_MAX_STEPS = 2, PARAM_BUF_LEN = 3, PARAM_B = 4 };
 
 struct WorkspaceMap {
-    size_t kc, vc;              // KV cache: K [L][B][Hkv][planes][S][Dh], V transposed [L][B][Hkv][planes][Dh][S]
+    size_t kc, vc;              // KV cache: K [L][B][Hkv][planes][S][Dh], V transposed in blocks [L][B][Hkv][planes][S/32][Dh][32]
     size_t rope_cos, rope_sin;  // fp32 [S][Dh/2]
     size_t x, nx, qkv, qrot, att, gu, h, logits, topv;
     size_t gemm_part, gemm_cnt, attn_part, attn_cnt, amax_part;
@@ -91,9 +91,15 @@ struct KernelDims {    // model + capacities as the kernels need them
 };
 
 // element offset of plane 0 of one (layer, sequence, kv head) block of the K or V cache; plane p
-// follows at p * S * Dh.  K block is [S][Dh], V block is transposed [Dh][S].
+// follows at p * S * Dh.  K block is [S][Dh].  V block is transposed in blocks of 32 positions,
+// [S/32][Dh][32] (v_index): the attention kernel reads V^T rows of 32 keys, so one key block of a head is one
+// contiguous piece of 32 * Dh elements instead of Dh pieces of 64 bytes.
 __host__ __device__ inline size_t kv_block(const KernelDims& kd, int layer, int b, int kh) {
     return ((((size_t)layer * kd.B + b) * kd.Hkv + kh) * (size_t)kd.kvp) * (size_t)kd.S * kd.Dh;
+}
+
+__host__ __device__ inline size_t v_index(int dh, int pos, int Dh) {
+    return ((size_t)(pos >> 5) * Dh + dh) * 32 + (pos & 31);
 }
 
 int fc_build_maps(const fastcot_config* cfg, ModelMap* mm, WorkspaceMap* wm, KernelDims* kd);

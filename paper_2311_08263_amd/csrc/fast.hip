@@ -42,6 +42,7 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     if (sp > FC_MAX_ATTN_SPLITS) sp = FC_MAX_ATTN_SPLITS;
     while (sp > 1 && kd.B * kd.H * sp > 768) --sp;     // measured (batch 8, 40 heads): 2 splits best, 6 are 40% slower
     p->attn_splits = sp < 1 ? 1 : sp;
+    p->attn_bpw = 8;
     // column-owner kernel: workgroups per GEMM (one per CU where the matrix allows)
     const int nts[5] = {kd.qkvN / 16, kd.d / 16, 2 * kd.F / 16, kd.d / 16, kd.V / 16};
     // measured on the 7B shape: one workgroup per CU, one weight batch in flight per wave; the O
@@ -92,7 +93,7 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     g.amax_val = (float*)(ws + wm.amax_part);
     AttnArgs at; memset(&at, 0, sizeof(at));
     at.q = q; at.ldq = qd; at.kc = g.kc; at.vc = g.vc; at.B = kd.B; at.H = kd.H; at.Hkv = kd.Hkv; at.S = kd.S; at.W = kd.W; at.kvp = kd.kvp;
-    at.n_state = g.n_state; at.out = att; at.ldo = qd; at.part = (float*)(ws + wm.attn_part); at.cnt = (int32_t*)(ws + wm.attn_cnt);
+    at.n_state = g.n_state; at.out = att; at.ldo = qd; at.part = (float*)(ws + wm.attn_part); at.cnt = (int32_t*)(ws + wm.attn_cnt); at.bpw = a.plan->attn_bpw;
 
     GemmCoArgs co; memset(&co, 0, sizeof(co));
     co.M = M; co.eps = kd.eps; co.n_state = g.n_state; co.cosT = g.cosT; co.sinT = g.sinT; co.kc = g.kc; co.vc = g.vc;
@@ -191,7 +192,7 @@ hipError_t fc_attn_iso(const float* q, const void* kc, const void* vc, int n, in
     AttnArgs at; memset(&at, 0, sizeof(at));
     at.q = q; at.ldq = H * 128; at.kc = (const bf16_t*)kc; at.vc = (const bf16_t*)vc; at.layer = 0; at.B = 1; at.H = H;
     at.Hkv = Hkv; at.S = S; at.W = W; at.kvp = 1; at.n_state = (const int32_t*)sc; at.out = out; at.ldo = H * 128;
-    at.cnt = (int32_t*)(sc + 256);
+    at.cnt = (int32_t*)(sc + 256); at.bpw = 8;
     at.part = (float*)(sc + 256 + (((size_t)H * 4 + 255) & ~(size_t)255));
     return fc_attn16(at, 1, iso_attn_splits(n + W), st);
 }

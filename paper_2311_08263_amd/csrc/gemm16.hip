@@ -294,7 +294,7 @@ __global__ __launch_bounds__(512) void k_gemm16(Gemm16Args a) {
                 const int b = (a.m0 + m) / a.Wn, j = (a.m0 + m) % a.Wn;
                 const int pos = a.n_state[b] + j;
                 if (pos >= a.S) continue;
-                bf16_t* vr = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + (size_t)e * a.S + pos;
+                bf16_t* vr = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + v_index(e, pos, 128);
                 const float vv = ex[(size_t)m * 132 + e];
                 const uint32_t h0 = bf16_rne_bits(vv);
                 vr[0] = (bf16_t)h0;

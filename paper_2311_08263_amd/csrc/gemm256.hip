@@ -236,12 +236,12 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
                     }
                 } else if (pk) {
                     const int kh = hh - a.H - a.Hkv;
-                    bf16_t* vr = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + (size_t)(16 * t + 4 * g4) * a.S + pos;
+                    bf16_t* vr = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + v_index(16 * t + 4 * g4, pos, 128);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const uint32_t h0 = rne16(v[e]);
-                        vr[(size_t)e * a.S] = (bf16_t)h0;
-                        if (a.kvp == 2) vr[(size_t)e * a.S + plane] = (bf16_t)rne16(v[e] - up16(h0));
+                        vr[e * 32] = (bf16_t)h0;
+                        if (a.kvp == 2) vr[e * 32 + plane] = (bf16_t)rne16(v[e] - up16(h0));
                     }
                 }
             } else if (EPI == EPI_LMHEAD) {

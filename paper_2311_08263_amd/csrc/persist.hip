@@ -372,7 +372,7 @@ __global__ __launch_bounds__(512) void k_step(PersistArgs a) {
                         const int b = m / a.W, j = m % a.W;
                         const int pos = a.state[a.sm.n + b] + j;
                         if (pos >= a.S) continue;
-                        bf16_t* vr = a.vc + ((((size_t)layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + (size_t)e * a.S + pos;
+                        bf16_t* vr = a.vc + ((((size_t)layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + v_index(e, pos, 128);
                         const float vv = lds_ex[(size_t)m * 132 + e];
                         const uint32_t h0 = rne16(vv);
                         st_agent_u16(vr, h0);
@@ -506,11 +506,9 @@ __global__ __launch_bounds__(512) void k_step(PersistArgs a) {
                 lrun = lrun * alpha + ps;
                 Frag ph, pl;
                 split8(p, ph, pl);
-                int k8 = kb + 8 * g4;
-                if (k8 > a.S - 8) k8 = a.S - 8;
 #pragma unroll
                 for (int dt = 0; dt < 8; ++dt) {
-                    const bf16_t* vp = vbase + (size_t)(16 * dt + lm) * a.S + k8;
+                    const bf16_t* vp = vbase + ((size_t)(kb >> 5) * 128 + 16 * dt + lm) * 32 + 8 * g4;
                     Frag vf; vf.u = ld_kv16(vp, coh);
                     acc[dt] *= alpha;
                     acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, ph.v, acc[dt], 0, 0, 0);

@@ -130,7 +130,7 @@ __global__ void k_rope_cache(const float* qkv, float* qrot, KernelDims kd, int l
     const float* vrow = row + (size_t)(kd.H + kd.Hkv) * kd.Dh;
     for (int i = threadIdx.x; i < kd.Hkv * kd.Dh; i += blockDim.x) {
         int kh = i / kd.Dh, e = i % kd.Dh;
-        size_t base = kv_block(kd, layer, b, kh) + (size_t)e * kd.S + pos;
+        size_t base = kv_block(kd, layer, b, kh) + v_index(e, pos, kd.Dh);
         kvstore<DT>(vc, base, plane, kd.kvp, vrow[i]);
     }
 }
@@ -174,9 +174,8 @@ __global__ void k_attn_plain(const float* q, int ldq, const void* kc, const void
     den = block_sum(den, red);
     __syncthreads();
     for (int i = threadIdx.x; i < kd.Dh; i += blockDim.x) {
-        size_t vb = kbase + (size_t)i * kd.S;   // transposed V: [Dh][S]
-        float acc = 0;
-        for (int t = 0; t <= last; ++t) acc += sc[t] * kvload<DT>(vc, vb + t, plane, kd.kvp);
+        float acc = 0;                          // transposed V in blocks of 32 positions
+        for (int t = 0; t <= last; ++t) acc += sc[t] * kvload<DT>(vc, kbase + v_index(i, t, kd.Dh), plane, kd.kvp);
         out[(size_t)m * kd.H * kd.Dh + (size_t)h * kd.Dh + i] = acc / den;
     }
 }
@@ -272,7 +271,7 @@ hipError_t fc_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s
     return hipGetLastError();
 }
 
-// canonical K, V [S_in][Hkv][Dh] -> cache layout of one sequence: K [Hkv][S][Dh], V^T [Hkv][Dh][S]
+// canonical K, V [S_in][Hkv][Dh] -> cache layout of one sequence: K [Hkv][S][Dh], V^T [Hkv][S/32][Dh][32]
 template <int DT>
 __global__ void k_kv_scatter(const void* k, const void* v, int S_in, int Hkv, int Dh, int S, void* kc, void* vc) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -280,10 +279,10 @@ __global__ void k_kv_scatter(const void* k, const void* v, int S_in, int Hkv, in
     int e = (int)(i % Dh), h = (int)((i / Dh) % Hkv), t = (int)(i / ((size_t)Dh * Hkv));
     if (DT == FASTCOT_F32) {
         ((float*)kc)[((size_t)h * S + t) * Dh + e] = ((const float*)k)[i];
-        ((float*)vc)[((size_t)h * Dh + e) * S + t] = ((const float*)v)[i];
+        ((float*)vc)[(size_t)h * Dh * S + v_index(e, t, Dh)] = ((const float*)v)[i];
     } else {
         ((bf16_t*)kc)[((size_t)h * S + t) * Dh + e] = ((const bf16_t*)k)[i];
-        ((bf16_t*)vc)[((size_t)h * Dh + e) * S + t] = ((const bf16_t*)v)[i];
+        ((bf16_t*)vc)[(size_t)h * Dh * S + v_index(e, t, Dh)] = ((const bf16_t*)v)[i];
     }
 }
 hipError_t fc_kv_scatter(const void* k, const void* v, int S_in, int Hkv, int Dh, int S, int dt, void* kc, void* vc,

@@ -116,7 +116,8 @@ def test_attention_isolation(fc, n, W, H, Hkv):
     # garbage (finite) beyond the visible range must not matter: positions >= n+W are never read as visible
     kc2, vc2 = kc.clone(), vc.clone()
     kc2[:, n + W:, :] = 7.0
-    vc2[:, :, n + W:] = -9.0
+    beyond = (torch.arange(S, device="cuda") >= n + W).view(S // 32, 32)   # vt_cache is [Hkv][S/32][Dh][32]
+    vc2.permute(0, 2, 1, 3)[:, :, beyond] = -9.0
     out2 = fc.attn_window(torch.from_numpy(q).cuda(), kc2, vc2, n)
     assert torch.equal(out, out2)
 
