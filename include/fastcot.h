@@ -171,10 +171,10 @@ const char* fastcot_kernel_name(int32_t kind);
 /* Kernel-isolation entry points (the same kernels the step uses, on raw device pointers).
  *
  * Window-causal attention (Eq. 2 conditioning as a mask): q device fp32 [W][H][Dh] (already
- * rotated); k_cache / vt_cache in the library's single-plane cache layout for one sequence, K as
- * [Hkv][max_seq][Dh] and V transposed in blocks of 32 positions as [Hkv][max_seq/32][Dh][32] (position p
- * of element e at ((p/32)*Dh + e)*32 + p%32; max_seq a multiple of 32), elements of `dtype`, positions
- * 0..n+W-1 filled; row j attends positions 0..n+j.  out device fp32 [W][H*Dh].  scratch: device,
+ * rotated); k_cache / vt_cache in the library's single-plane cache layout for one sequence: per kv head
+ * max_seq/32 blocks of 32 positions x Dh elements, each block stored in the order of the attention
+ * kernel's matrix-core operand fragments (written by fastcot_kv_scatter; max_seq and Dh multiples of 32),
+ * elements of `dtype`, positions 0..n+W-1 filled; row j attends positions 0..n+j.  out device fp32 [W][H*Dh].  scratch: device,
  * fastcot_attn_scratch_bytes() bytes, zeroed once by the caller before first use.
  * fastcot_kv_scatter writes canonical k, v (device, [S][Hkv][Dh], `dtype`) into that layout. */
 size_t fastcot_attn_scratch_bytes(int32_t W, int32_t H, int32_t Dh);

@@ -267,15 +267,15 @@ class Context:
 
 # ---------------------------------------------------------------------------- kernel isolation
 def kv_scatter(k, v, max_seq: int):
-    """k, v: device tensors [S, Hkv, Dh] (bf16 or fp32) -> (k_cache [Hkv,max_seq,Dh], vt_cache [Hkv,max_seq/32,Dh,32]);
-    max_seq must be a multiple of 32."""
+    """k, v: device tensors [S, Hkv, Dh] (bf16 or fp32) -> (k_cache, vt_cache), each [Hkv, max_seq/32, 32*Dh] in the
+    library's blocked fragment order; max_seq and Dh must be multiples of 32."""
     torch = _torch()
     S, Hkv, Dh = k.shape
     dt = 0 if k.dtype == torch.float32 else 1
-    kc = torch.zeros(Hkv, max_seq, Dh, dtype=k.dtype, device="cuda")
+    kc = torch.zeros(Hkv, max_seq // 32, 32 * Dh, dtype=k.dtype, device="cuda")
     if max_seq % 32:
         raise ValueError("max_seq must be a multiple of 32")
-    vc = torch.zeros(Hkv, max_seq // 32, Dh, 32, dtype=k.dtype, device="cuda")
+    vc = torch.zeros(Hkv, max_seq // 32, 32 * Dh, dtype=k.dtype, device="cuda")
     _check(lib().fastcot_kv_scatter(k.data_ptr(), v.data_ptr(), S, Hkv, Dh, max_seq, dt, kc.data_ptr(), vc.data_ptr(),
                                     _stream_ptr()))
     return kc, vc
@@ -285,7 +285,7 @@ def attn_window(q, kc, vc, n: int, scratch=None):
     """q: device fp32 [W,H,Dh]; kc/vc from kv_scatter; returns out fp32 [W, H*Dh]."""
     torch = _torch()
     W, H, Dh = q.shape
-    Hkv, max_seq = kc.shape[0], kc.shape[1]
+    Hkv, max_seq = kc.shape[0], kc.shape[1] * 32
     dt = 0 if kc.dtype == torch.float32 else 1
     if scratch is None:
         scratch = torch.zeros(lib().fastcot_attn_scratch_bytes(W, H, Dh), dtype=torch.uint8, device="cuda")

@@ -70,7 +70,7 @@ static int valid_cfg(const fastcot_config* c) {
         c->d_ffn <= 0 || c->vocab <= 0 || c->max_batch <= 0 || c->max_seq <= 0 || c->window <= 0) return 0;
     if (c->dtype != FASTCOT_F32 && c->dtype != FASTCOT_BF16) return 0;
     if (c->n_heads % c->n_kv_heads) return 0;
-    if (c->head_dim % 16 || c->d_model % 16 || c->d_ffn % 16 || c->vocab % 16) return 0;
+    if (c->head_dim % 32 || c->d_model % 16 || c->d_ffn % 16 || c->vocab % 16) return 0;
     if (c->dtype == FASTCOT_BF16 && (c->d_model % 32 || c->d_ffn % 32 || (c->n_heads * c->head_dim) % 32)) return 0;
     if (c->max_seq > 16000 || c->max_seq < 2 * c->window) return 0;
     if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return 0;

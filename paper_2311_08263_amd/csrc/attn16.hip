@@ -11,8 +11,10 @@
 // stored transposed, [Dh][positions], so these are 16-byte loads too) and P^T, which is exactly the
 // register layout the score tiles already have, as the B operand.  The two 16-key score tiles of a
 // block interleave keys (tile t row r <-> key 8*(r/4) + 4*t + r%4) so that a lane ends with 8
-// consecutive keys.  Waves are merged through LDS, key splits through a scratch buffer by the last
-// workgroup to arrive, always in index order, so results do not depend on timing.
+// consecutive keys.  Waves are merged through LDS (each wave finishes a quarter of the head), key
+// splits through a scratch buffer by the last workgroup to arrive, always in index order, so results
+// do not depend on timing.  How many of the launched splits work on a sequence is decided at run
+// time from its length.
 #include "attn16.h"
 #include "xwg.h"
 
@@ -38,7 +40,7 @@ __device__ inline void split8(const float* v, Frag& hi, Frag& lo) {
 #define PART_FLOATS (8 * 64 * 4 + 128)   // per (bh, split, qt): O^T tiles, then m[64], l[64] per lane
 
 template <int QT, int KVP>
-__global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
+__global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
     extern __shared__ float lds[];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int lm = lane & 15, g = lane >> 4;
@@ -91,24 +93,23 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
         const int kb = blk << 5;
         Frag (&kf)[KVP][2][4] = r.kf; Frag (&vf)[KVP][8] = r.vf;
         // K tiles (A operand): tile t row r=lm <-> key kb + 8*(lm/4) + 4*t + lm%4 ; dh 32*g + 8*s..
+        // (the cache stores each block as these eight fragments, one contiguous kilobyte each; the loads are
+        // non-temporal: K and V are read once per step, and letting them allocate in L2 cost 40% at batch 8)
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            int key = kb + 8 * (lm >> 2) + 4 * t + (lm & 3);
-            if (key > a.S - 1) key = a.S - 1;
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int pl = 0; pl < KVP; ++pl) {
-                const u32x4_t* kp = (const u32x4_t*)(kbase + pl * plane + (size_t)key * 128 + 32 * g);
+                const u32x4_t* kp = (const u32x4_t*)(kbase + pl * plane + (size_t)blk * 4096) + lane;
 #pragma unroll
-                for (int s = 0; s < 4; ++s) kf[pl][t][s].u = kp[s];
+                for (int s = 0; s < 4; ++s) kf[pl][t][s].u = __builtin_nontemporal_load(kp + (t * 4 + s) * 64);
             }
-        }
         // V^T tiles (A operand): row 16*dt + lm, keys kb + 8*g .. +7
-        // (the V cache is transposed in blocks of 32 positions: block blk is 128 rows of 32 keys, contiguous)
+        // (stored as eight fragments per block as well)
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
             for (int pl = 0; pl < KVP; ++pl)
-                vf[pl][dt].u = *(const u32x4_t*)(vbase + pl * plane + ((size_t)blk * 128 + 16 * dt + lm) * 32 + 8 * g);
+                vf[pl][dt].u = __builtin_nontemporal_load((const u32x4_t*)(vbase + pl * plane + (size_t)blk * 4096) + dt * 64 + lane);
     };
     auto compute = [&](const KV& r, int blk) {
         const int kb = blk << 5;
@@ -165,7 +166,10 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
             }
         }
     };
-    // two register sets: the next block of this wave travels while the current one is used
+    // two register sets: the next block of this wave travels while the current one is used.  With one
+    // query tile there are registers to spare and the scheduler is told to keep all loads of the next
+    // block ahead of the current block's arithmetic; with two tiles the compiler is left to reuse each
+    // register as soon as it is free (two workgroups share a CU instead).
     {
         KV ra, rb;
         int blk = blk0 + wv;
@@ -173,10 +177,12 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
             load(ra, blk);
             for (;;) {
                 load(rb, blk + 4);
+                if (QT == 1) __builtin_amdgcn_sched_barrier(0);
                 compute(ra, blk);
                 blk += 4;
                 if (blk >= blk1) break;
                 load(ra, blk + 4);
+                if (QT == 1) __builtin_amdgcn_sched_barrier(0);
                 compute(rb, blk);
                 blk += 4;
                 if (blk >= blk1) break;
@@ -190,9 +196,10 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
         lrun[qt] += __shfl_xor(lrun[qt], 32, 64);
     }
 
-    // merge the 4 waves: waves 1..3 publish to LDS, wave 0 folds them in order
-    if (wv > 0) {
-        float* dst = lds + (size_t)(wv - 1) * QT * PART_FLOATS;
+    // ---- merge the 4 waves: everyone publishes to LDS, then wave w finishes output tiles 2w and 2w+1
+    // (16 head elements each) over the four partials, in wave order
+    {
+        float* dst = lds + (size_t)wv * QT * PART_FLOATS;
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
 #pragma unroll
@@ -202,64 +209,91 @@ __global__ __launch_bounds__(256) void k_attn16(AttnArgs a) {
         }
     }
     __syncthreads();
-    if (wv > 0) return;
-    auto fold = [&](const float* src, bool global) {
+    f32x4_t o2[QT][2];
+    float mw[QT], lw[QT];
 #pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
-            const float* s = src + qt * PART_FLOATS;
-            const float mo = global ? ld_agent_f32(s + 2048 + lane) : s[2048 + lane];
-            const float lo = global ? ld_agent_f32(s + 2112 + lane) : s[2112 + lane];
-            const float mnew = fmaxf(mrun[qt], mo);
-            const float wa = expf(mrun[qt] - mnew), wb = expf(mo - mnew);
-            lrun[qt] = lrun[qt] * wa + lo * wb;
-            mrun[qt] = mnew;
+    for (int qt = 0; qt < QT; ++qt) {
+        float mv[4], m = NEG_BIG;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
-                f32x4_t o;
-                if (global) {
+        for (int v = 0; v < 4; ++v) { mv[v] = lds[(size_t)(v * QT + qt) * PART_FLOATS + 2048 + lane]; m = fmaxf(m, mv[v]); }
+        float l = 0.f;
+        o2[qt][0] = o2[qt][1] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) o[r] = ld_agent_f32(s + (dt * 64 + lane) * 4 + r);
-                } else o = *(const f32x4_t*)(s + (dt * 64 + lane) * 4);
-                acc[qt][dt] = acc[qt][dt] * wa + o * wb;
-            }
+        for (int v = 0; v < 4; ++v) {
+            const float* src = lds + (size_t)(v * QT + qt) * PART_FLOATS;
+            const float wgt = expf(mv[v] - m);
+            l += src[2112 + lane] * wgt;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) o2[qt][t] += *(const f32x4_t*)(src + ((2 * wv + t) * 64 + lane) * 4) * wgt;
         }
-    };
-    for (int w2 = 1; w2 < 4; ++w2) fold(lds + (size_t)(w2 - 1) * QT * PART_FLOATS, false);
+        mw[qt] = m; lw[qt] = l;
+    }
 
     if (nsp > 1) {
+        // ---- key splits: partial tiles go to memory with agent-scope stores; the last workgroup to
+        // arrive reads all of them back -- every load of the merge is in flight at once (each wave its
+        // two tiles of every split), splits folded in index order
         float* mine = a.part + ((size_t)bh * nsp_max + sp) * QT * PART_FLOATS;
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt)
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) st_agent_f32(mine + qt * PART_FLOATS + (dt * 64 + lane) * 4 + r, acc[qt][dt][r]);
-            st_agent_f32(mine + qt * PART_FLOATS + 2048 + lane, mrun[qt]);
-            st_agent_f32(mine + qt * PART_FLOATS + 2112 + lane, lrun[qt]);
+                for (int r = 0; r < 4; ++r) st_agent_f32(mine + qt * PART_FLOATS + ((2 * wv + t) * 64 + lane) * 4 + r, o2[qt][t][r]);
+            if (wv == 0) {
+                st_agent_f32(mine + qt * PART_FLOATS + 2048 + lane, mw[qt]);
+                st_agent_f32(mine + qt * PART_FLOATS + 2112 + lane, lw[qt]);
+            }
         }
         wait_vmem_done();
-        int old = 0;
-        if (lane == 0) old = arrive_agent(a.cnt + bh);
-        old = __shfl(old, 0, 64);
-        if (old != nsp - 1) return;
+        __syncthreads();                                   // all four waves' stores have completed
+        int* flag = (int*)(lds + 4 * QT * PART_FLOATS);
+        if (tid == 0) *flag = arrive_agent(a.cnt + bh);
+        __syncthreads();
+        if (*flag != nsp - 1) return;
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
-            mrun[qt] = NEG_BIG; lrun[qt] = 0.f;
+            float m = NEG_BIG, l = 0.f;
+            o2[qt][0] = o2[qt][1] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+            for (int s0 = 0; s0 < nsp; s0 += 4) {          // four splits' loads in flight at a time
+                float ms[4], ls[4];
+                f32x4_t os[4][2];
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) acc[qt][dt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+                for (int u = 0; u < 4; ++u) {
+                    const int s2 = s0 + u < nsp ? s0 + u : nsp - 1;
+                    const float* src = a.part + ((size_t)bh * nsp_max + s2) * QT * PART_FLOATS + qt * PART_FLOATS;
+                    ms[u] = ld_agent_f32(src + 2048 + lane);
+                    ls[u] = ld_agent_f32(src + 2112 + lane);
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) os[u][t][r] = ld_agent_f32(src + ((2 * wv + t) * 64 + lane) * 4 + r);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const bool valid = s0 + u < nsp;
+                    const float mu = valid ? ms[u] : NEG_BIG;
+                    const float mnew = fmaxf(m, mu);
+                    const float wa = expf(m - mnew), wb = valid ? expf(mu - mnew) : 0.f;
+                    l = l * wa + ls[u] * wb;
+                    o2[qt][0] = o2[qt][0] * wa + os[u][0] * wb;
+                    o2[qt][1] = o2[qt][1] * wa + os[u][1] * wb;
+                    m = mnew;
+                }
+            }
+            lw[qt] = l;
         }
-        for (int s2 = 0; s2 < nsp; ++s2) fold(a.part + ((size_t)bh * nsp_max + s2) * QT * PART_FLOATS, true);
-        if (lane == 0) st_agent_i32(a.cnt + bh, 0);
+        if (tid == 0) st_agent_i32(a.cnt + bh, 0);
     }
-    // out[row][h*128 + 16*dt + 4*g + r] = O / l
+    // out[row][h*128 + 16*dt + 4*g + r] = O / l, this wave's tiles dt = 2*wv, 2*wv + 1
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         const int j = qt * 16 + lm;
         if (j < a.W) {
-            const float inv = 1.0f / lrun[qt];
+            const float inv = 1.0f / lw[qt];
             float* o = a.out + (size_t)(b * a.W + j) * a.ldo + h * 128 + 4 * g;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) *(f32x4_t*)(o + 16 * dt) = acc[qt][dt] * inv;
+            for (int t = 0; t < 2; ++t) *(f32x4_t*)(o + 16 * (2 * wv + t)) = o2[qt][t] * inv;
         }
     }
 }
@@ -273,7 +307,14 @@ hipError_t fc_attn16(const AttnArgs& a, int Bact, int nsplit, hipStream_t st) {
     if (a.W < 1 || a.W > 32 || nsplit < 1 || nsplit > FC_MAX_ATTN_SPLITS || Bact * a.H > FC_MAX_COUNTERS || a.S < 32 || a.S % 32 || a.bpw < 1)
         return hipErrorInvalidValue;
     dim3 grid(Bact * a.H, nsplit);
-    const size_t l1 = (size_t)3 * PART_FLOATS * 4, l2 = 2 * l1;
+    const size_t l1 = (size_t)4 * PART_FLOATS * 4 + 16, l2 = (size_t)8 * PART_FLOATS * 4 + 16;
+    static bool lds_ok = false;                          // two query tiles need more than the default 64 KB
+    if (!lds_ok) {
+        hipError_t e = hipFuncSetAttribute((const void*)k_attn16<2, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l2);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_attn16<2, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l2);
+        if (e != hipSuccess) return e;
+        lds_ok = true;
+    }
     if (a.kvp == 2) {
         if (a.W > 16) k_attn16<2, 2><<<grid, 256, l2, st>>>(a);
         else k_attn16<1, 2><<<grid, 256, l1, st>>>(a);

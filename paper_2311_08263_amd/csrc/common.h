@@ -72,7 +72,7 @@ enum { FLAG_ALL_DONE = 0, FLAG_ERROR = 1 };
 enum { PARAM_MAX_NEW = 0, PARAM_EOS = 1, PARAM_MAX_STEPS = 2, PARAM_BUF_LEN = 3, PARAM_B = 4 };
 
 struct WorkspaceMap {
-    size_t kc, vc;              // KV cache: K [L][B][Hkv][planes][S][Dh], V transposed in blocks [L][B][Hkv][planes][S/32][Dh][32]
+    size_t kc, vc;              // KV cache [L][B][Hkv][planes][S/32 blocks][32 * Dh] in fragment order (k_index, v_index)
     size_t rope_cos, rope_sin;  // fp32 [S][Dh/2]
     size_t x, nx, qkv, qrot, att, gu, h, logits, topv;
     size_t gemm_part, gemm_cnt, attn_part, attn_cnt, amax_part;
@@ -91,15 +91,26 @@ struct KernelDims {    // model + capacities as the kernels need them
 };
 
 // element offset of plane 0 of one (layer, sequence, kv head) block of the K or V cache; plane p
-// follows at p * S * Dh.  K block is [S][Dh].  V block is transposed in blocks of 32 positions,
-// [S/32][Dh][32] (v_index): the attention kernel reads V^T rows of 32 keys, so one key block of a head is one
-// contiguous piece of 32 * Dh elements instead of Dh pieces of 64 bytes.
+// follows at p * S * Dh.  Inside a plane both caches are cut into blocks of 32 positions (32 * Dh
+// elements), and a block is stored in the order in which the attention kernel's MFMA A-operand
+// fragments want it, so that every 16-byte-per-lane load of a wave reads one contiguous kilobyte
+// (whole cache lines) instead of 64 pieces of 16 bytes:
+//  K: eight fragments (t, s), t = score tile (rows r <-> position 8*(r/4) + 4*t + r%4 of the block),
+//     s = which eight of each 32 head elements; lane = r + 16 * (dh / 32), element dh % 8.
+//  V (transposed): Dh/16 fragments of 16 head elements; lane = dh % 16 + 16 * (position / 8), element
+//     position % 8.
+// S is a multiple of 32 and Dh a multiple of 32.
 __host__ __device__ inline size_t kv_block(const KernelDims& kd, int layer, int b, int kh) {
     return ((((size_t)layer * kd.B + b) * kd.Hkv + kh) * (size_t)kd.kvp) * (size_t)kd.S * kd.Dh;
 }
-
+__host__ __device__ inline size_t k_index(int pos, int dh, int Dh) {
+    const int kk = pos & 31, t = (kk >> 2) & 1, r = 4 * (kk >> 3) + (kk & 3);
+    const int G = Dh >> 5, s = (dh & 31) >> 3, lane = r + 16 * (dh >> 5);
+    return (size_t)(pos >> 5) * 32 * Dh + (size_t)((t * 4 + s) * 16 * G + lane) * 8 + (dh & 7);
+}
 __host__ __device__ inline size_t v_index(int dh, int pos, int Dh) {
-    return ((size_t)(pos >> 5) * Dh + dh) * 32 + (pos & 31);
+    const int kk = pos & 31;
+    return (size_t)(pos >> 5) * 32 * Dh + (size_t)((dh >> 4) * 64 + (dh & 15) + 16 * (kk >> 3)) * 8 + (kk & 7);
 }
 
 int fc_build_maps(const fastcot_config* cfg, ModelMap* mm, WorkspaceMap* wm, KernelDims* kd);

@@ -40,9 +40,9 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     p->lm = mk(kd.d, kd.V);
     int nb = (kd.S + 31) / 32, sp = (nb + 7) / 8;
     if (sp > FC_MAX_ATTN_SPLITS) sp = FC_MAX_ATTN_SPLITS;
-    while (sp > 1 && kd.B * kd.H * sp > 768) --sp;     // measured (batch 8, 40 heads): 2 splits best, 6 are 40% slower
+    while (sp > 1 && kd.B * kd.H * sp > 512) --sp;     // measured (batch 8, 40 heads): 1 split 75 us, 2 splits 102 us
     p->attn_splits = sp < 1 ? 1 : sp;
-    p->attn_bpw = 8;
+    p->attn_bpw = 4;     // measured (7B shape, 350 positions): 3-4 key blocks per workgroup, about one per wave
     // column-owner kernel: workgroups per GEMM (one per CU where the matrix allows)
     const int nts[5] = {kd.qkvN / 16, kd.d / 16, 2 * kd.F / 16, kd.d / 16, kd.V / 16};
     // measured on the 7B shape: one workgroup per CU, one weight batch in flight per wave; the O
@@ -174,7 +174,7 @@ hipError_t fc_fast_forward(const FastArgs& a) {
 __global__ void k_set_i32(int32_t* p, int32_t v) { if (threadIdx.x == 0) *p = v; }
 
 static int iso_attn_splits(int S) {
-    int nb = (S + 31) / 32, sp = (nb + 7) / 8;
+    int nb = (S + 31) / 32, sp = (nb + 3) / 4;
     return sp < 1 ? 1 : (sp > FC_MAX_ATTN_SPLITS ? FC_MAX_ATTN_SPLITS : sp);
 }
 // scratch: [0,256) the committed length; [256, 256+4*H) counters; then split partials
@@ -192,7 +192,7 @@ hipError_t fc_attn_iso(const float* q, const void* kc, const void* vc, int n, in
     AttnArgs at; memset(&at, 0, sizeof(at));
     at.q = q; at.ldq = H * 128; at.kc = (const bf16_t*)kc; at.vc = (const bf16_t*)vc; at.layer = 0; at.B = 1; at.H = H;
     at.Hkv = Hkv; at.S = S; at.W = W; at.kvp = 1; at.n_state = (const int32_t*)sc; at.out = out; at.ldo = H * 128;
-    at.cnt = (int32_t*)(sc + 256); at.bpw = 8;
+    at.cnt = (int32_t*)(sc + 256); at.bpw = 4;
     at.part = (float*)(sc + 256 + (((size_t)H * 4 + 255) & ~(size_t)255));
     return fc_attn16(at, 1, iso_attn_splits(n + W), st);
 }

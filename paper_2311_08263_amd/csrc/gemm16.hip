@@ -277,12 +277,13 @@ __global__ __launch_bounds__(512) void k_gemm16(Gemm16Args a) {
                     float* q = a.out + (size_t)m * a.ldo + hh * 128;
                     q[i] = r0; q[i + 64] = r1;
                 } else {
-                    bf16_t* kr = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + (hh - a.H)) * a.kvp) * plane + (size_t)pos * 128;
+                    bf16_t* kr = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + (hh - a.H)) * a.kvp) * plane;
+                    const size_t i0 = k_index(pos, i, 128), i1 = k_index(pos, i + 64, 128);
                     const uint32_t h0 = bf16_rne_bits(r0), h1 = bf16_rne_bits(r1);
-                    kr[i] = (bf16_t)h0; kr[i + 64] = (bf16_t)h1;
+                    kr[i0] = (bf16_t)h0; kr[i1] = (bf16_t)h1;
                     if (a.kvp == 2) {
-                        kr[plane + i] = (bf16_t)bf16_rne_bits(r0 - bf16_bits_f32(h0));
-                        kr[plane + i + 64] = (bf16_t)bf16_rne_bits(r1 - bf16_bits_f32(h1));
+                        kr[plane + i0] = (bf16_t)bf16_rne_bits(r0 - bf16_bits_f32(h0));
+                        kr[plane + i1] = (bf16_t)bf16_rne_bits(r1 - bf16_bits_f32(h1));
                     }
                 }
             }

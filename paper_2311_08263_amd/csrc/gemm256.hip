@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int nt = nt0 + j < a.NT ? nt0 + j : a.NT - 1;
-            wt[j] = Wp[((size_t)nt * KT + kc) * 64];
+            wt[j] = Wp[((size_t)nt * KT + kc) * 64];       // plain loads: the row blocks of a column block share these lines in L2
         }
     };
 
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
                     if (pk) {
                         if (hh < a.H) *(f32x4_t*)(a.out + (size_t)row * a.ldo + hh * 128 + el) = rr;
                         else {
-                            bf16_t* kr = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + (hh - a.H)) * a.kvp) * plane + (size_t)pos * 128 + el;
+                            bf16_t* kr = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + (hh - a.H)) * a.kvp) * plane + k_index(pos, el, 128);
                             uint32_t h[4];
 #pragma unroll
                             for (int e = 0; e < 4; ++e) h[e] = rne16(rr[e]);
@@ -240,8 +240,8 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const uint32_t h0 = rne16(v[e]);
-                        vr[e * 32] = (bf16_t)h0;
-                        if (a.kvp == 2) vr[e * 32 + plane] = (bf16_t)rne16(v[e] - up16(h0));
+                        vr[e * 8] = (bf16_t)h0;
+                        if (a.kvp == 2) vr[e * 8 + plane] = (bf16_t)rne16(v[e] - up16(h0));
                     }
                 }
             } else if (EPI == EPI_LMHEAD) {

@@ -199,7 +199,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
                 if (ok) {
                     if (hh < a.H) *(f32x4_t*)(a.out + (size_t)m * a.ldo + hh * 128 + el) = r;
                     else {
-                        bf16_t* kr = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + (hh - a.H)) * a.kvp) * plane + (size_t)pos * 128 + el;
+                        bf16_t* kr = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + (hh - a.H)) * a.kvp) * plane + k_index(pos, el, 128);
                         uint32_t h[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) h[e] = rne16(r[e]);
@@ -218,8 +218,8 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const uint32_t h0 = rne16(v[e]);
-                    vr[e * 32] = (bf16_t)h0;
-                    if (a.kvp == 2) vr[e * 32 + plane] = (bf16_t)rne16(v[e] - up16(h0));
+                    vr[e * 8] = (bf16_t)h0;
+                    if (a.kvp == 2) vr[e * 8 + plane] = (bf16_t)rne16(v[e] - up16(h0));
                 }
             }
         }

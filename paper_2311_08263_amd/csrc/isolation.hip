@@ -28,7 +28,7 @@ extern "C" size_t fastcot_attn_scratch_bytes(int32_t W, int32_t H, int32_t Dh) {
 
 extern "C" int fastcot_kv_scatter(const void* d_k, const void* d_v, int32_t S, int32_t Hkv, int32_t Dh, int32_t max_seq,
                                   int32_t dtype, void* d_k_cache, void* d_vt_cache, void* hip_stream) {
-    if (!d_k || !d_v || !d_k_cache || !d_vt_cache || S <= 0 || S > max_seq || max_seq % 32 || Hkv <= 0 || Dh <= 0 ||
+    if (!d_k || !d_v || !d_k_cache || !d_vt_cache || S <= 0 || S > max_seq || max_seq % 32 || Hkv <= 0 || Dh <= 0 || Dh % 32 ||
         (dtype != FASTCOT_F32 && dtype != FASTCOT_BF16)) return FASTCOT_EINVAL;
     hipError_t e = fc_kv_scatter(d_k, d_v, S, Hkv, Dh, max_seq, dtype, d_k_cache, d_vt_cache, (hipStream_t)hip_stream);
     return e == hipSuccess ? 0 : FASTCOT_EHIP;
@@ -38,7 +38,7 @@ extern "C" int fastcot_attn_window(const float* d_q, const void* d_k_cache, cons
                                    int32_t H, int32_t Hkv, int32_t Dh, int32_t max_seq, int32_t dtype, float* d_out,
                                    void* d_scratch, void* hip_stream) {
     if (!d_q || !d_k_cache || !d_vt_cache || !d_out || !d_scratch) return FASTCOT_EINVAL;
-    if (n < 0 || W <= 0 || H <= 0 || Hkv <= 0 || H % Hkv || Dh <= 0 || Dh % 16 || max_seq > 16000 || max_seq % 32) return FASTCOT_EINVAL;
+    if (n < 0 || W <= 0 || H <= 0 || Hkv <= 0 || H % Hkv || Dh <= 0 || Dh % 32 || max_seq > 16000 || max_seq % 32) return FASTCOT_EINVAL;
     if (dtype != FASTCOT_F32 && dtype != FASTCOT_BF16) return FASTCOT_EINVAL;
     if (n + W > max_seq) return FASTCOT_ECAPACITY;
     hipStream_t st = (hipStream_t)hip_stream;

@@ -355,12 +355,13 @@ __global__ __launch_bounds__(512) void k_step(PersistArgs a) {
                             float* q = a.q + (size_t)m * (a.H * 128) + hh * 128;
                             st_agent_f32(q + i, r0); st_agent_f32(q + i + 64, r1);
                         } else {
-                            bf16_t* kr = a.kc + ((((size_t)layer * a.B + b) * a.Hkv + (hh - a.H)) * a.kvp) * plane + (size_t)pos * 128;
+                            bf16_t* kr = a.kc + ((((size_t)layer * a.B + b) * a.Hkv + (hh - a.H)) * a.kvp) * plane;
+                            const size_t i0 = k_index(pos, i, 128), i1 = k_index(pos, i + 64, 128);
                             const uint32_t h0 = rne16(r0), h1 = rne16(r1);
-                            st_agent_u16(kr + i, h0); st_agent_u16(kr + i + 64, h1);
+                            st_agent_u16(kr + i0, h0); st_agent_u16(kr + i1, h1);
                             if (a.kvp == 2) {
-                                st_agent_u16(kr + plane + i, rne16(r0 - up16(h0)));
-                                st_agent_u16(kr + plane + i + 64, rne16(r1 - up16(h1)));
+                                st_agent_u16(kr + plane + i0, rne16(r0 - up16(h0)));
+                                st_agent_u16(kr + plane + i1, rne16(r1 - up16(h1)));
                             }
                         }
                     }
@@ -465,17 +466,15 @@ __global__ __launch_bounds__(512) void k_step(PersistArgs a) {
                 f32x4_t sc[2];
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    int key = kb + 8 * (lm >> 2) + 4 * t + (lm & 3);
-                    if (key > a.S - 1) key = a.S - 1;
-                    const bf16_t* kp = kbase + (size_t)key * 128 + 32 * g4;
+                    const bf16_t* kp = kbase + (size_t)blk * 4096 + (size_t)(t * 4 * 64 + lane) * 8;   // fragment (t, s) at + s * 512
                     sc[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int s = 0; s < 4; ++s) {
-                        Frag kf; kf.u = ld_kv16(kp + 8 * s, coh);
+                        Frag kf; kf.u = ld_kv16(kp + 512 * s, coh);
                         sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qh[s].v, sc[t], 0, 0, 0);
                         sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, ql[s].v, sc[t], 0, 0, 0);
                         if (two) {
-                            Frag kl; kl.u = ld_kv16(kp + plane + 8 * s, coh);
+                            Frag kl; kl.u = ld_kv16(kp + plane + 512 * s, coh);
                             sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kl.v, qh[s].v, sc[t], 0, 0, 0);
                         }
                     }
@@ -508,7 +507,7 @@ __global__ __launch_bounds__(512) void k_step(PersistArgs a) {
                 split8(p, ph, pl);
 #pragma unroll
                 for (int dt = 0; dt < 8; ++dt) {
-                    const bf16_t* vp = vbase + ((size_t)(kb >> 5) * 128 + 16 * dt + lm) * 32 + 8 * g4;
+                    const bf16_t* vp = vbase + (size_t)(kb >> 5) * 4096 + (size_t)(dt * 64 + lane) * 8;
                     Frag vf; vf.u = ld_kv16(vp, coh);
                     acc[dt] *= alpha;
                     acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, ph.v, acc[dt], 0, 0, 0);

@@ -122,9 +122,9 @@ __global__ void k_rope_cache(const float* qkv, float* qrot, KernelDims kd, int l
             q[e] = ra; q[e + half] = rb;
         } else {
             int kh = hh - kd.H;
-            size_t base = kv_block(kd, layer, b, kh) + (size_t)pos * kd.Dh;
-            kvstore<DT>(kc, base + e, plane, kd.kvp, ra);
-            kvstore<DT>(kc, base + e + half, plane, kd.kvp, rb);
+            size_t base = kv_block(kd, layer, b, kh);
+            kvstore<DT>(kc, base + k_index(pos, e, kd.Dh), plane, kd.kvp, ra);
+            kvstore<DT>(kc, base + k_index(pos, e + half, kd.Dh), plane, kd.kvp, rb);
         }
     }
     const float* vrow = row + (size_t)(kd.H + kd.Hkv) * kd.Dh;
@@ -158,7 +158,7 @@ __global__ void k_attn_plain(const float* q, int ldq, const void* kc, const void
     float mx = -3.0e38f;
     for (int t = threadIdx.x; t <= last; t += blockDim.x) {
         float s = 0;
-        for (int i = 0; i < kd.Dh; ++i) s += qv[i] * kvload<DT>(kc, kbase + (size_t)t * kd.Dh + i, plane, kd.kvp);
+        for (int i = 0; i < kd.Dh; ++i) s += qv[i] * kvload<DT>(kc, kbase + k_index(t, i, kd.Dh), plane, kd.kvp);
         s *= scale;
         sc[t] = s;
         mx = fmaxf(mx, s);
@@ -271,17 +271,17 @@ hipError_t fc_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s
     return hipGetLastError();
 }
 
-// canonical K, V [S_in][Hkv][Dh] -> cache layout of one sequence: K [Hkv][S][Dh], V^T [Hkv][S/32][Dh][32]
+// canonical K, V [S_in][Hkv][Dh] -> cache layout of one sequence: per head [S/32 blocks][32 * Dh] in fragment order (k_index, v_index)
 template <int DT>
 __global__ void k_kv_scatter(const void* k, const void* v, int S_in, int Hkv, int Dh, int S, void* kc, void* vc) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (size_t)S_in * Hkv * Dh) return;
     int e = (int)(i % Dh), h = (int)((i / Dh) % Hkv), t = (int)(i / ((size_t)Dh * Hkv));
     if (DT == FASTCOT_F32) {
-        ((float*)kc)[((size_t)h * S + t) * Dh + e] = ((const float*)k)[i];
+        ((float*)kc)[(size_t)h * S * Dh + k_index(t, e, Dh)] = ((const float*)k)[i];
         ((float*)vc)[(size_t)h * Dh * S + v_index(e, t, Dh)] = ((const float*)v)[i];
     } else {
-        ((bf16_t*)kc)[((size_t)h * S + t) * Dh + e] = ((const bf16_t*)k)[i];
+        ((bf16_t*)kc)[(size_t)h * S * Dh + k_index(t, e, Dh)] = ((const bf16_t*)k)[i];
         ((bf16_t*)vc)[(size_t)h * Dh * S + v_index(e, t, Dh)] = ((const bf16_t*)v)[i];
     }
 }

@@ -114,10 +114,11 @@ def test_attention_isolation(fc, n, W, H, Hkv):
     print(f"attention max |d| {err:.3e}")
     assert err < 1e-4
     # garbage (finite) beyond the visible range must not matter: positions >= n+W are never read as visible
-    kc2, vc2 = kc.clone(), vc.clone()
-    kc2[:, n + W:, :] = 7.0
-    beyond = (torch.arange(S, device="cuda") >= n + W).view(S // 32, 32)   # vt_cache is [Hkv][S/32][Dh][32]
-    vc2.permute(0, 2, 1, 3)[:, :, beyond] = -9.0
+    kg = np.concatenate([kb, np.full((S - n - W, Hkv, Dh), 0x40E0, dtype=kb.dtype)])      # bf16 7.0
+    vg = np.concatenate([vb, np.full((S - n - W, Hkv, Dh), 0xC110, dtype=vb.dtype)])      # bf16 -9.0
+    kc2, vc2 = fc.kv_scatter(torch.from_numpy(kg.view(np.int16)).cuda().view(torch.bfloat16),
+                             torch.from_numpy(vg.view(np.int16)).cuda().view(torch.bfloat16), S)
+    assert not torch.equal(kc, kc2) and not torch.equal(vc, vc2)
     out2 = fc.attn_window(torch.from_numpy(q).cuda(), kc2, vc2, n)
     assert torch.equal(out, out2)
 
