@@ -145,6 +145,9 @@ enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLAN
        FASTCOT_OPT_NW_LM = 26,
        FASTCOT_OPT_ATTN_BLOCKS = 28, /* key blocks of 32 positions per attention workgroup: of the launched
                                       * splits, ceil(blocks / value) work on a sequence, the rest exit */
+       /* K slices per column owner of the column-owner GEMM for the O / down projections (1..8; the
+        * workgroup count must be a multiple of it) */
+       FASTCOT_OPT_KS_O = 32, FASTCOT_OPT_KS_DOWN = 33,
        FASTCOT_OPT_CO_SINGLE = 27,   /* 1: one weight batch in flight per wave (two workgroups per CU) */
        /* debug: run only the first `value` stages of a forward (per layer: QKV, attention, O,
         * gate/up, down); negative = all */

@@ -263,7 +263,17 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
         const int NT = nts[option - FASTCOT_OPT_NW_QKV];
         if (value < 0 || value > NT || (value > 0 && (NT + value - 1) / value > 8))
             return fail(c, FASTCOT_EINVAL, "workgroups of the column-owner GEMM: 0 (split-K kernel) or NT/8 .. NT%s");
-        c->plan.nw[option - FASTCOT_OPT_NW_QKV] = value;
+        const int gi = option - FASTCOT_OPT_NW_QKV, ks = c->plan.ks[gi] > 1 ? c->plan.ks[gi] : 1;
+        if (value > 0 && (value % ks || value / ks > NT || (NT + value / ks - 1) / (value / ks) > 8))
+            return fail(c, FASTCOT_EINVAL, "workgroups of the column-owner GEMM do not fit its K slices per owner%s");
+        c->plan.nw[gi] = value;
+    } else if (option == FASTCOT_OPT_KS_O || option == FASTCOT_OPT_KS_DOWN) {
+        const int gi = option == FASTCOT_OPT_KS_O ? 1 : 3, NT = c->kd.d / 16, nw = c->plan.nw[gi];
+        const int K = gi == 1 ? c->kd.H * c->kd.Dh : c->kd.F;
+        if (value < 1 || value > 8 || K / 256 < value) return fail(c, FASTCOT_EINVAL, "K slices per owner out of range%s");
+        if (nw > 0 && (nw % value || nw / value > NT || nw / value < 1 || (NT + nw / value - 1) / (nw / value) > 8))
+            return fail(c, FASTCOT_EINVAL, "K slices per owner do not fit the workgroup count of that GEMM%s");
+        c->plan.ks[gi] = value;
     } else if (option == FASTCOT_OPT_CO_SINGLE) c->plan.co_single = value != 0;
     else if (option == FASTCOT_OPT_ATTN_SPLITS) {
         if (value < 1 || value > FC_MAX_ATTN_SPLITS) return fail(c, FASTCOT_EINVAL, "attention splits out of range%s");

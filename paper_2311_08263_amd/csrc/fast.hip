@@ -47,8 +47,16 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     const int nts[5] = {kd.qkvN / 16, kd.d / 16, 2 * kd.F / 16, kd.d / 16, kd.V / 16};
     // measured on the 7B shape: one workgroup per CU, one weight batch in flight per wave; the O
     // projection (few columns, short K) is faster through the split-K kernel
-    for (int i = 0; i < 5; ++i) p->nw[i] = fc_gemmco_grid(nts[i]);
-    if (nts[1] < 512) p->nw[1] = 0;     // fewer than two n-tiles per CU
+    for (int i = 0; i < 5; ++i) { p->nw[i] = fc_gemmco_grid(nts[i]); p->ks[i] = 1; }
+    if (nts[1] < 512) {                  // O projection with fewer than two n-tiles per CU
+        // measured at the 7B shape: two K slices per owner (16.6 us) beat the split-K kernel (17.6 us)
+        const int G = p->nw[1], K = kd.H * kd.Dh;
+        if (G % 2 == 0 && G / 2 <= nts[1] && (nts[1] + G / 2 - 1) / (G / 2) <= 8 && K >= 2048) p->ks[1] = 2;
+        else p->nw[1] = 0;
+    }
+    // down projection: K is long and the columns few, so every workgroup would read far more activation
+    // bytes than weight bytes; K slices per owner cut that (measured at the 7B shape)
+    if (kd.F >= 2 * kd.d && kd.F >= 4096 && p->nw[3] % 4 == 0 && p->nw[3] / 4 <= nts[3] && (nts[3] + p->nw[3] / 4 - 1) / (p->nw[3] / 4) <= 8) p->ks[3] = 4;
     p->co_single = 1;
 }
 
@@ -111,7 +119,8 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         const int nw = M <= 16 ? a.plan->nw[gi] : 0;      // workgroups of the column-owner kernel, 0 = split-K kernel
         if (nw > 0) {
             co.W = (const bf16_t*)W; co.K = K; co.NT = N / 16; co.X = X; co.ldx = ldx; co.gain = gain; co.out = out; co.ldo = ldo;
-            co.layer = g.layer;
+            co.layer = g.layer; co.ks = epi == EPI_RESID ? a.plan->ks[gi] : 1;
+            co.xpart = (float*)(ws + wm.gemm_part); co.xcnt = (int32_t*)(ws + wm.gemm_cnt);
             co.amax_idx = (int32_t*)(co.amax_val + (size_t)nw * 16);
             return fc_gemmco(epi, co, nw, a.st);
         }

@@ -15,10 +15,14 @@ struct GemmCoArgs {
     bf16_t* kc; bf16_t* vc;
     int32_t layer, H, Hkv, B, S, Wn, kvp;
     float* amax_val; int32_t* amax_idx;   // LM head: winners per workgroup [workgroups][16]
+    int32_t ks;            // EPI_RESID only: workgroups per column owner, each taking 1/ks of K (1..8)
+    float* xpart;          // ks > 1: partial tiles [workgroup][8][64 lanes][4]
+    int32_t* xcnt;         // ks > 1: one arrival counter per owner, zero between launches
     int32_t single_buffer; // one batch in flight per wave (fewer registers: two workgroups per CU) instead of two
 };
 
-// G workgroups; workgroup i owns n-tiles [i*NT/G, (i+1)*NT/G), at most 8; fc_gemmco_grid picks one
-// workgroup per CU (all resident, one round) unless the matrix is wider than 8 n-tiles per CU
+// G workgroups = G / ks owners x ks K slices; owner i owns n-tiles [i*NT/owners, (i+1)*NT/owners), at most
+// 8; fc_gemmco_grid picks one workgroup per CU (all resident, one round) unless the matrix is wider than
+// 8 n-tiles per CU
 int fc_gemmco_grid(int NT);
 hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st);

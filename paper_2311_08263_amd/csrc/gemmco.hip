@@ -3,13 +3,18 @@
 // A workgroup of 8 waves owns NW n-tiles (16 output columns each) over the whole of K; wave w
 // takes the w-th eighth of K.  No workgroup ever needs another workgroup's result: the eight
 // partial tiles meet in LDS, then waves 0..NW-1 each finish one tile and run the fused epilogue.
-// Compared with slicing K across workgroups this trades the global hand-off (partial tiles through
+// For the residual GEMMs with long K and few columns (down, O) the workgroups of a launch can also be
+// grouped ks to an owner, each taking 1/ks of K and so reading only 1/ks of the activations (at the 7B
+// shape the down projection reads 704 KB of activations per workgroup against 352 KB of weights); the ks
+// partial tiles (1 KB each) meet through memory and the last workgroup to arrive adds them in slice order.
+// Compared with slicing K across workgroups everywhere this trades the global hand-off (partial tiles through
 // memory, an atomic counter, a second pass by the last arriver) for more activation reads out of
 // L2: every workgroup reads all 16 x K activations, straight into registers in MFMA B-fragment
 // order (lane = row % 16 + 16 * k-octet: two 16-byte loads per k-tile), converts them to a bf16
 // hi + lo pair and reuses each fragment for its NW weight tiles.  Weights stream HBM -> VGPR once,
 // in MFMA fragment order, KB k-tiles x NW n-tiles per batch.
 #include "gemmco.h"
+#include "xwg.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
@@ -39,12 +44,15 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int lm = lane & 15, g4 = lane >> 4;
     // workgroup i owns n-tiles [i*NT/G, (i+1)*NT/G): at most NW of them
-    const int G = gridDim.x;
-    const int nt0 = (int)(((unsigned)blockIdx.x * (unsigned)a.NT) / (unsigned)G);
-    const int nt1 = (int)(((unsigned)(blockIdx.x + 1) * (unsigned)a.NT) / (unsigned)G);
-    const int KT = a.K >> 5, KTw = KT >> 3;
-    const int kt_begin = w * KTw, kt_end = kt_begin + KTw;
-    const int nb = (KTw + KB - 1) / KB;
+    const int ks = (EPI == EPI_RESID && a.ks > 1) ? a.ks : 1;
+    const int G = gridDim.x / ks, owner = blockIdx.x / ks, slice = blockIdx.x % ks;
+    const int nt0 = (int)(((unsigned)owner * (unsigned)a.NT) / (unsigned)G);
+    const int nt1 = (int)(((unsigned)(owner + 1) * (unsigned)a.NT) / (unsigned)G);
+    // this workgroup's K slice in k-tiles, cut in eight for the waves (ragged cuts allowed)
+    const int KT = a.K >> 5;
+    const int s_lo = (int)((unsigned)KT * (unsigned)slice / (unsigned)ks), s_len = (int)((unsigned)KT * (unsigned)(slice + 1) / (unsigned)ks) - s_lo;
+    const int kt_begin = s_lo + ((w * s_len) >> 3), kt_end = s_lo + (((w + 1) * s_len) >> 3);
+    const int nb = (((s_len + 7) >> 3) + KB - 1) / KB;          // batches of the longest wave
     const int row = lm < a.M ? lm : a.M - 1;            // rows past M repeat a valid row; never written
     const float* xr = a.X + (size_t)row * a.ldx + 8 * g4;
     const u32x4_t* wbase = (const u32x4_t*)a.W + lane;
@@ -160,6 +168,33 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         v *= rs;
     }
     const int m = lm;
+    if (EPI == EPI_RESID && ks > 1) {
+        // partial tiles of the ks slices meet through memory; the last workgroup to arrive adds them
+        float* mine = a.xpart + ((size_t)blockIdx.x * 8 + w) * 256 + lane * 4;
+        if (fin) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) st_agent_f32(mine + r, v[r]);
+        }
+        wait_vmem_done();
+        __syncthreads();
+        int* flag = (int*)lds_ss;
+        if (tid == 0) *flag = arrive_agent(a.xcnt + owner);
+        __syncthreads();
+        if (*flag != ks - 1) return;
+        if (fin) {
+            f32x4_t part[8];
+#pragma unroll
+            for (int s2 = 0; s2 < 8; ++s2) {
+                const float* src = a.xpart + ((size_t)(owner * ks + (s2 < ks ? s2 : 0)) * 8 + w) * 256 + lane * 4;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) part[s2][r] = ld_agent_f32(src + r);
+            }
+            v = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s2 = 0; s2 < 8; ++s2) if (s2 < ks) v += part[s2];
+        }
+        if (tid == 0) st_agent_i32(a.xcnt + owner, 0);
+    }
     if (EPI == EPI_RESID) {
         if (fin && m < a.M) {
             f32x4_t* o = (f32x4_t*)(a.out + (size_t)m * a.ldo + nt * 16 + 4 * g4);
@@ -284,7 +319,8 @@ static hipError_t launch_k(const GemmCoArgs& a, int G, hipStream_t st) {
 }
 template <int EPI>
 static hipError_t launch_epi(const GemmCoArgs& a, int G, hipStream_t st) {
-    const int nw = (a.NT + G - 1) / G;           // most n-tiles any workgroup owns
+    const int owners = G / (a.ks > 1 ? a.ks : 1);
+    const int nw = (a.NT + owners - 1) / owners;  // most n-tiles any workgroup owns
     if (a.single_buffer) {
         switch (nw) {
             case 1: return launch_k<EPI, 1, 8, false>(a, G, st);
@@ -308,7 +344,11 @@ static hipError_t launch_epi(const GemmCoArgs& a, int G, hipStream_t st) {
 }
 
 hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st) {
-    if (a.M < 1 || a.M > 16 || a.K % 256 || a.NT < 1 || G < 1 || G > a.NT || (a.NT + G - 1) / G > 8) return hipErrorInvalidValue;
+    const int ks = a.ks > 1 ? a.ks : 1;
+    if (a.M < 1 || a.M > 16 || a.K % 256 || a.NT < 1 || G < 1 || ks > 8 || G % ks || G / ks > a.NT ||
+        (a.NT + G / ks - 1) / (G / ks) > 8 || a.K / 256 < ks)
+        return hipErrorInvalidValue;
+    if (ks > 1 && (epi != EPI_RESID || !a.xpart || !a.xcnt || G / ks > FC_MAX_COUNTERS)) return hipErrorInvalidValue;
     switch (epi) {
         case EPI_RESID: return launch_epi<EPI_RESID>(a, G, st);
         case EPI_SWIGLU: return launch_epi<EPI_SWIGLU>(a, G, st);
