@@ -104,8 +104,18 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
     }
     KernelDims k;
     k.L = c->n_layers; k.d = d; k.H = c->n_heads; k.Hkv = c->n_kv_heads; k.Dh = c->head_dim; k.F = F;
-    k.V = c->vocab; k.B = c->max_batch; k.S = (c->max_seq + 31) & ~31; k.W = c->window; k.M = k.B * k.W;
+    k.V = c->vocab; k.B = c->max_batch; k.S = (c->max_seq + 31) & ~31; k.W = c->window;
     k.qkvN = qd + 2 * kvd; k.eps = c->rms_eps; k.esz = (int)esz; k.kvp = c->dtype == FASTCOT_BF16 ? 2 : 1;
+    // prefill runs the same kernels over chunks of the prompt; where the matrix-core path covers the
+    // shape a chunk is up to 256 rows per sequence (at most 512 rows in all), else one window
+    k.Wcap = k.W; k.M = k.B * k.W;
+    if (fc_fast_supported(k, k.M)) {
+        int ch = 256;
+        while (ch > 32 && k.B * ch > 512) ch >>= 1;
+        if (ch > k.S) ch = k.S;
+        if (ch > k.Wcap) k.Wcap = ch;
+    }
+    k.M = k.B * k.Wcap;
     if (kd) *kd = k;
     if (wm) {
         size_t cur = 0;
@@ -127,7 +137,7 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
         StateMap s; int w = 0;
         auto ti = [&](int words) { int o = w; w += (words + 3) & ~3; return o; };
         s.n = ti(k.B); s.g = ti(k.B); s.done = ti(k.B); s.steps = ti(k.B); s.newest = ti(k.B); s.lastK = ti(k.B);
-        s.plen = ti(k.B); s.olen = ti(k.B); s.win = ti(k.B * k.W); s.o = ti(k.B * k.W);
+        s.plen = ti(k.B); s.olen = ti(k.B); s.win = ti(k.B * k.Wcap); s.o = ti(k.B * k.Wcap);
         s.buf = ti(k.B * k.S); s.out = ti(k.B * k.S); s.prompt = ti(k.B * k.S); s.flags = ti(8); s.params = ti(8);
         s.words = w;
         wm->st = s;
@@ -311,9 +321,9 @@ static hipError_t prof_mark(fastcot_ctx* c, int kind) {
         if ((c)->prof_on) HIPCHK(c, prof_mark(c, -1));                             \
     } while (0)
 
-static int forward_plain(fastcot_ctx* c, int lmhead) {
+static int forward_plain(fastcot_ctx* c, int lmhead, int R) {
     const KernelDims kd0 = c->kd;
-    KernelDims kd = kd0; kd.M = c->Bact * kd.W;
+    KernelDims kd = kd0; kd.W = R; kd.M = c->Bact * R;
     const int dt = c->cfg.dtype, M = kd.M, d = kd.d, qd = kd.H * kd.Dh;
     char* ws = c->ws; const char* wt = c->weights;
     int32_t* stp = state_ptr(c);
@@ -343,20 +353,25 @@ static int forward_plain(fastcot_ctx* c, int lmhead) {
     return 0;
 }
 
-static bool use_persist(const fastcot_ctx* c) {
-    return !c->opt_plain && c->opt_persist && fc_persist_supported(c->kd, c->Bact * c->kd.W);
+static bool use_persist(const fastcot_ctx* c, int R = 0) {
+    KernelDims kd = c->kd;
+    if (R > 0) kd.W = R;
+    return !c->opt_plain && c->opt_persist && fc_persist_supported(kd, c->Bact * kd.W);
 }
 
-static int forward(fastcot_ctx* c, int lmhead, int do_accept = 0) {
-    if (c->opt_plain || !fc_fast_supported(c->kd, c->Bact * c->kd.W)) return forward_plain(c, lmhead);
+// one forward pass over R rows per sequence (R = 0: the window)
+static int forward(fastcot_ctx* c, int lmhead, int do_accept = 0, int R = 0) {
+    if (R <= 0) R = c->kd.W;
+    if (R > c->kd.Wcap) return fail(c, FASTCOT_ECAPACITY, "pass of %s%ld rows per sequence exceeds the workspace (%ld)", "", (long)R, (long)c->kd.Wcap);
+    if (c->opt_plain || !fc_fast_supported(c->kd, c->Bact * R)) return forward_plain(c, lmhead, R);
     FastArgs a;
-    a.kd = c->kd; a.kd.M = c->Bact * c->kd.W; a.Bact = c->Bact;
+    a.kd = c->kd; a.kd.W = R; a.kd.M = c->Bact * R; a.Bact = c->Bact;
     a.mm = &c->mm; a.wm = &c->wm; a.weights = c->weights; a.ws = c->ws; a.dbg_logits = c->dbg_logits;
     a.plan = &c->plan; a.st = c->st; a.lmhead = lmhead;
     a.dbg_stop = c->dbg_stop;
     a.prof = c->prof_on ? c : nullptr;
     a.prof_mark = c->prof_on ? [](void* p, int kind) { return prof_mark((fastcot_ctx*)p, kind); } : nullptr;
-    hipError_t e = use_persist(c) ? fc_persist_step(a, do_accept, a.prof, a.prof_mark) : fc_fast_forward(a);
+    hipError_t e = use_persist(c, R) ? fc_persist_step(a, do_accept, a.prof, a.prof_mark) : fc_fast_forward(a);
     if (e != hipSuccess) return fail(c, FASTCOT_EHIP, "forward launch failed: %s", hipGetErrorString(e));
     return 0;
 }
@@ -434,13 +449,21 @@ extern "C" int fastcot_prefill(fastcot_ctx* c, int32_t B, const int32_t* prompts
     HIPCHK(c, hipMemset(stp + sm.n, 0, (size_t)kd.B * 4));
     if (B != c->Bact) drop_graph(c);
     c->Bact = B; c->buf_len = buf_len; c->prefilled = 0; c->generated = 0;
-    const int chunks = (maxlen - 1 + kd.W - 1) / kd.W;
-    const int nch = chunks > 0 ? chunks : 1;   // one pass even for 1-token prompts (sets up the window)
-    for (int ch = 0; ch < nch; ++ch) {
-        HIPCHK(c, fc_prefill_window(stp, sm, B, kd.W, kd.S, ch, c->st));
-        if (chunks > 0) { int rc = forward(c, 0); if (rc) return rc; }
-        HIPCHK(c, fc_prefill_advance(stp, sm, B, kd.W, kd.S, ch, ch == nch - 1, c->st));
-    }
+    // passes of R rows per sequence over prompt tokens 0 .. maxlen-2 (the last prompt token becomes slot 0
+    // of the first window); the plain path keeps R = window
+    const int rows_cap = (c->opt_plain || !fc_fast_supported(kd, B * kd.W)) ? kd.W : kd.Wcap;
+    int p0 = 0;
+    do {
+        const int left = maxlen - 1 - p0;
+        int R = left < rows_cap ? ((left + 15) & ~15) : rows_cap;
+        if (R > rows_cap) R = rows_cap;
+        if (R < 1) R = rows_cap < 16 ? rows_cap : 16;          // 1-token prompts: no forward, only the window set-up
+        const bool last = p0 + R >= maxlen - 1;
+        HIPCHK(c, fc_prefill_window(stp, sm, B, R, kd.S, p0, c->st));
+        if (left > 0) { int rc = forward(c, 0, 0, R); if (rc) return rc; }
+        HIPCHK(c, fc_prefill_advance(stp, sm, B, kd.W, kd.S, p0 + R, last, c->st));
+        p0 += R;
+    } while (p0 < maxlen - 1);
     HIPCHK(c, hipStreamSynchronize(c->st));
     { int rc = check_abort(c); if (rc) return rc; }
     c->prefilled = 1;
@@ -603,7 +626,7 @@ extern "C" int fastcot_profile_step(fastcot_ctx* c, int32_t iters, float* mean_m
 // ------------------------------------------------------------------ debug read-back of activations
 extern "C" int fastcot_debug_read(fastcot_ctx* c, int32_t what, float* host, size_t count) {
     if (!c || !host) return fail(c, FASTCOT_EINVAL, "NULL argument%s");
-    const size_t M = (size_t)c->kd.B * c->kd.W;
+    const size_t M = (size_t)c->kd.M;
     size_t off, cap;
     switch (what) {
         case 0: off = c->wm.x; cap = M * c->kd.d; break;

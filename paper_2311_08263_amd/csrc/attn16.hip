@@ -44,10 +44,15 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
     extern __shared__ float lds[];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int lm = lane & 15, g = lane >> 4;
-    const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H, kvh = h / (a.H / a.Hkv);
+    // a window of more than 32 rows is cut into sub-windows of 32: sub-window `sub` of a sequence is a
+    // unit of its own whose rows see the committed positions plus the window rows up to their own (the
+    // K/V of all window rows are already in the cache when this kernel starts)
+    const int nsub = (a.W + 31) >> 5;
+    const int bh = blockIdx.x, h = bh % a.H, sub = (bh / a.H) % nsub, b = bh / (a.H * nsub), kvh = h / (a.H / a.Hkv);
     const int sp = blockIdx.y, nsp_max = gridDim.y;
-    const int n = a.n_state[b];
-    int T = n + a.W;
+    const int row0 = 32 * sub, Wr = a.W - row0 < 32 ? a.W - row0 : 32;      // rows of this unit
+    const int n = a.n_state[b] + row0;                       // positions every row of the unit sees
+    int T = n + Wr;
     if (T > a.S) T = a.S;                                    // capacity guard (the host checks first)
     const int NB = (T + 31) >> 5;
     // splits actually used: about a.bpw key blocks per workgroup (the launch provides nsp_max for the
@@ -66,8 +71,8 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         int j = qt * 16 + lm;
-        if (j >= a.W) j = a.W - 1;
-        const float* qr = a.q + (size_t)(b * a.W + j) * a.ldq + h * 128 + 32 * g;
+        if (j >= Wr) j = Wr - 1;
+        const float* qr = a.q + (size_t)(b * a.W + row0 + j) * a.ldq + h * 128 + 32 * g;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             float4 x0 = *(const float4*)(qr + 8 * s), x1 = *(const float4*)(qr + 8 * s + 4);
@@ -130,7 +135,7 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
             }
             // lane: row j = qt*16 + lm, keys kb + 8*g + e  (e = 4*t + r)
             const int j = qt * 16 + lm;
-            const int lastvis = n + (j < a.W ? j : a.W - 1);
+            const int lastvis = n + (j < Wr ? j : Wr - 1);
             float p[8];
             float bm = NEG_BIG;
 #pragma unroll
@@ -289,9 +294,9 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         const int j = qt * 16 + lm;
-        if (j < a.W) {
+        if (j < Wr) {
             const float inv = 1.0f / lw[qt];
-            float* o = a.out + (size_t)(b * a.W + j) * a.ldo + h * 128 + 4 * g;
+            float* o = a.out + (size_t)(b * a.W + row0 + j) * a.ldo + h * 128 + 4 * g;
 #pragma unroll
             for (int t = 0; t < 2; ++t) *(f32x4_t*)(o + 16 * (2 * wv + t)) = o2[qt][t] * inv;
         }
@@ -299,14 +304,15 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
 }
 
 size_t fc_attn16_part_bytes(int BH, int nsplit, int W) {
-    const int QT = W > 16 ? 2 : 1;
-    return (size_t)BH * nsplit * QT * PART_FLOATS * 4;
+    const int QT = W > 16 ? 2 : 1, nsub = (W + 31) / 32;
+    return (size_t)BH * nsub * nsplit * QT * PART_FLOATS * 4;
 }
 
 hipError_t fc_attn16(const AttnArgs& a, int Bact, int nsplit, hipStream_t st) {
-    if (a.W < 1 || a.W > 32 || nsplit < 1 || nsplit > FC_MAX_ATTN_SPLITS || Bact * a.H > FC_MAX_COUNTERS || a.S < 32 || a.S % 32 || a.bpw < 1)
+    const int nsub = (a.W + 31) / 32;
+    if (a.W < 1 || nsplit < 1 || nsplit > FC_MAX_ATTN_SPLITS || Bact * nsub * a.H > FC_MAX_COUNTERS || a.S < 32 || a.S % 32 || a.bpw < 1)
         return hipErrorInvalidValue;
-    dim3 grid(Bact * a.H, nsplit);
+    dim3 grid(Bact * nsub * a.H, nsplit);
     const size_t l1 = (size_t)4 * PART_FLOATS * 4 + 16, l2 = (size_t)8 * PART_FLOATS * 4 + 16;
     static bool lds_ok = false;                          // two query tiles need more than the default 64 KB
     if (!lds_ok) {

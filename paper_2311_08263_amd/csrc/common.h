@@ -83,7 +83,8 @@ struct WorkspaceMap {
 };
 
 struct KernelDims {    // model + capacities as the kernels need them
-    int32_t L, d, H, Hkv, Dh, F, V, B, S, W, M;
+    int32_t L, d, H, Hkv, Dh, F, V, B, S, W, M;   // W = rows per sequence of a pass (the window, or a prefill chunk), M = rows of a pass
+    int32_t Wcap;      // most rows per sequence any pass may have (the workspace is sized for B * Wcap rows)
     int32_t qkvN;      // (H + 2 Hkv) * Dh
     float eps;
     int32_t esz;       // bytes per weight / cache element

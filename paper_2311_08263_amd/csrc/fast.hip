@@ -11,7 +11,7 @@
 enum { KK_EMBED = 0, KK_QKV = 2, KK_ATTN = 4, KK_O = 5, KK_GU = 6, KK_DOWN = 8, KK_LM = 9, KK_ARGMAX = 10 };
 
 bool fc_fast_supported(const KernelDims& kd, int rows) {
-    return kd.esz == 2 && kd.Dh == 128 && rows >= 1 && kd.W <= 32 && kd.d % 256 == 0 && kd.F % 256 == 0 &&
+    return kd.esz == 2 && kd.Dh == 128 && rows >= 1 && kd.d % 256 == 0 && kd.F % 256 == 0 &&
            (kd.H * kd.Dh) % 256 == 0 && kd.S % 32 == 0 && kd.V % 16 == 0;
 }
 
@@ -73,7 +73,7 @@ void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t
     if (kd.H * kd.Dh > kmax) kmax = kd.H * kd.Dh;
     const size_t big = fc_split_bytes(kd.M, kmax) + (size_t)FC_GEMM256_MAX_SK * kd.M * kd.d * 4 + 4096;
     if (*gemm_part_bytes < big) *gemm_part_bytes = big;
-    *attn_part_bytes = fc_attn16_part_bytes(kd.B * kd.H, FC_MAX_ATTN_SPLITS, kd.W) + 4096;
+    *attn_part_bytes = fc_attn16_part_bytes(kd.B * kd.H, FC_MAX_ATTN_SPLITS, kd.Wcap > kd.W ? kd.Wcap : kd.W) + 4096;
 }
 
 #define FLAUNCH(kind, call)                                                          \

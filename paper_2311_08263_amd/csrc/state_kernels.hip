@@ -3,28 +3,30 @@
 // step can be replayed without host arguments.
 #include "kernels.h"
 
-// Prefill chunk `chunk`: window slot j of sequence b carries prompt token chunk*W + j if that
-// token is one of the first len-1 prompt tokens, else a pad (its K/V is never committed).
-__global__ void k_prefill_window(int32_t* st, StateMap sm, int B, int W, int S, int chunk) {
+// Prefill pass of R rows per sequence starting at prompt position p0: row j of sequence b carries
+// prompt token p0 + j if that token is one of the first len-1 prompt tokens, else a pad (its K/V is
+// never committed).
+__global__ void k_prefill_window(int32_t* st, StateMap sm, int B, int R, int S, int p0) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= B * W) return;
-    int b = i / W, j = i % W;
+    if (i >= B * R) return;
+    int b = i / R, j = i % R;
     int len = st[sm.plen + b];
-    int p = chunk * W + j;
+    int p = p0 + j;
     st[sm.win + i] = (p < len - 1) ? st[sm.prompt + (size_t)b * S + p] : 0;
 }
-hipError_t fc_prefill_window(int32_t* state, const StateMap& sm, int B, int W, int S, int chunk, hipStream_t st) {
-    k_prefill_window<<<(B * W + 255) / 256, 256, 0, st>>>(state, sm, B, W, S, chunk);
+hipError_t fc_prefill_window(int32_t* state, const StateMap& sm, int B, int R, int S, int p0, hipStream_t st) {
+    k_prefill_window<<<(B * R + 255) / 256, 256, 0, st>>>(state, sm, B, R, S, p0);
     return hipGetLastError();
 }
 
-// After the forward of a prefill chunk: commit the K/V of the real prompt rows.  After the last
-// chunk, set up the first Jacobi window: slot 0 = last prompt token, slots 1.. = buffer[0..W-2].
-__global__ void k_prefill_advance(int32_t* st, StateMap sm, int B, int W, int S, int chunk, int last) {
+// After the forward of a prefill pass that ended at prompt position p1: commit the K/V of the real
+// prompt rows.  After the last pass, set up the first Jacobi window: slot 0 = last prompt token,
+// slots 1.. = buffer[0..W-2].
+__global__ void k_prefill_advance(int32_t* st, StateMap sm, int B, int W, int S, int p1, int last) {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     int len = st[sm.plen + b];
-    int n = (chunk + 1) * W;
+    int n = p1;
     if (n > len - 1) n = len - 1;
     st[sm.n + b] = n;
     if (last) {
@@ -35,9 +37,9 @@ __global__ void k_prefill_advance(int32_t* st, StateMap sm, int B, int W, int S,
         for (int j = 1; j < W; ++j) st[sm.win + b * W + j] = st[sm.buf + (size_t)b * S + j - 1];
     }
 }
-hipError_t fc_prefill_advance(int32_t* state, const StateMap& sm, int B, int W, int S, int chunk, int last,
+hipError_t fc_prefill_advance(int32_t* state, const StateMap& sm, int B, int W, int S, int p1, int last,
                               hipStream_t st) {
-    k_prefill_advance<<<(B + 63) / 64, 64, 0, st>>>(state, sm, B, W, S, chunk, last);
+    k_prefill_advance<<<(B + 63) / 64, 64, 0, st>>>(state, sm, B, W, S, p1, last);
     return hipGetLastError();
 }
 

@@ -36,7 +36,7 @@ def setup(fc, shape, B, S, W):
 @pytest.mark.parametrize("persistent", [0, 1])
 @pytest.mark.parametrize("shape,B,W,P", [(SMALL, 1, 16, 45), (SMALL, 2, 16, 33), (SMALL_MHA, 1, 8, 20),
                                          (SMALL, 1, 32, 70), (SMALL_MHA, 3, 5, 12), (SMALL, 4, 32, 40),
-                                         (SMALL_MHA, 3, 16, 30)])
+                                         (SMALL_MHA, 3, 16, 30), (SMALL, 1, 64, 75), (SMALL_MHA, 2, 40, 300)])
 def test_follow_mode_small_models(fc, shape, B, W, P, persistent):
     if persistent and B * W > 16:
         pytest.skip("the persistent kernel covers at most 16 rows per step")
