@@ -139,6 +139,44 @@ def extras(torch, fc, synthgen, packed, log_fn):
     return out
 
 
+def window_sweep(args):
+    """Step time against window size and prompt length (the measurement of the paper's Fig. 2, Sec. 3.2:
+    how large may the window grow before the step stops being free), batch 1, 7B and 13B shapes."""
+    import torch
+    import synthgen
+    import paper_2311_08263_amd as fc
+    rows = []
+    for shape_name in ("7b", "13b"):
+        shape = synthgen.SHAPES[shape_name]
+        packed = None
+        for P in (256, 1024, 4096):
+            for W in (1, 2, 4, 8, 16, 32, 64, 128):
+                steps, warm = 12, 3
+                max_seq = ((P + W * (steps + warm + 3) + 31) // 32) * 32
+                cfg = fc.Config.from_shape(shape, 1, max_seq, W)
+                if packed is None:
+                    log(f"window sweep: building {shape_name} weights")
+                    packed = fc.load_synth_weights(cfg, shape)
+                ctx = fc.Context(cfg, packed)
+                ctx.prefill(synthgen.prompts(1, P, shape.vocab), [P], synthgen.buffer_init(1, W * (steps + warm + 2), shape.vocab))
+                for _ in range(warm):
+                    ctx.step(sync=False)
+                ctx.stream.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    ctx.step(sync=False)
+                ctx.stream.synchronize()
+                ms = 1e3 * (time.perf_counter() - t0) / steps
+                rows.append({"shape": shape_name, "prompt": P, "window": W, "ms_per_step": round(ms, 3)})
+                log(f"window sweep {shape_name} prompt {P:5d} window {W:4d}: {ms:8.3f} ms/step")
+                ctx.close()
+                del ctx
+        del packed
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "ms per Jacobi step against window size and prompt length (Fig. 2)", "unit": "ms",
+                      "n_gpus": 1, "data": "synthetic", "dtype": "bf16", "rows": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -150,12 +188,17 @@ def main():
     ap.add_argument("--plain", action="store_true", help="time the plain kernels instead of the MFMA path")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary measurements (streaming-read ceiling, isolated attention and LM head, perfect draft)")
+    ap.add_argument("--window-sweep", action="store_true",
+                    help="instead of the benchmark: ms/step for windows 1..128 x prompts 256..4096 on the 7B and 13B shapes")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device-to-device copy of 512 MiB (the known-size kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus above 1 is not supported "
                  "(sequences are independent: a multi-GPU run would shard the batch, see DESIGN.md)")
+
+    if args.window_sweep:
+        return window_sweep(args)
 
     import torch
     import synthgen
