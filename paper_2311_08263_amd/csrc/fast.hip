@@ -58,6 +58,13 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     // bytes than weight bytes; K slices per owner cut that (measured at the 7B shape)
     if (kd.F >= 2 * kd.d && kd.F >= 4096 && p->nw[3] % 4 == 0 && p->nw[3] / 4 <= nts[3] && (nts[3] + p->nw[3] / 4 - 1) / (p->nw[3] / 4) <= 8) p->ks[3] = 4;
     p->co_single = 1;
+    // 17..32 rows (two row tiles): at most 4 n-tiles per workgroup, K slices halved until they fit
+    for (int i = 0; i < 5; ++i) {
+        const int G2 = fc_gemmco_grid(nts[i], 4);
+        int k2 = p->ks[i];
+        while (k2 > 1 && (G2 % k2 || G2 / k2 > nts[i] || (nts[i] + G2 / k2 - 1) / (G2 / k2) > 4)) k2 >>= 1;
+        p->nw2[i] = G2; p->ks2[i] = k2;
+    }
 }
 
 void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t* attn_part_bytes) {
@@ -116,12 +123,14 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     int gi = 0;        // which GEMM of the plan
     auto gemm = [&](int epi, const GemmPlan& pl, const void* W, int K, int N, const float* X, int ldx, const float* gain,
                     float* out, int ldo) {
-        const int nw = M <= 16 ? a.plan->nw[gi] : 0;      // workgroups of the column-owner kernel, 0 = split-K kernel
+        // workgroups of the column-owner kernel (0 = split-K kernel) and its K slices per owner
+        const int nw = M <= 16 ? a.plan->nw[gi] : (M <= 32 ? a.plan->nw2[gi] : 0);
+        const int ksl = M <= 16 ? a.plan->ks[gi] : a.plan->ks2[gi];
         if (nw > 0) {
             co.W = (const bf16_t*)W; co.K = K; co.NT = N / 16; co.X = X; co.ldx = ldx; co.gain = gain; co.out = out; co.ldo = ldo;
-            co.layer = g.layer; co.ks = epi == EPI_RESID ? a.plan->ks[gi] : 1;
+            co.layer = g.layer; co.ks = epi == EPI_RESID ? ksl : 1;
             co.xpart = (float*)(ws + wm.gemm_part); co.xcnt = (int32_t*)(ws + wm.gemm_cnt);
-            co.amax_idx = (int32_t*)(co.amax_val + (size_t)nw * 16);
+            co.amax_idx = (int32_t*)(co.amax_val + (size_t)nw * (M > 16 ? 32 : 16));
             return fc_gemmco(epi, co, nw, a.st);
         }
         if (M > 32) {        // matrix-core bound: activations split once, tiles of 64 rows x 256 columns
@@ -164,7 +173,7 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     if (a.dbg_stop >= 0 && nstage >= a.dbg_stop) return hipSuccess;
     if (a.lmhead) {
         const int stride = M > 16 ? 32 : 16;
-        const int nwlm = M <= 16 ? a.plan->nw[4] : 0;
+        const int nwlm = M <= 16 ? a.plan->nw[4] : (M <= 32 ? a.plan->nw2[4] : 0);
         const int nwin = nwlm > 0 ? nwlm : a.plan->lm.ncg;    // partial winners to reduce
         g.amax_idx = (int32_t*)(g.amax_val + (size_t)nwin * stride);
         gi = 4;

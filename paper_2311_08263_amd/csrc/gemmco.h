@@ -6,7 +6,7 @@ struct GemmCoArgs {
     const bf16_t* W;       // fused matrix in fragment order
     int32_t K, NT;         // inputs (multiple of 256), n-tiles
     const float* X;        // activations fp32 [M][ldx]
-    int32_t ldx, M;
+    int32_t ldx, M;        // M <= 32 rows
     const float* gain;     // RMSNorm gain [K]; NULL = no norm in front of this GEMM
     float eps;
     float* out;            // RESID: residual stream (+=); SWIGLU: hidden [M][F]; QKV: q [M][H*128]; LMHEAD: logits or NULL
@@ -14,7 +14,7 @@ struct GemmCoArgs {
     const int32_t* n_state; const float* cosT; const float* sinT;
     bf16_t* kc; bf16_t* vc;
     int32_t layer, H, Hkv, B, S, Wn, kvp;
-    float* amax_val; int32_t* amax_idx;   // LM head: winners per workgroup [workgroups][16]
+    float* amax_val; int32_t* amax_idx;   // LM head: winners per workgroup [workgroups][16 or 32 rows]
     int32_t ks;            // EPI_RESID only: workgroups per column owner, each taking 1/ks of K (1..8)
     float* xpart;          // ks > 1: partial tiles [workgroup][8][64 lanes][4]
     int32_t* xcnt;         // ks > 1: one arrival counter per owner, zero between launches
@@ -24,5 +24,5 @@ struct GemmCoArgs {
 // G workgroups = G / ks owners x ks K slices; owner i owns n-tiles [i*NT/owners, (i+1)*NT/owners), at most
 // 8; fc_gemmco_grid picks one workgroup per CU (all resident, one round) unless the matrix is wider than
 // 8 n-tiles per CU
-int fc_gemmco_grid(int NT);
+int fc_gemmco_grid(int NT, int most = 8);
 hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st);

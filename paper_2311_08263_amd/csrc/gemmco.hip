@@ -1,4 +1,4 @@
-// Column-owner weight-streaming bf16 GEMM for up to 16 activation rows.
+// Column-owner weight-streaming bf16 GEMM for up to 32 activation rows (MT = 1 or 2 row tiles of 16).
 //
 // A workgroup of 8 waves owns NW n-tiles (16 output columns each) over the whole of K; wave w
 // takes the w-th eighth of K.  No workgroup ever needs another workgroup's result: the eight
@@ -28,17 +28,20 @@ __device__ inline uint32_t rne16(float f) {
 __device__ inline float up16(uint32_t b) { return __uint_as_float(b << 16); }
 
 // One batch = KB k-tiles: the wave's weight tiles for its n-tiles and its activation octets.
-template <int NW, int KB> struct Batch {
+template <int NW, int KB, int MT> struct Batch {
     u32x4_t wt[NW][KB];
-    float4 xa[KB][2];
+    float4 xa[KB][MT][2];
 };
 
-template <int EPI, int NW, int KB, bool DB>
+// NW * MT <= 8 output tiles per workgroup: after the K slices of the eight waves have met in LDS, wave
+// ti finishes tile ti = j * MT + mt (n-tile j of the workgroup, row tile mt).
+template <int EPI, int NW, int KB, bool DB, int MT>
 __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     extern __shared__ float lds[];
-    f32x4_t* lds_part = (f32x4_t*)lds;                  // [8 waves][NW][64 lanes]
-    float* lds_ss = lds + 8 * NW * 256;                 // [8][16]
-    float* lds_amv = lds_ss + 8 * 16;                   // [8][16]
+    constexpr int TW = NW * MT;                          // output tiles per workgroup
+    f32x4_t* lds_part = (f32x4_t*)lds;                  // [8 waves][TW][64 lanes]
+    float* lds_ss = lds + 8 * TW * 256;                 // [8][MT * 16]
+    float* lds_amv = lds_ss + 8 * MT * 16;              // [8][16]
     int* lds_ami = (int*)(lds_amv + 8 * 16);            // [8][16]
     float* lds_gain = (float*)(lds_ami + 8 * 16);       // [K] (only with a norm in front)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -53,15 +56,16 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     const int s_lo = (int)((unsigned)KT * (unsigned)slice / (unsigned)ks), s_len = (int)((unsigned)KT * (unsigned)(slice + 1) / (unsigned)ks) - s_lo;
     const int kt_begin = s_lo + ((w * s_len) >> 3), kt_end = s_lo + (((w + 1) * s_len) >> 3);
     const int nb = (((s_len + 7) >> 3) + KB - 1) / KB;          // batches of the longest wave
-    const int row = lm < a.M ? lm : a.M - 1;            // rows past M repeat a valid row; never written
-    const float* xr = a.X + (size_t)row * a.ldx + 8 * g4;
+    const float* xr[MT];                                // rows past M repeat a valid row; never written
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) xr[mt] = a.X + (size_t)(mt * 16 + lm < a.M ? mt * 16 + lm : a.M - 1) * a.ldx + 8 * g4;
     const u32x4_t* wbase = (const u32x4_t*)a.W + lane;
 
     // All loads are unconditional (a conditionally loaded register batch would be copied, and a copy
     // waits for every load in flight): past the end of the slice, or for n-tiles this workgroup does
     // not own, the address falls back to the first tile of the matrix (cached), and the activations
     // of such k-tiles are zeroed at use.
-    auto load = [&](Batch<NW, KB>& b, int ib) {
+    auto load = [&](Batch<NW, KB, MT>& b, int ib) {
 #pragma unroll
         for (int t = 0; t < KB; ++t) {
             const int kt = kt_begin + ib * KB + t;
@@ -76,40 +80,53 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         for (int t = 0; t < KB; ++t) {
             const int kt = kt_begin + ib * KB + t;
             const int kc = (ib < nb && kt < kt_end) ? kt : kt_begin;
-            b.xa[t][0] = *(const float4*)(xr + kc * 32);
-            b.xa[t][1] = *(const float4*)(xr + kc * 32 + 4);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                b.xa[t][mt][0] = *(const float4*)(xr[mt] + kc * 32);
+                b.xa[t][mt][1] = *(const float4*)(xr[mt] + kc * 32 + 4);
+            }
         }
     };
 
-    f32x4_t acc[NW];
+    f32x4_t acc[NW][MT];
+    float ss[MT];
 #pragma unroll
-    for (int j = 0; j < NW; ++j) acc[j] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-    float ss = 0.f;
+    for (int mt = 0; mt < MT; ++mt) {
+        ss[mt] = 0.f;
+#pragma unroll
+        for (int j = 0; j < NW; ++j) acc[j][mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    }
 
-    auto compute = [&](const Batch<NW, KB>& b, int ib) {
+    auto compute = [&](const Batch<NW, KB, MT>& b, int ib) {
 #pragma unroll
         for (int t = 0; t < KB; ++t) {
             const int kt = kt_begin + ib * KB + t;
             const float keep = (ib < nb && kt < kt_end) ? 1.0f : 0.0f;
-            float v[8] = {b.xa[t][0].x, b.xa[t][0].y, b.xa[t][0].z, b.xa[t][0].w, b.xa[t][1].x, b.xa[t][1].y, b.xa[t][1].z, b.xa[t][1].w};
+            const int kc = keep != 0.0f ? kt : kt_begin;
+            float4 g0, g1;
+            if (a.gain) { g0 = *(const float4*)(lds_gain + kc * 32 + 8 * g4); g1 = *(const float4*)(lds_gain + kc * 32 + 8 * g4 + 4); }
+            Frag hi[MT], lo[MT];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) { v[e] *= keep; ss += v[e] * v[e]; }
-            if (a.gain) {
-                const int kc = keep != 0.0f ? kt : kt_begin;
-                const float4 g0 = *(const float4*)(lds_gain + kc * 32 + 8 * g4), g1 = *(const float4*)(lds_gain + kc * 32 + 8 * g4 + 4);
-                v[0] *= g0.x; v[1] *= g0.y; v[2] *= g0.z; v[3] *= g0.w; v[4] *= g1.x; v[5] *= g1.y; v[6] *= g1.z; v[7] *= g1.w;
+            for (int mt = 0; mt < MT; ++mt) {
+                float v[8] = {b.xa[t][mt][0].x, b.xa[t][mt][0].y, b.xa[t][mt][0].z, b.xa[t][mt][0].w,
+                              b.xa[t][mt][1].x, b.xa[t][mt][1].y, b.xa[t][mt][1].z, b.xa[t][mt][1].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { v[e] *= keep; ss[mt] += v[e] * v[e]; }
+                if (a.gain) { v[0] *= g0.x; v[1] *= g0.y; v[2] *= g0.z; v[3] *= g0.w; v[4] *= g1.x; v[5] *= g1.y; v[6] *= g1.z; v[7] *= g1.w; }
+                uint32_t h[8], l[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { h[e] = rne16(v[e]); l[e] = rne16(v[e] - up16(h[e])); }
+                hi[mt].u = (u32x4_t){h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+                lo[mt].u = (u32x4_t){l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
             }
-            uint32_t h[8], l[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) { h[e] = rne16(v[e]); l[e] = rne16(v[e] - up16(h[e])); }
-            Frag hi, lo;
-            hi.u = (u32x4_t){h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
-            lo.u = (u32x4_t){l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
 #pragma unroll
             for (int j = 0; j < NW; ++j) {
                 Frag wf; wf.u = b.wt[j][t];
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, hi.v, acc[j], 0, 0, 0);
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, lo.v, acc[j], 0, 0, 0);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, hi[mt].v, acc[j][mt], 0, 0, 0);
+                    acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, lo[mt].v, acc[j][mt], 0, 0, 0);
+                }
             }
         }
     };
@@ -117,10 +134,10 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     // two batches in flight per wave: the next one is requested before the current one is used
     // (DB = false keeps one batch per wave in flight and fewer registers, so that two workgroups
     // share a CU and overlap each other's phases instead)
-    Batch<NW, KB> A;
+    Batch<NW, KB, MT> A;
     load(A, 0);
     if (DB) {
-        Batch<NW, KB> B;
+        Batch<NW, KB, MT> B;
         load(B, 1);
         if (a.gain) {       // the norm gain goes through LDS once per workgroup
             for (int i = tid * 4; i < a.K; i += 512 * 4) *(float4*)(lds_gain + i) = *(const float4*)(a.gain + i);
@@ -144,30 +161,34 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     }
 
     // the eight K slices meet in LDS
-    ss += __shfl_xor(ss, 16, 64);
-    ss += __shfl_xor(ss, 32, 64);
-    if (g4 == 0) lds_ss[w * 16 + lm] = ss;
 #pragma unroll
-    for (int j = 0; j < NW; ++j) lds_part[(w * NW + j) * 64 + lane] = acc[j];
+    for (int mt = 0; mt < MT; ++mt) {
+        ss[mt] += __shfl_xor(ss[mt], 16, 64);
+        ss[mt] += __shfl_xor(ss[mt], 32, 64);
+        if (g4 == 0) lds_ss[(w * MT + mt) * 16 + lm] = ss[mt];
+#pragma unroll
+        for (int j = 0; j < NW; ++j) lds_part[(w * TW + j * MT + mt) * 64 + lane] = acc[j][mt];
+    }
     __syncthreads();
 
-    // waves 0..NW-1 finish one tile each: lane holds row lm, columns nt*16 + 4*g4 + r
-    const int nt = nt0 + w;
-    const bool fin = w < NW && nt < nt1;
+    // waves 0..TW-1 finish one tile each: lane holds row mt*16 + lm, columns nt*16 + 4*g4 + r
+    const int tj = w / MT, tm = w % MT;
+    const int nt = nt0 + tj;
+    const bool fin = w < TW && nt < nt1;
     f32x4_t v = (f32x4_t){0.f, 0.f, 0.f, 0.f};
     float rs = 1.0f;
     if (fin) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) v += lds_part[(q * NW + w) * 64 + lane];
+        for (int q = 0; q < 8; ++q) v += lds_part[(q * TW + w) * 64 + lane];
         if (a.gain) {
             float s = 0.f;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) s += lds_ss[q * 16 + lm];
+            for (int q = 0; q < 8; ++q) s += lds_ss[(q * MT + tm) * 16 + lm];
             rs = 1.0f / sqrtf(s / (float)a.K + a.eps);
         }
         v *= rs;
     }
-    const int m = lm;
+    const int m = tm * 16 + lm;
     if (EPI == EPI_RESID && ks > 1) {
         // partial tiles of the ks slices meet through memory; the last workgroup to arrive adds them
         float* mine = a.xpart + ((size_t)blockIdx.x * 8 + w) * 256 + lane * 4;
@@ -273,15 +294,17 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         }
         if (g4 == 0) { lds_amv[w * 16 + lm] = best; lds_ami[w * 16 + lm] = bi; }
         __syncthreads();
-        if (tid < 16) {
-            float bv = lds_amv[tid]; int bx = lds_ami[tid];
+        if (tid < 16 * MT) {                 // row tid: the waves whose tile is row tile tid / 16
+            const int rt = tid >> 4, r16 = tid & 15;
+            float bv = -3.0e38f; int bx = 0x7fffffff;
 #pragma unroll
-            for (int q = 1; q < 8; ++q) {
-                const float ov = lds_amv[q * 16 + tid]; const int oi = lds_ami[q * 16 + tid];
+            for (int q = 0; q < 8; ++q) {
+                if (q % MT != rt) continue;
+                const float ov = lds_amv[q * 16 + r16]; const int oi = lds_ami[q * 16 + r16];
                 if (ov > bv || (ov == bv && oi < bx)) { bv = ov; bx = oi; }
             }
-            a.amax_val[(size_t)blockIdx.x * 16 + tid] = bv;
-            a.amax_idx[(size_t)blockIdx.x * 16 + tid] = bx;
+            a.amax_val[(size_t)blockIdx.x * (16 * MT) + tid] = bv;
+            a.amax_idx[(size_t)blockIdx.x * (16 * MT) + tid] = bx;
         }
     }
 }
@@ -296,57 +319,67 @@ static int num_cus() {
     return g_cus;
 }
 
-// grid: one workgroup per CU unless that would give a workgroup more than 8 n-tiles
-int fc_gemmco_grid(int NT) {
+// grid: one workgroup per CU unless that would give a workgroup more than `most` n-tiles (8 for up
+// to 16 rows, 4 for up to 32 rows: a workgroup finishes at most 8 output tiles)
+int fc_gemmco_grid(int NT, int most) {
     int G = num_cus();
     if (G > NT) G = NT;
-    while ((NT + G - 1) / G > 8) G += num_cus();
+    while ((NT + G - 1) / G > most) G += num_cus();
     return G;
 }
 
-template <int EPI, int NW, int KB, bool DB>
+template <int EPI, int NW, int KB, bool DB, int MT>
 static hipError_t launch_k(const GemmCoArgs& a, int G, hipStream_t st) {
-    const size_t lds = (size_t)8 * NW * 1024 + 3 * 8 * 16 * 4 + (a.gain ? (size_t)a.K * 4 : 0) + 64;
+    const size_t lds = (size_t)8 * NW * MT * 1024 + (size_t)(8 * MT * 16 + 2 * 8 * 16) * 4 + (a.gain ? (size_t)a.K * 4 : 0) + 64;
     static bool raised = false;
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_gemmco<EPI, NW, KB, DB>, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        hipError_t e = hipFuncSetAttribute((const void*)k_gemmco<EPI, NW, KB, DB, MT>, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
         if (e != hipSuccess) return e;
         raised = true;
     }
     if (lds > 150 * 1024) return hipErrorInvalidValue;
-    k_gemmco<EPI, NW, KB, DB><<<G, 512, lds, st>>>(a);
+    k_gemmco<EPI, NW, KB, DB, MT><<<G, 512, lds, st>>>(a);
     return hipGetLastError();
 }
 template <int EPI>
 static hipError_t launch_epi(const GemmCoArgs& a, int G, hipStream_t st) {
     const int owners = G / (a.ks > 1 ? a.ks : 1);
     const int nw = (a.NT + owners - 1) / owners;  // most n-tiles any workgroup owns
+    if (a.M > 16) {                               // two row tiles: at most 4 n-tiles per workgroup
+        switch (nw) {
+            case 1: return launch_k<EPI, 1, 4, false, 2>(a, G, st);
+            case 2: return launch_k<EPI, 2, 4, false, 2>(a, G, st);
+            case 3: return launch_k<EPI, 3, 2, false, 2>(a, G, st);
+            case 4: return launch_k<EPI, 4, 2, false, 2>(a, G, st);
+        }
+        return hipErrorInvalidValue;
+    }
     if (a.single_buffer) {
         switch (nw) {
-            case 1: return launch_k<EPI, 1, 8, false>(a, G, st);
-            case 2: return launch_k<EPI, 2, 4, false>(a, G, st);
-            case 3: return launch_k<EPI, 3, 4, false>(a, G, st);
-            case 4: return launch_k<EPI, 4, 4, false>(a, G, st);
-            case 5: case 6: return launch_k<EPI, 6, 2, false>(a, G, st);
-            case 7: case 8: return launch_k<EPI, 8, 2, false>(a, G, st);
+            case 1: return launch_k<EPI, 1, 8, false, 1>(a, G, st);
+            case 2: return launch_k<EPI, 2, 4, false, 1>(a, G, st);
+            case 3: return launch_k<EPI, 3, 4, false, 1>(a, G, st);
+            case 4: return launch_k<EPI, 4, 4, false, 1>(a, G, st);
+            case 5: case 6: return launch_k<EPI, 6, 2, false, 1>(a, G, st);
+            case 7: case 8: return launch_k<EPI, 8, 2, false, 1>(a, G, st);
         }
         return hipErrorInvalidValue;
     }
     switch (nw) {
-        case 1: return launch_k<EPI, 1, 6, true>(a, G, st);
-        case 2: return launch_k<EPI, 2, 4, true>(a, G, st);
-        case 3: return launch_k<EPI, 3, 3, true>(a, G, st);
-        case 4: return launch_k<EPI, 4, 2, true>(a, G, st);
-        case 5: case 6: return launch_k<EPI, 6, 2, true>(a, G, st);
-        case 7: case 8: return launch_k<EPI, 8, 1, true>(a, G, st);
+        case 1: return launch_k<EPI, 1, 6, true, 1>(a, G, st);
+        case 2: return launch_k<EPI, 2, 4, true, 1>(a, G, st);
+        case 3: return launch_k<EPI, 3, 3, true, 1>(a, G, st);
+        case 4: return launch_k<EPI, 4, 2, true, 1>(a, G, st);
+        case 5: case 6: return launch_k<EPI, 6, 2, true, 1>(a, G, st);
+        case 7: case 8: return launch_k<EPI, 8, 1, true, 1>(a, G, st);
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st) {
-    const int ks = a.ks > 1 ? a.ks : 1;
-    if (a.M < 1 || a.M > 16 || a.K % 256 || a.NT < 1 || G < 1 || ks > 8 || G % ks || G / ks > a.NT ||
-        (a.NT + G / ks - 1) / (G / ks) > 8 || a.K / 256 < ks)
+    const int ks = a.ks > 1 ? a.ks : 1, most = a.M > 16 ? 4 : 8;
+    if (a.M < 1 || a.M > 32 || a.K % 256 || a.NT < 1 || G < 1 || ks > 8 || G % ks || G / ks > a.NT ||
+        (a.NT + G / ks - 1) / (G / ks) > most || a.K / 256 < ks)
         return hipErrorInvalidValue;
     if (ks > 1 && (epi != EPI_RESID || !a.xpart || !a.xcnt || G / ks > FC_MAX_COUNTERS)) return hipErrorInvalidValue;
     switch (epi) {
