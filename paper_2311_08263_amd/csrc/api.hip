@@ -131,7 +131,9 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
         wm->gemm_part = take(wm->gemm_part_bytes); wm->gemm_cnt = take(FC_MAX_COUNTERS * 4);
         wm->attn_part = take(wm->attn_part_bytes); wm->attn_cnt = take(FC_MAX_COUNTERS * 4);
         {
-            size_t am = (size_t)(k.V / 16 + 8) * 32 * 8, am2 = (size_t)(k.V / 256 + 1) * ((M + 15) / 16 * 16) * 8;
+            // column-owner / split-K kernels: per workgroup 32 rows; many-row kernel: per column block of 64
+            // (narrow tiles) or 256 columns, all rows
+            size_t am = (size_t)(k.V / 16 + 8) * 32 * 8, am2 = (size_t)(k.V / 64 + 1) * ((M + 15) / 16 * 16) * 8;
             wm->amax_part = take(am > am2 ? am : am2);
         }     // winners per column group / per workgroup
         StateMap s; int w = 0;

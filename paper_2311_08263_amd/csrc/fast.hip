@@ -119,7 +119,9 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     big.H = kd.H; big.Hkv = kd.Hkv; big.B = kd.B; big.S = kd.S; big.Wn = kd.W; big.kvp = kd.kvp;
     big.amax_stride = (M + 15) / 16 * 16;
     big.part = (float*)(ws + wm.gemm_part + ((fc_split_bytes(kd.M, kd.F > qd ? (kd.F > d ? kd.F : d) : (qd > d ? qd : d)) + 255) & ~(size_t)255));
-    big.amax_val = g.amax_val; big.amax_idx = (int32_t*)(g.amax_val + (size_t)((kd.V / 16 + 15) / 16) * big.amax_stride);
+    // LM head: one winner per row and column block (16 n-tiles, or 4 with the narrow tiles)
+    const int lm_ncb = fc_gemm256_narrow(EPI_LMHEAD, M, kd.V / 16) ? (kd.V / 16 + 3) / 4 : (kd.V / 16 + 15) / 16;
+    big.amax_val = g.amax_val; big.amax_idx = (int32_t*)(g.amax_val + (size_t)lm_ncb * big.amax_stride);
     int gi = 0;        // which GEMM of the plan
     auto gemm = [&](int epi, const GemmPlan& pl, const void* W, int K, int N, const float* X, int ldx, const float* gain,
                     float* out, int ldo) {
@@ -182,7 +184,7 @@ hipError_t fc_fast_forward(const FastArgs& a) {
             FLAUNCH(KK_ARGMAX, fc_argmax_final(g.amax_val, g.amax_idx, nwin, stride, M, stp + wm.st.o,
                                                (float*)(ws + wm.topv), a.st));
         else
-            FLAUNCH(KK_ARGMAX, fc_argmax_final(big.amax_val, big.amax_idx, (kd.V / 16 + 15) / 16, big.amax_stride, M,
+            FLAUNCH(KK_ARGMAX, fc_argmax_final(big.amax_val, big.amax_idx, lm_ncb, big.amax_stride, M,
                                                stp + wm.st.o, (float*)(ws + wm.topv), a.st));
     }
     return hipSuccess;

@@ -16,8 +16,10 @@ struct Gemm256Args {
     int32_t amax_stride;
     int32_t sk;            // K slices (RESID only when > 1: partial tiles to `part`, then added in slice order)
     float* part;           // [sk][M][NT*16] fp32
+    int32_t cw;            // n-tiles per wave: 0 = chosen from the shape, 1 or 4 = forced
 };
 #define FC_GEMM256_MAX_SK 8
+bool fc_gemm256_narrow(int epi, int M, int NT);     // true: 64 x 64 tiles (few rows x few columns), else 64 x 256
 int fc_gemm256_sk(int M, int K, int NT);   // slices that fill the chip for a matrix with few columns
 
 // X [M][ldx] fp32 -> AF; gain != NULL applies RMSNorm (fp32 statistics over the K inputs) first

@@ -89,19 +89,22 @@ hipError_t fc_split(const float* X, int ldx, int M, int K, const float* gain, fl
 }
 
 // ------------------------------------------------------------------ the GEMM
-template <int EPI>
+// CW = n-tiles per wave: 4 (tiles of 64 rows x 256 columns) where that gives the chip enough workgroups,
+// 1 (64 x 64) for few rows x few columns, where the GEMM is still a weight stream and needs the
+// workgroups more than the reuse.
+template <int EPI, int CW>
 __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
     __shared__ u32x4_t stage[2][4][4][2][64];           // [buffer][k-tile][row tile][hi|lo][lane]: 2 x 32 KB
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int lm = lane & 15, g4 = lane >> 4;
     const int KT = a.K >> 5, NS = KT >> 2, MT = (a.M + 15) >> 4;
     // id -> (XCD x, sequence number q on that XCD) -> row block q % nrb of unit 8 * (q / nrb) + x
-    const int nrb = (MT + 3) >> 2, ncb = (a.NT + 15) >> 4;
+    const int nrb = (MT + 3) >> 2, ncb = (a.NT + 4 * CW - 1) / (4 * CW);
     const int xq = blockIdx.x >> 3, unit = (xq / nrb) * 8 + (blockIdx.x & 7), rb = xq % nrb;
     if (unit >= ncb * a.sk) return;                      // grid padding (whole workgroup leaves together)
     const int cb = unit / a.sk, ks = unit % a.sk;
     const int s_lo = (int)((unsigned)NS * (unsigned)ks / (unsigned)a.sk), s_hi = (int)((unsigned)NS * (unsigned)(ks + 1) / (unsigned)a.sk);
-    const int nt0 = cb * 16 + 4 * w;                     // this wave's 4 n-tiles
+    const int nt0 = cb * (4 * CW) + CW * w;              // this wave's CW n-tiles
     const int mt0 = rb * 4;
     const u32x4_t* AFp = (const u32x4_t*)a.AF;
     const u32x4_t* Wp = (const u32x4_t*)a.W + lane;
@@ -123,23 +126,23 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
             stage[buf][f >> 3][(f >> 1) & 3][f & 1][ln] = r[i];
         }
     };
-    auto wload = [&](u32x4_t (&wt)[4], int kt) {
+    auto wload = [&](u32x4_t (&wt)[CW], int kt) {
         const int kc = kt < KT ? kt : KT - 1;                 // past the end: re-read the last k-tile (never used)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < CW; ++j) {
             const int nt = nt0 + j < a.NT ? nt0 + j : a.NT - 1;
             wt[j] = Wp[((size_t)nt * KT + kc) * 64];       // plain loads: the row blocks of a column block share these lines in L2
         }
     };
 
-    f32x4_t acc[4][4];
+    f32x4_t acc[CW][4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < CW; ++j)
 #pragma unroll
         for (int m = 0; m < 4; ++m) acc[j][m] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
     u32x4_t sr[8];
-    u32x4_t W0[4], W1[4], W2[4], W3[4];
+    u32x4_t W0[CW], W1[CW], W2[CW], W3[CW];
     stage_load(sr, s_lo);
     wload(W0, 4 * s_lo); wload(W1, 4 * s_lo + 1); wload(W2, 4 * s_lo + 2); wload(W3, 4 * s_lo + 3);
     stage_store(sr, 0);
@@ -149,7 +152,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
     do {                                                                                            \
         Frag ah[4], al[4];                                                                          \
         _Pragma("unroll") for (int m = 0; m < 4; ++m) { ah[m].u = stage[buf][U][m][0][lane]; al[m].u = stage[buf][U][m][1][lane]; } \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                             \
+        _Pragma("unroll") for (int j = 0; j < CW; ++j) {                                            \
             Frag wf; wf.u = WSET[j];                                                                \
             _Pragma("unroll") for (int m = 0; m < 4; ++m) {                                         \
                 acc[j][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, ah[m].v, acc[j][m], 0, 0, 0); \
@@ -181,7 +184,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
         const int row = (mt0 + m) * 16 + lm;
         const bool rok = mt0 + m < MT && row < a.M;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < CW; ++j) {
             const int nt = nt0 + j;
             const bool ok = rok && nt < a.NT;
             const f32x4_t v = acc[j][m];
@@ -293,6 +296,12 @@ __global__ __launch_bounds__(256) void k_resid_reduce(const float* part, int sk,
     *o = *o + s;
 }
 
+// narrow tiles where the wide ones would give fewer than 200 workgroups and K cannot be split instead
+// (the residual GEMMs fill the chip with K slices, which keeps the reuse of the wide tile)
+bool fc_gemm256_narrow(int epi, int M, int NT) {
+    return epi != EPI_RESID && ((NT + 15) / 16) * (((M + 15) / 16 + 3) / 4) < 200;
+}
+
 int fc_gemm256_sk(int M, int K, int NT) {
     const int nwg = ((NT + 15) / 16) * (((M + 15) / 16 + 3) / 4), NS = K / 128;
     if (nwg >= 200) return 1;
@@ -302,18 +311,28 @@ int fc_gemm256_sk(int M, int K, int NT) {
     return sk < 1 ? 1 : sk;
 }
 
+template <int CW>
+static hipError_t launch256(int epi, const Gemm256Args& a, dim3 grid, hipStream_t st) {
+    switch (epi) {
+        case EPI_RESID: k_gemm256<EPI_RESID, CW><<<grid, 256, 0, st>>>(a); break;
+        case EPI_SWIGLU: k_gemm256<EPI_SWIGLU, CW><<<grid, 256, 0, st>>>(a); break;
+        case EPI_QKV: k_gemm256<EPI_QKV, CW><<<grid, 256, 0, st>>>(a); break;
+        case EPI_LMHEAD: k_gemm256<EPI_LMHEAD, CW><<<grid, 256, 0, st>>>(a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t fc_gemm256(int epi, const Gemm256Args& a, hipStream_t st) {
     if (a.M < 1 || a.K % 256 || a.NT < 1 || a.sk < 1 || a.sk > FC_GEMM256_MAX_SK || a.sk > a.K / 128) return hipErrorInvalidValue;
     if (a.sk > 1 && (epi != EPI_RESID || !a.part)) return hipErrorInvalidValue;
-    const int nrb = ((a.M + 15) / 16 + 3) / 4, units = ((a.NT + 15) / 16) * a.sk;
+    // narrow tiles when wide ones would leave most of the chip idle
+    const int nrb = ((a.M + 15) / 16 + 3) / 4;
+    const int cw = (fc_gemm256_narrow(epi, a.M, a.NT) && a.cw != 4) || a.cw == 1 ? 1 : 4;
+    const int units = ((a.NT + 4 * cw - 1) / (4 * cw)) * a.sk;
     dim3 grid((unsigned)((units + 7) / 8) * 8 * nrb);
-    switch (epi) {
-        case EPI_RESID: k_gemm256<EPI_RESID><<<grid, 256, 0, st>>>(a); break;
-        case EPI_SWIGLU: k_gemm256<EPI_SWIGLU><<<grid, 256, 0, st>>>(a); break;
-        case EPI_QKV: k_gemm256<EPI_QKV><<<grid, 256, 0, st>>>(a); break;
-        case EPI_LMHEAD: k_gemm256<EPI_LMHEAD><<<grid, 256, 0, st>>>(a); break;
-        default: return hipErrorInvalidValue;
-    }
+    hipError_t e = cw == 1 ? launch256<1>(epi, a, grid, st) : launch256<4>(epi, a, grid, st);
+    if (e != hipSuccess) return e;
     if (a.sk > 1) {
         const size_t n = (size_t)a.M * (a.NT * 4);
         k_resid_reduce<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a.part, a.sk, a.M, a.NT * 16, a.out, a.ldo);
