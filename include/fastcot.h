@@ -119,6 +119,15 @@ int fastcot_get_state(fastcot_ctx* ctx, int32_t* n, int32_t* generated, int32_t*
 
 /* Debug: if d_logits (device, fp32 [max_batch*W][vocab]) is non-NULL every following step also
  * stores the full logits there (row b*W + j); NULL switches it off. */
+/* Answer phase (Sec. 4.4 "Trigger Answer"), after fastcot_generate has returned: every sequence continues
+ * from its prompt and exact tokens (already in the cache), the approximate tokens still in its window
+ * (the glimpse; none for a sequence that ended with the EOS given to fastcot_generate), and the n_trigger
+ * answer-trigger token ids (host, may be 0), and decodes greedily, one token per step, until
+ * max_new_tokens or eos_id (< 0: off).  out_ids host
+ * [B][max_new_tokens] (-1 past out_len[b]).  Afterwards the context needs a new fastcot_prefill. */
+int fastcot_answer(fastcot_ctx* ctx, const int32_t* trigger_ids, int32_t n_trigger, int32_t max_new_tokens,
+                   int32_t eos_id, int32_t* out_ids, int32_t* out_len);
+
 int fastcot_debug_logits(fastcot_ctx* ctx, float* d_logits);
 
 /* Options.  FASTCOT_OPT_PLAIN_KERNELS = 1 routes every step through the plain one-thread-per-

@@ -22,6 +22,7 @@ struct fastcot_ctx {
     hipStream_t st;
     int Bact;            // sequences of the current run
     int prefilled, generated;
+    int last_eos;        // eos_id of the last fastcot_generate (-1 = none)
     int buf_len;
     int opt_plain, opt_graph, opt_persist, dbg_stop;
     float* dbg_logits;
@@ -517,7 +518,7 @@ extern "C" int fastcot_generate(fastcot_ctx* c, int32_t max_new, int32_t max_ste
     }
     int32_t params[8] = {max_new, eos_id < 0 ? -1 : eos_id, max_steps > 0 ? max_steps : 0, c->buf_len, B, 0, 0, 0};
     HIPCHK(c, hipMemcpy(stp + sm.params, params, sizeof(params), hipMemcpyHostToDevice));
-    c->generated = 1;
+    c->generated = 1; c->last_eos = eos_id < 0 ? -1 : eos_id;
     c->step_ms.clear();
     size_t ev_used = 0;
     auto next_event = [&](hipEvent_t* ev) -> hipError_t {
@@ -575,6 +576,112 @@ extern "C" int fastcot_generate(fastcot_ctx* c, int32_t max_new, int32_t max_ste
         HIPCHK(c, hipMemcpy(win.data(), stp + sm.win, win.size() * 4, hipMemcpyDeviceToHost));
         for (int b = 0; b < B; ++b) for (int j = 1; j < W; ++j) approx_tail[(size_t)b * (W - 1) + j - 1] = win[(size_t)b * W + j];
     }
+    return 0;
+}
+
+// ------------------------------------------------------------------ answer phase
+// Sec. 4.4 "Trigger Answer": when the iterations have stopped, the complete prompt, all generated tokens --
+// the exact ones and the approximate ones still in the window, the glimpse -- and the answer trigger are
+// put together and the model decodes the answer directly.  Here the cache already holds the K/V of the
+// prompt and the exact tokens, so only the newest exact token, the glimpse and the trigger are run through
+// the model (one pass, no LM head; their last token becomes the input of the first decoding step), then
+// the answer is decoded greedily one token per step (Eq. 1).  A sequence that ended with EOS has no
+// glimpse: its context ends at the EOS.
+extern "C" int fastcot_answer(fastcot_ctx* c, const int32_t* trigger_ids, int32_t n_trigger, int32_t max_new,
+                              int32_t eos_id, int32_t* out_ids, int32_t* out_len) {
+    if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
+    if (!c->prefilled || !c->generated) return fail(c, FASTCOT_ESTATE, "fastcot_answer needs a finished fastcot_generate%s");
+    if (!out_ids || !out_len || max_new < 1 || n_trigger < 0 || (n_trigger > 0 && !trigger_ids))
+        return fail(c, FASTCOT_EINVAL, "bad arguments%s");
+    const KernelDims& kd = c->kd; const StateMap& sm = c->wm.st; const int B = c->Bact, W = kd.W, S = kd.S;
+    for (int i = 0; i < n_trigger; ++i)
+        if (trigger_ids[i] < 0 || trigger_ids[i] >= kd.V) return fail(c, FASTCOT_EINVAL, "trigger token out of vocabulary%s");
+    int32_t* stp = state_ptr(c);
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    std::vector<int32_t> hn(B), hg(B), holen(B), hnew(B), hplen(B), hwin((size_t)B * W), hout((size_t)B * S);
+    HIPCHK(c, hipMemcpy(hn.data(), stp + sm.n, (size_t)B * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(hg.data(), stp + sm.g, (size_t)B * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(holen.data(), stp + sm.olen, (size_t)B * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(hnew.data(), stp + sm.newest, (size_t)B * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(hplen.data(), stp + sm.plen, (size_t)B * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(hwin.data(), stp + sm.win, hwin.size() * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(hout.data(), stp + sm.out, hout.size() * 4, hipMemcpyDeviceToHost));
+    // per sequence: the tokens that still have to enter the cache, and the committed length they start at
+    std::vector<std::vector<int32_t>> ctxrows(B);
+    int R = 0;
+    for (int b = 0; b < B; ++b) {
+        std::vector<int32_t>& t = ctxrows[b];
+        const bool eos_end = c->last_eos >= 0 && holen[b] > 0 && hout[(size_t)b * S + holen[b] - 1] == c->last_eos;
+        if (eos_end) {       // keep the exact tokens up to the EOS; K/V valid below its position
+            hn[b] = hplen[b] - 1 + holen[b];
+            t.push_back(c->last_eos);
+        } else {             // newest exact token (not in the cache yet), then the glimpse
+            if (hn[b] != hplen[b] - 1 + hg[b]) return fail(c, FASTCOT_ESTATE, "inconsistent sequence state%s");
+            t.push_back(hg[b] > 0 ? hnew[b] : hwin[(size_t)b * W]);
+            for (int j = 1; j < W; ++j) t.push_back(hwin[(size_t)b * W + j]);
+        }
+        for (int i = 0; i < n_trigger; ++i) t.push_back(trigger_ids[i]);
+        if ((int)t.size() - 1 > R) R = (int)t.size() - 1;
+        if (hn[b] + (int)t.size() + max_new + 1 > S) return fail(c, FASTCOT_ECAPACITY, "answer phase does not fit max_seq%s");
+    }
+    HIPCHK(c, hipMemcpy(stp + sm.n, hn.data(), (size_t)B * 4, hipMemcpyHostToDevice));
+    // context passes of at most Wcap rows per sequence (all but the last context token): rows beyond a
+    // sequence's own are pads whose K/V is never committed
+    const int rows_cap = (c->opt_plain || !fc_fast_supported(kd, B * kd.W)) ? kd.W : kd.Wcap;
+    for (int p0 = 0; p0 < R; p0 += rows_cap) {
+        const int Rp = R - p0 < rows_cap ? R - p0 : rows_cap;
+        std::vector<int32_t> rows((size_t)B * Rp, 0);
+        for (int b = 0; b < B; ++b)
+            for (int j = 0; j < Rp && p0 + j + 1 < (int)ctxrows[b].size(); ++j) rows[(size_t)b * Rp + j] = ctxrows[b][p0 + j];
+        HIPCHK(c, hipMemcpy(stp + sm.win, rows.data(), rows.size() * 4, hipMemcpyHostToDevice));
+        int rc = forward(c, 0, 0, Rp);
+        if (rc) return rc;
+        HIPCHK(c, hipStreamSynchronize(c->st));
+        for (int b = 0; b < B; ++b) {
+            int adv = (int)ctxrows[b].size() - 1 - p0;
+            hn[b] += adv < 0 ? 0 : (adv > Rp ? Rp : adv);
+        }
+        HIPCHK(c, hipMemcpy(stp + sm.n, hn.data(), (size_t)B * 4, hipMemcpyHostToDevice));
+    }
+    // one-token window per sequence: slot 0 = the last context token
+    std::vector<int32_t> slot0(B), zero(B, 0);
+    for (int b = 0; b < B; ++b) slot0[b] = ctxrows[b].back();
+    HIPCHK(c, hipMemcpy(stp + sm.win, slot0.data(), (size_t)B * 4, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(stp + sm.newest, slot0.data(), (size_t)B * 4, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(stp + sm.g, zero.data(), (size_t)B * 4, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(stp + sm.done, zero.data(), (size_t)B * 4, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(stp + sm.steps, zero.data(), (size_t)B * 4, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(stp + sm.olen, zero.data(), (size_t)B * 4, hipMemcpyHostToDevice));
+    int32_t params[8] = {max_new, eos_id < 0 ? -1 : eos_id, 0, S, B, 0, 0, 0};
+    HIPCHK(c, hipMemcpy(stp + sm.params, params, sizeof(params), hipMemcpyHostToDevice));
+    int32_t zeros[8] = {0};
+    HIPCHK(c, hipMemcpy(stp + sm.flags, zeros, sizeof(zeros), hipMemcpyHostToDevice));
+    c->prefilled = 0;        // the windowed state is gone: the next run starts with fastcot_prefill
+    // greedy decoding, one row per sequence and step; as many steps at a time as every unfinished sequence
+    // still needs at least
+    std::vector<int32_t> g2(B, 0), d2(B, 0);
+    bool all_done = false;
+    while (!all_done) {
+        int need = 1;
+        for (int b = 0; b < B; ++b) if (!d2[b] && max_new - g2[b] > need) need = max_new - g2[b];
+        for (int s = 0; s < need; ++s) {
+            int rc = forward(c, 1, 0, 1);
+            if (rc) return rc;
+            HIPCHK(c, fc_accept_commit(stp, sm, B, 1, S, c->st));
+        }
+        HIPCHK(c, hipMemcpyAsync(c->pinned, stp + sm.g, (size_t)B * 4, hipMemcpyDeviceToHost, c->st));
+        HIPCHK(c, hipMemcpyAsync(c->pinned + B, stp + sm.done, (size_t)B * 4, hipMemcpyDeviceToHost, c->st));
+        HIPCHK(c, hipMemcpyAsync(c->pinned + 2 * B, stp + sm.flags, 8, hipMemcpyDeviceToHost, c->st));
+        HIPCHK(c, hipStreamSynchronize(c->st));
+        { int rc = check_abort(c); if (rc) return rc; }
+        all_done = c->pinned[2 * B + FLAG_ALL_DONE] != 0;
+        for (int b = 0; b < B; ++b) { g2[b] = c->pinned[b]; d2[b] = c->pinned[B + b]; }
+        if (c->pinned[2 * B + FLAG_ERROR]) return fail(c, FASTCOT_ECAPACITY, "a sequence ran out of cache capacity%s");
+    }
+    HIPCHK(c, hipMemcpy(hout.data(), stp + sm.out, hout.size() * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(out_len, stp + sm.olen, (size_t)B * 4, hipMemcpyDeviceToHost));
+    for (int b = 0; b < B; ++b)
+        for (int i = 0; i < max_new; ++i) out_ids[(size_t)b * max_new + i] = i < out_len[b] ? hout[(size_t)b * S + i] : -1;
     return 0;
 }
 

@@ -81,6 +81,45 @@ def test_fast_path_matches_plain_path_and_oracle_stream(fc):
         assert outs[0]["steps"][0] == ref["steps"] and (outs[0]["ids"][0] == outs[1]["ids"][0]).all()
 
 
+def test_answer_phase_bf16(fc):
+    """Answer phase (Sec. 4.4 "Trigger Answer") on a bf16 model, batch of two stopping differently (one by
+    the iteration cap with a glimpse, both with a trigger): the MFMA kernels and the plain kernels give the
+    same answer tokens, and they are the oracle's greedy continuation of the combined context up to the
+    first low-margin row."""
+    shape, W, P, N, NA = SMALL, 16, 40, 48, 10
+    S = ((P + N + 3 * W + NA + 31) // 32) * 32
+    ctx, om = setup(fc, shape, 2, S, W)
+    prompts = synthgen.prompts(2, P, shape.vocab, seed=51)
+    lens = [P, P - 5]
+    buf = synthgen.buffer_init(2, N + 2 * W, shape.vocab, seed=52)
+    trigger = np.array([11, 222, 333, 44], dtype=np.int32)
+    res = {}
+    for plain in (0, 1):
+        say(f"bf16 answer phase plain={plain}")
+        ctx.set_option(1, plain)
+        ctx.prefill(prompts, lens, buf)
+        out = ctx.generate(N, max_steps=4)
+        st = ctx.state()
+        ans = ctx.answer(trigger, NA)
+        res[plain] = (out, st, ans)
+    (out, st, ans), (out1, st1, ans1) = res[0], res[1]
+    assert (out["ids"] == out1["ids"]).all() and (st["window"] == st1["window"]).all()
+    for b in range(2):
+        g = int(st["g"][b])
+        exact = out["ids"][b][:g]
+        assert int(out["len"][b]) == g and exact[-1] == st["window"][b][0]
+        combined = np.concatenate([prompts[b, :lens[b]], exact, st["window"][b][1:], trigger]).astype(np.int32)
+        want = om.greedy_ar(combined, NA)
+        ss = om.session(S)
+        ss.forward(combined[:-1], 0, want_logits=False)
+        lg, _, _ = ss.forward(np.concatenate([combined[-1:], want[:-1]]), len(combined) - 1)
+        low = np.where(margins(lg) <= 0.05)[0]
+        upto = int(low[0]) if len(low) else NA
+        assert ans["ids"][b][:upto].tolist() == want[:upto].tolist(), (b, upto)
+        assert ans1["ids"][b][:upto].tolist() == want[:upto].tolist(), (b, upto)
+        print(f"answer phase seq {b}: {upto} of {NA} tokens above the margin, all equal")
+
+
 def test_deterministic_replay(fc):
     shape, W, P, N = SMALL, 16, 30, 40
     S = ((P + N + 2 * W + 31) // 32) * 32

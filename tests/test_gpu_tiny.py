@@ -43,6 +43,29 @@ def test_generate_matches_oracle_free_run(env):
     assert (out["ids"][0] == om.greedy_ar(prompt[0], N)).all()
 
 
+def test_generate_matches_stored_trajectory(env):
+    """The same run against tests/golden/tiny_trajectory.json (written by the oracle alone)."""
+    import json
+    import os
+    fc, _ = env
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "tiny_trajectory.json")) as f:
+        g = json.load(f)
+    P, W, N = g["config"]["prompt"], g["config"]["window"], g["config"]["new_tokens"]
+    say("tiny generate against the stored trajectory")
+    ctx = make_ctx(fc, 1, P + N + 2 * W, W)
+    ctx.prefill(np.array([g["prompt"]], dtype=np.int32), [P], synthgen.buffer_init(1, N + 2 * W, TINY.vocab))
+    Ks = []
+    while True:
+        nacc, acc, _ = ctx.step()
+        Ks.append(int(nacc[0]) - 1)
+        if sum(k + 1 for k in Ks) >= N:
+            break
+    assert Ks == g["K"]
+    ctx.prefill(np.array([g["prompt"]], dtype=np.int32), [P], synthgen.buffer_init(1, N + 2 * W, TINY.vocab))
+    out = ctx.generate(N)
+    assert out["ids"][0].tolist() == g["ids"] and int(out["steps"][0]) == g["steps"] and out["tail"][0].tolist() == g["tail"]
+
+
 def test_stepwise_logits_and_counts(env):
     fc, om = env
     P, W, N = 32, 8, 64
@@ -145,3 +168,40 @@ def test_capacity_and_state_errors(env):
     with pytest.raises(fc.FastcotError) as e:
         ctx.generate(16)
     assert e.value.rc == -2
+
+
+@pytest.mark.parametrize("mode", ["cap", "eos", "budget"])
+def test_answer_phase_matches_greedy_on_the_combined_context(env, mode):
+    """Sec. 4.4 "Trigger Answer": prompt + exact tokens + glimpse (none after an EOS) + trigger, then greedy
+    decoding; the oracle does the same with its greedy loop (Eq. 1) over the combined token list."""
+    fc, om = env
+    P, W, N, NA = 32, 8, 40, 12
+    trigger = np.array([5, 77, 301], dtype=np.int32)
+    prompt = synthgen.prompts(1, P, TINY.vocab, seed=31)
+    buf = synthgen.buffer_init(1, N + 2 * W, TINY.vocab, seed=32)
+    greedy = om.greedy_ar(prompt[0], N)
+    eos = int(greedy[9]) if mode == "eos" else -1
+    max_steps = 5 if mode == "cap" else 0
+    ref = om.jacobi_generate(prompt[0], buf[0], W, N, max_steps=max_steps, eos=eos)
+    say(f"tiny answer phase, stop by {mode}")
+    ctx = make_ctx(fc, 1, P + N + 4 * W + NA + 8, W)
+    ctx.prefill(prompt, [P], buf)
+    out = ctx.generate(N, max_steps=max_steps, eos_id=eos)
+    n_exact = int(out["len"][0])
+    assert out["ids"][0][:n_exact].tolist() == ref["ids"].tolist()
+    st = ctx.state()
+    if mode == "eos":
+        assert out["ids"][0][n_exact - 1] == eos
+        combined = np.concatenate([prompt[0], out["ids"][0][:n_exact], trigger])
+    else:
+        # every exact token the run accepted (the last step may have accepted more than the budget), then
+        # the glimpse
+        g = int(st["g"][0])
+        exact = om.greedy_ar(prompt[0], g)
+        assert exact[:n_exact].tolist() == out["ids"][0][:n_exact].tolist() and exact[g - 1] == st["window"][0][0]
+        combined = np.concatenate([prompt[0], exact, st["window"][0][1:], trigger])
+    want = om.greedy_ar(combined.astype(np.int32), NA)
+    ans = ctx.answer(trigger, NA)
+    assert ans["len"][0] == NA and ans["ids"][0].tolist() == want.tolist()
+    with pytest.raises(fc.FastcotError):
+        ctx.step()                      # the windowed state is gone until the next prefill

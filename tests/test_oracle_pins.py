@@ -285,3 +285,22 @@ def test_bf16_storage_is_exact():
     la, _, _ = a.session(16).forward(t, 0)
     lb, _, _ = b.session(16).forward(t, 0)
     assert (la == lb).all()
+
+
+def test_stored_tiny_trajectory_is_reproduced():
+    """tests/golden/tiny_trajectory.json was written by tests/golden/make_golden.py from this oracle: the
+    oracle, the input generators and the stored trajectory must still agree (regression pin, Sec. 4.1-4.4)."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "golden", "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    with open(os.path.join(here, "golden", "tiny_trajectory.json")) as f:
+        stored = json.load(f)
+    assert mod.trajectory() == stored
+    # structure every trajectory has: each step accepts K+1 in 1..W, the counts add up to the output
+    W, N = stored["config"]["window"], stored["config"]["new_tokens"]
+    assert all(0 <= k <= W - 1 for k in stored["K"]) and len(stored["K"]) == stored["steps"]
+    assert sum(k + 1 for k in stored["K"]) >= N > sum(k + 1 for k in stored["K"][:-1])
