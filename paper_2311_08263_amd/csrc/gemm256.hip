@@ -8,7 +8,13 @@
 // straight from global memory, 4 k-tiles ahead) feeds 8.  Activation fragments of 4 k-tiles at a
 // time are copied global -> LDS by the whole workgroup, double buffered (2 x 32 KB), one barrier per
 // stage.  The four workgroups of a column block re-read the same weights: HBM sees them once, the
-// repeats come from L2: workgroup ids are mapped so that the row blocks of one column block run on
+// repeats come from L2.  What bounds the kernel at 256 rows is LDS bandwidth (128 bytes per clock and CU): every
+// MFMA of 16 clocks takes a quarter of a 1 KB activation fragment out of LDS per wave, half of what the LDS
+// delivers when all four SIMDs issue back to back, and the two do not overlap perfectly (measured: MFMA busy
+// 38 %, no bank conflicts, 2.6 % of wave time waiting on LDS instructions, 54 % on any instruction).  A
+// variant with 128-row tiles and both operands staged through LDS (half the L2 -> CU traffic) was slower
+// (gate/up 170 us against 156 us): the next step is a register tile with more columns per wave or the
+// 32x32x16 MFMA, which both halve the LDS bytes per flop.  Workgroup ids are mapped so that the row blocks of one column block run on
 // the same XCD (ids that are equal mod 8 share an XCD and its L2), back to back.  Matrices with few
 // columns (O and down projections) are also split along K so that the launch fills the chip; the
 // slices store partial tiles and k_resid_reduce adds them to the residual stream in slice order.
@@ -160,11 +166,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
             }                                                                                       \
         }                                                                                           \
         wload(WSET, 4 * s + U + 4);                                                                 \
+        __builtin_amdgcn_sched_barrier(0);   /* keep these loads here: four k-tiles ahead of their use */ \
     } while (0)
 
     int buf = 0;
     for (int s = s_lo; s < s_hi; ++s) {
         stage_load(sr, s + 1 < s_hi ? s + 1 : s);        // next stage's activations travel while this one is used
+        __builtin_amdgcn_sched_barrier(0);               // (left alone the scheduler sinks all loads to the end of the stage)
         STEP(W0, 0);
         STEP(W1, 1);
         STEP(W2, 2);
