@@ -157,7 +157,8 @@ enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLAN
        /* K slices per column owner of the column-owner GEMM for the O / down projections (1..8; the
         * workgroup count must be a multiple of it) */
        FASTCOT_OPT_KS_O = 32, FASTCOT_OPT_KS_DOWN = 33,
-       FASTCOT_OPT_CO_SINGLE = 27,   /* 1: one weight batch in flight per wave (two workgroups per CU) */
+       FASTCOT_OPT_CO_SINGLE = 27,   /* weight batches in flight per wave of the column-owner GEMM: 1 = one, 0 = two,
+                                      * 2 (default) = chosen per GEMM */
        /* debug: run only the first `value` stages of a forward (per layer: QKV, attention, O,
         * gate/up, down); negative = all */
        FASTCOT_OPT_DEBUG_STAGES = 30 };

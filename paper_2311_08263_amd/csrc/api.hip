@@ -287,7 +287,10 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
         if (nw > 0 && (nw % value || nw / value > NT || nw / value < 1 || (NT + nw / value - 1) / (nw / value) > 8))
             return fail(c, FASTCOT_EINVAL, "K slices per owner do not fit the workgroup count of that GEMM%s");
         c->plan.ks[gi] = value;
-    } else if (option == FASTCOT_OPT_CO_SINGLE) c->plan.co_single = value != 0;
+    } else if (option == FASTCOT_OPT_CO_SINGLE) {
+        if (value < 0 || value > 2) return fail(c, FASTCOT_EINVAL, "buffering of the column-owner GEMM: 0, 1 or 2%s");
+        c->plan.co_single = value;
+    }
     else if (option == FASTCOT_OPT_ATTN_SPLITS) {
         if (value < 1 || value > FC_MAX_ATTN_SPLITS) return fail(c, FASTCOT_EINVAL, "attention splits out of range%s");
         c->plan.attn_splits = value;

@@ -14,7 +14,7 @@ struct FastPlan {
     GemmPlan qkv, o, gu, down, lm;
     int32_t attn_splits;
     int32_t attn_bpw;  // key blocks of 32 per attention workgroup (decides at run time how many of the splits work)
-    int32_t co_single; // column-owner GEMM: single-buffered variant
+    int32_t co_single; // column-owner GEMM: 1 = one weight batch in flight per wave, 0 = two, 2 = chosen per GEMM
     int32_t ks[5];     // column-owner GEMM: K slices per owner (residual GEMMs only; 1 elsewhere)
     int32_t nw2[5], ks2[5];   // the same for passes of 17..32 rows (two row tiles per workgroup)
     int32_t nw[5];     // column-owner GEMM: workgroups for QKV, O, gate/up, down, LM head; 0 = use the split-K kernel

@@ -146,8 +146,10 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         for (int ib = 0; ib < nb; ib += 2) {
             compute(A, ib);
             load(A, ib + 2);
+            __builtin_amdgcn_sched_barrier(0);          // the loads stay here, ahead of the other batch's arithmetic
             compute(B, ib + 1);
             load(B, ib + 3);
+            __builtin_amdgcn_sched_barrier(0);
         }
     } else {
         if (a.gain) {
