@@ -119,6 +119,13 @@ int fastcot_get_state(fastcot_ctx* ctx, int32_t* n, int32_t* generated, int32_t*
 
 /* Debug: if d_logits (device, fp32 [max_batch*W][vocab]) is non-NULL every following step also
  * stores the full logits there (row b*W + j); NULL switches it off. */
+/* Changes the window size between two fastcot_jacobi_step calls (not during fastcot_generate): the next
+ * step runs `window` rows per sequence, slot 0 the newest exact token, the rest from the buffer.  1 <= window
+ * <= the rows a pass may have (the configured window, or 256 where the matrix-core path covers the model);
+ * FASTCOT_ECAPACITY if a sequence has no room for it.  The accepted stream does not depend on the window
+ * (Sec. 4.1); the step count does.  This is the hook an adaptive-window controller needs (Limitations). */
+int fastcot_set_window(fastcot_ctx* ctx, int32_t window);
+
 /* Answer phase (Sec. 4.4 "Trigger Answer"), after fastcot_generate has returned: every sequence continues
  * from its prompt and exact tokens (already in the cache), the approximate tokens still in its window
  * (the glimpse; none for a sequence that ended with the EOS given to fastcot_generate), and the n_trigger

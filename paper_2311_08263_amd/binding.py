@@ -62,6 +62,7 @@ SYMBOLS = {
     "fastcot_profile_step": (ctypes.c_int, [vp, i32, vp, vp]),
     "fastcot_kernel_name": (ctypes.c_char_p, [i32]),
     "fastcot_attn_scratch_bytes": (sz, [i32, i32, i32]),
+    "fastcot_set_window": (ctypes.c_int, [vp, i32]),
     "fastcot_answer": (ctypes.c_int, [vp, vp, i32, i32, i32, vp, vp]),
     "fastcot_stream_read": (ctypes.c_int, [vp, ctypes.c_size_t, vp, vp]),
     "fastcot_kv_scatter": (ctypes.c_int, [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]),
@@ -226,6 +227,11 @@ class Context:
         _check(lib().fastcot_generate(self.h, max_new_tokens, max_steps, eos_id, ids.ctypes.data, olen.ctypes.data,
                                       steps.ctypes.data, tail.ctypes.data), self.h)
         return dict(ids=ids, len=olen, steps=steps, tail=tail[:, :W - 1])
+
+    def set_window(self, window: int) -> None:
+        """Window size of the following steps (between step() calls only)."""
+        _check(lib().fastcot_set_window(self.h, window), self.h)
+        self.cfg.window = window
 
     def answer(self, trigger_ids, max_new_tokens: int, eos_id: int = -1):
         """Answer phase after generate(): glimpse + trigger enter the cache, then greedy decoding."""

@@ -501,6 +501,30 @@ extern "C" int fastcot_jacobi_step(fastcot_ctx* c, int32_t* n_accepted, int32_t*
     return 0;
 }
 
+// ------------------------------------------------------------------ window size between steps
+// The paper fixes the window per run and names an adaptive size as future work (Limitations); this is the
+// hook such a controller needs: from the next fastcot_jacobi_step on, every sequence runs `window` rows.
+extern "C" int fastcot_set_window(fastcot_ctx* c, int32_t window) {
+    if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
+    if (!c->prefilled) return fail(c, FASTCOT_ESTATE, "fastcot_set_window before fastcot_prefill%s");
+    if (c->generated) return fail(c, FASTCOT_ESTATE, "fastcot_set_window after fastcot_generate%s");
+    if (window < 1 || window > c->kd.Wcap) return fail(c, FASTCOT_ECAPACITY, "window %s%ld outside 1..%ld", "", (long)window, (long)c->kd.Wcap);
+    if (window == c->kd.W) return 0;
+    const StateMap& sm = c->wm.st; const int B = c->Bact;
+    int32_t* stp = state_ptr(c);
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    std::vector<int32_t> hn(B), hg(B);
+    HIPCHK(c, hipMemcpy(hn.data(), stp + sm.n, (size_t)B * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(hg.data(), stp + sm.g, (size_t)B * 4, hipMemcpyDeviceToHost));
+    for (int b = 0; b < B; ++b)
+        if (hn[b] + window > c->kd.S || hg[b] + 2 * window - 1 > c->buf_len)
+            return fail(c, FASTCOT_ECAPACITY, "window %s%ld does not fit the cache or the buffer of a sequence", "", (long)window);
+    drop_graph(c);
+    c->kd.W = window; c->cfg.window = window;
+    HIPCHK(c, fc_rewindow(stp, sm, B, window, c->kd.S, c->st));
+    return 0;
+}
+
 // ------------------------------------------------------------------ generate
 extern "C" int fastcot_generate(fastcot_ctx* c, int32_t max_new, int32_t max_steps, int32_t eos_id, int32_t* out_ids,
                                 int32_t* out_len, int32_t* out_steps, int32_t* approx_tail) {

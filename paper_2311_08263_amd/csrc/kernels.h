@@ -18,6 +18,7 @@ hipError_t fc_argmax_plain(const float* logits, int M, int V, int32_t* ids, floa
 hipError_t fc_prefill_window(int32_t* state, const StateMap& sm, int B, int R, int S, int p0, hipStream_t st);
 hipError_t fc_prefill_advance(int32_t* state, const StateMap& sm, int B, int W, int S, int p1, int last,
                               hipStream_t st);
+hipError_t fc_rewindow(int32_t* state, const StateMap& sm, int B, int W, int S, hipStream_t st);
 hipError_t fc_accept_commit(int32_t* state, const StateMap& sm, int B, int W, int S, hipStream_t st);
 
 // ---- weight packing

@@ -88,6 +88,21 @@ __global__ void k_accept_commit(int32_t* st, StateMap sm, int B, int W, int S) {
     __syncthreads();
     if (threadIdx.x == 0) st[sm.flags + FLAG_ALL_DONE] = (not_done == 0);
 }
+// A new window size between steps: the window is rebuilt from the newest exact token and the buffer
+// (the buffer already holds every output of the previous steps, Sec. 4.3 "Cache Update").
+__global__ void k_rewindow(int32_t* st, StateMap sm, int B, int W, int S) {
+    const int buf_len = st[sm.params + PARAM_BUF_LEN];
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B * W) return;
+    const int b = i / W, j = i % W;
+    const int p = st[sm.g + b] + j - 1;
+    st[sm.win + i] = j == 0 ? st[sm.newest + b] : (p < buf_len ? st[sm.buf + (size_t)b * S + p] : 0);
+}
+hipError_t fc_rewindow(int32_t* state, const StateMap& sm, int B, int W, int S, hipStream_t st) {
+    k_rewindow<<<(B * W + 255) / 256, 256, 0, st>>>(state, sm, B, W, S);
+    return hipGetLastError();
+}
+
 hipError_t fc_accept_commit(int32_t* state, const StateMap& sm, int B, int W, int S, hipStream_t st) {
     k_accept_commit<<<1, 64, 0, st>>>(state, sm, B, W, S);
     return hipGetLastError();

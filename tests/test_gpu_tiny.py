@@ -205,3 +205,28 @@ def test_answer_phase_matches_greedy_on_the_combined_context(env, mode):
     assert ans["len"][0] == NA and ans["ids"][0].tolist() == want.tolist()
     with pytest.raises(fc.FastcotError):
         ctx.step()                      # the windowed state is gone until the next prefill
+
+
+def test_window_size_changes_between_steps(env):
+    """Sec. 4.1: whatever the window, every step accepts at least the one exact token and the accepted stream
+    is the greedy continuation (Eq. 1); the window may therefore change from step to step."""
+    fc, om = env
+    P, N, Wmax = 32, 48, 16
+    prompt = synthgen.prompts(1, P, TINY.vocab, seed=61)
+    buf = synthgen.buffer_init(1, N + 4 * Wmax, TINY.vocab, seed=62)
+    greedy = om.greedy_ar(prompt[0], N + Wmax)
+    say("tiny window schedule")
+    ctx = make_ctx(fc, 1, P + N + 4 * Wmax, Wmax)
+    ctx.prefill(prompt, [P], buf)
+    got, schedule, i = [], [8, 8, 4, 16, 2, 1, 5, 16, 3], 0
+    with pytest.raises(fc.FastcotError):
+        ctx.set_window(Wmax + 1)                    # the plain path's passes are at most the configured window
+    while len(got) < N:
+        W = schedule[i % len(schedule)]
+        i += 1
+        ctx.set_window(W)
+        nacc, acc, win = ctx.step()
+        assert 1 <= nacc[0] <= W and win.shape == (1, W)
+        got.extend(acc[0][:nacc[0]].tolist())
+        assert win[0][0] == got[-1]
+    assert got == greedy[:len(got)].tolist()
