@@ -18,6 +18,7 @@ struct GemmCoArgs {
     int32_t ks;            // EPI_RESID only: workgroups per column owner, each taking 1/ks of K (1..8)
     float* xpart;          // ks > 1: partial tiles [workgroup][8][64 lanes][4]
     int32_t* xcnt;         // ks > 1: one arrival counter per owner, zero between launches
+    int32_t rotate;        // walk the K batches in a per-wave rotated order (spreads the streams over the memory channels)
     int32_t single_buffer; // one batch in flight per wave (fewer registers: two workgroups per CU) instead of two
 };
 

@@ -56,6 +56,14 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     const int s_lo = (int)((unsigned)KT * (unsigned)slice / (unsigned)ks), s_len = (int)((unsigned)KT * (unsigned)(slice + 1) / (unsigned)ks) - s_lo;
     const int kt_begin = s_lo + ((w * s_len) >> 3), kt_end = s_lo + (((w + 1) * s_len) >> 3);
     const int nb = (((s_len + 7) >> 3) + KB - 1) / KB;          // batches of the longest wave
+    // With a.rotate every wave walks its batches in a rotated order that differs from wave to wave and
+    // workgroup to workgroup: the slices of different workgroups start at addresses that differ by multiples
+    // of K * 32 bytes, so in step they would all sit on the same memory channels (measured at the 7B shape:
+    // down -5 %, LM head -7 %, gate/up -2 %, QKV +4 %: the caller decides per GEMM).  Batch ib of the loop is
+    // batch (ib + rot) mod nbw of the wave's own nbw batches; the loop indices beyond nbw stay invalid.
+    const int nbw = (kt_end - kt_begin + KB - 1) / KB;
+    const int rot = (a.rotate && nbw > 0) ? (int)(((unsigned)blockIdx.x * 7u + (unsigned)w * 3u) % (unsigned)nbw) : 0;
+    auto rot_batch = [&](int ib) { int r = ib + rot; return ib < nbw ? (r >= nbw ? r - nbw : r) : ib; };
     const float* xr[MT];                                // rows past M repeat a valid row; never written
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) xr[mt] = a.X + (size_t)(mt * 16 + lm < a.M ? mt * 16 + lm : a.M - 1) * a.ldx + 8 * g4;
@@ -68,7 +76,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     auto load = [&](Batch<NW, KB, MT>& b, int ib) {
 #pragma unroll
         for (int t = 0; t < KB; ++t) {
-            const int kt = kt_begin + ib * KB + t;
+            const int kt = kt_begin + rot_batch(ib) * KB + t;
             const bool kv = ib < nb && kt < kt_end;
 #pragma unroll
             for (int j = 0; j < NW; ++j) {
@@ -78,7 +86,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         }
 #pragma unroll
         for (int t = 0; t < KB; ++t) {
-            const int kt = kt_begin + ib * KB + t;
+            const int kt = kt_begin + rot_batch(ib) * KB + t;
             const int kc = (ib < nb && kt < kt_end) ? kt : kt_begin;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
@@ -100,7 +108,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     auto compute = [&](const Batch<NW, KB, MT>& b, int ib) {
 #pragma unroll
         for (int t = 0; t < KB; ++t) {
-            const int kt = kt_begin + ib * KB + t;
+            const int kt = kt_begin + rot_batch(ib) * KB + t;
             const float keep = (ib < nb && kt < kt_end) ? 1.0f : 0.0f;
             const int kc = keep != 0.0f ? kt : kt_begin;
             float4 g0, g1;
