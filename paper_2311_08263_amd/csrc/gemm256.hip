@@ -8,13 +8,12 @@
 // straight from global memory, 4 k-tiles ahead) feeds 8.  Activation fragments of 4 k-tiles at a
 // time are copied global -> LDS by the whole workgroup, double buffered (2 x 32 KB), one barrier per
 // stage.  The four workgroups of a column block re-read the same weights: HBM sees them once, the
-// repeats come from L2.  What bounds the kernel at 256 rows is LDS bandwidth (128 bytes per clock and CU): every
-// MFMA of 16 clocks takes a quarter of a 1 KB activation fragment out of LDS per wave, half of what the LDS
-// delivers when all four SIMDs issue back to back, and the two do not overlap perfectly (measured: MFMA busy
-// 38 %, no bank conflicts, 2.6 % of wave time waiting on LDS instructions, 54 % on any instruction).  A
-// variant with 128-row tiles and both operands staged through LDS (half the L2 -> CU traffic) was slower
-// (gate/up 170 us against 156 us): the next step is a register tile with more columns per wave or the
-// 32x32x16 MFMA, which both halve the LDS bytes per flop.  Workgroup ids are mapped so that the row blocks of one column block run on
+// repeats come from L2.  What bounds the kernel at 256 rows is latency (measured: MFMA busy 38 %, no bank
+// conflicts, 2.6 % of wave time waiting on LDS instructions, 54 % on any instruction): weights and the next
+// stage's activations are requested about 1.7 us before their use, less than an L2 round trip under this load.
+// Two variants that halved a bandwidth instead were slower: 128-row tiles with both operands staged through
+// LDS (half the L2 -> CU traffic; gate/up 170 us against 156 us) and 8 x 2 tiles per wave (half the LDS bytes
+// per MFMA, weights only two k-tiles ahead; 182 us).  Workgroup ids are mapped so that the row blocks of one column block run on
 // the same XCD (ids that are equal mod 8 share an XCD and its L2), back to back.  Matrices with few
 // columns (O and down projections) are also split along K so that the launch fills the chip; the
 // slices store partial tiles and k_resid_reduce adds them to the residual stream in slice order.
