@@ -242,9 +242,11 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) st_agent_f32(mine + qt * PART_FLOATS + ((2 * wv + t) * 64 + lane) * 4 + r, o2[qt][t][r]);
+            for (int t = 0; t < 2; ++t) {
+                float* dst = mine + qt * PART_FLOATS + ((2 * wv + t) * 64 + lane) * 4;
+                st_agent_f32x2(dst, o2[qt][t][0], o2[qt][t][1]);
+                st_agent_f32x2(dst + 2, o2[qt][t][2], o2[qt][t][3]);
+            }
             if (wv == 0) {
                 st_agent_f32(mine + qt * PART_FLOATS + 2048 + lane, mw[qt]);
                 st_agent_f32(mine + qt * PART_FLOATS + 2112 + lane, lw[qt]);
@@ -260,22 +262,26 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
         for (int qt = 0; qt < QT; ++qt) {
             float m = NEG_BIG, l = 0.f;
             o2[qt][0] = o2[qt][1] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-            for (int s0 = 0; s0 < nsp; s0 += 4) {          // four splits' loads in flight at a time
-                float ms[4], ls[4];
-                f32x4_t os[4][2];
+            for (int s0 = 0; s0 < nsp; s0 += 8) {          // eight splits' loads in flight at a time
+                float ms[8], ls[8];
+                f32x4_t os[8][2];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < 8; ++u) {
                     const int s2 = s0 + u < nsp ? s0 + u : nsp - 1;
                     const float* src = a.part + ((size_t)bh * nsp_max + s2) * QT * PART_FLOATS + qt * PART_FLOATS;
                     ms[u] = ld_agent_f32(src + 2048 + lane);
                     ls[u] = ld_agent_f32(src + 2112 + lane);
 #pragma unroll
-                    for (int t = 0; t < 2; ++t)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) os[u][t][r] = ld_agent_f32(src + ((2 * wv + t) * 64 + lane) * 4 + r);
+                    for (int t = 0; t < 2; ++t) {
+                        const float* p4 = src + ((2 * wv + t) * 64 + lane) * 4;
+                        float v0, v1, v2, v3;
+                        ld_agent_f32x2(p4, v0, v1);
+                        ld_agent_f32x2(p4 + 2, v2, v3);
+                        os[u][t] = (f32x4_t){v0, v1, v2, v3};
+                    }
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < 8; ++u) {
                     const bool valid = s0 + u < nsp;
                     const float mu = valid ? ms[u] : NEG_BIG;
                     const float mnew = fmaxf(m, mu);

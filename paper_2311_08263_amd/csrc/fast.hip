@@ -38,11 +38,14 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     p->gu = mk(kd.d, 2 * kd.F);
     p->down = mk(kd.F, kd.d);
     p->lm = mk(kd.d, kd.V);
-    int nb = (kd.S + 31) / 32, sp = (nb + 7) / 8;
-    if (sp > FC_MAX_ATTN_SPLITS) sp = FC_MAX_ATTN_SPLITS;
+    // at most 8 key splits: the last workgroup to arrive folds up to 8 partial results in one round of loads
+    // (measured at 2050 positions, 32 heads: 8 splits 24 us, 12 splits 32 us; at 350 positions 6 splits of 2
+    // key blocks 12.7 us, 3 splits of 4 blocks 14.9 us)
+    int nb = (kd.S + 31) / 32, sp = (nb + 1) / 2;
+    if (sp > 8) sp = 8;
     while (sp > 1 && kd.B * kd.H * sp > 512) --sp;     // measured (batch 8, 40 heads): 1 split 75 us, 2 splits 102 us
     p->attn_splits = sp < 1 ? 1 : sp;
-    p->attn_bpw = 4;     // measured (7B shape, 350 positions): 3-4 key blocks per workgroup, about one per wave
+    p->attn_bpw = 2;
     // column-owner kernel: workgroups per GEMM (one per CU where the matrix allows)
     const int nts[5] = {kd.qkvN / 16, kd.d / 16, 2 * kd.F / 16, kd.d / 16, kd.V / 16};
     // measured on the 7B shape: one workgroup per CU, one weight batch in flight per wave; the O
@@ -196,8 +199,8 @@ hipError_t fc_fast_forward(const FastArgs& a) {
 __global__ void k_set_i32(int32_t* p, int32_t v) { if (threadIdx.x == 0) *p = v; }
 
 static int iso_attn_splits(int S) {
-    int nb = (S + 31) / 32, sp = (nb + 3) / 4;
-    return sp < 1 ? 1 : (sp > FC_MAX_ATTN_SPLITS ? FC_MAX_ATTN_SPLITS : sp);
+    int nb = (S + 31) / 32, sp = (nb + 1) / 2;
+    return sp < 1 ? 1 : (sp > 8 ? 8 : sp);
 }
 // scratch: [0,256) the committed length; [256, 256+4*H) counters; then split partials
 size_t fc_attn_iso_scratch_bytes(int W, int H, int Dh) {
@@ -214,7 +217,7 @@ hipError_t fc_attn_iso(const float* q, const void* kc, const void* vc, int n, in
     AttnArgs at; memset(&at, 0, sizeof(at));
     at.q = q; at.ldq = H * 128; at.kc = (const bf16_t*)kc; at.vc = (const bf16_t*)vc; at.layer = 0; at.B = 1; at.H = H;
     at.Hkv = Hkv; at.S = S; at.W = W; at.kvp = 1; at.n_state = (const int32_t*)sc; at.out = out; at.ldo = H * 128;
-    at.cnt = (int32_t*)(sc + 256); at.bpw = 4;
+    at.cnt = (int32_t*)(sc + 256); at.bpw = 2;
     at.part = (float*)(sc + 256 + (((size_t)H * 4 + 255) & ~(size_t)255));
     return fc_attn16(at, 1, iso_attn_splits(n + W), st);
 }

@@ -22,5 +22,16 @@ __device__ inline void st_agent_i32(int32_t* p, int32_t v) {
 __device__ inline int32_t arrive_agent(int32_t* counter) {
     return __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// 8 bytes per lane with the same agent scope (the widest the compiler's atomics offer; it keeps the wait
+// counts itself, unlike a hand-written 16-byte load, whose destination registers it would feel free to move
+// before the data has arrived)
+__device__ inline void st_agent_f32x2(float* p, float a, float b) {
+    __hip_atomic_store((uint64_t*)p, (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void ld_agent_f32x2(const float* p, float& a, float& b) {
+    const uint64_t v = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    a = __uint_as_float((uint32_t)v); b = __uint_as_float((uint32_t)(v >> 32));
+}
 // all earlier vector-memory operations of this wave (the agent-scope stores above) have completed
 __device__ inline void wait_vmem_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
