@@ -43,7 +43,10 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     // key blocks 12.7 us, 3 splits of 4 blocks 14.9 us)
     int nb = (kd.S + 31) / 32, sp = (nb + 1) / 2;
     if (sp > 8) sp = 8;
-    while (sp > 1 && kd.B * kd.H * sp > 512) --sp;     // measured (batch 8, 40 heads): 1 split 75 us, 2 splits 102 us
+    // and no more workgroups than CUs: the kernel's register budget allows one workgroup per CU, a second
+    // round costs more than the split saves (measured: 64 heads, 600 positions: 4 splits 20.6 us, 8 splits
+    // 24.3 us; batch 8 x 40 heads: 1 split 75 us, 2 splits 102 us)
+    while (sp > 1 && kd.B * kd.H * sp > fc_num_cus()) --sp;
     p->attn_splits = sp < 1 ? 1 : sp;
     p->attn_bpw = 2;
     // column-owner kernel: workgroups per GEMM (one per CU where the matrix allows)

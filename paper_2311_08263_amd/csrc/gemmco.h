@@ -26,4 +26,5 @@ struct GemmCoArgs {
 // 8; fc_gemmco_grid picks one workgroup per CU (all resident, one round) unless the matrix is wider than
 // 8 n-tiles per CU
 int fc_gemmco_grid(int NT, int most = 8);
+int fc_num_cus();      // compute units of the current device
 hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st);

@@ -329,6 +329,8 @@ static int num_cus() {
     return g_cus;
 }
 
+int fc_num_cus() { return num_cus(); }
+
 // grid: one workgroup per CU unless that would give a workgroup more than `most` n-tiles (8 for up
 // to 16 rows, 4 for up to 32 rows: a workgroup finishes at most 8 output tiles)
 int fc_gemmco_grid(int NT, int most) {
