@@ -64,11 +64,17 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     // bytes than weight bytes; K slices per owner cut that (measured at the 7B shape)
     if (kd.F >= 2 * kd.d && kd.F >= 4096 && p->nw[3] % 4 == 0 && p->nw[3] / 4 <= nts[3] && (nts[3] + p->nw[3] / 4 - 1) / (p->nw[3] / 4) <= 8) p->ks[3] = 4;
     p->co_single = 2;    // measured (7B and 70B shapes): down and LM head 2-4 % faster with two batches in flight, QKV and O slower
-    // 17..32 rows (two row tiles): at most 4 n-tiles per workgroup, K slices halved until they fit
+    // 17..32 rows (two row tiles per workgroup, up to 16 output tiles): the same grids where the partial tiles
+    // fit the LDS, K slices halved until they divide the grid
+    const int kin[5] = {kd.d, kd.H * kd.Dh, kd.d, kd.F, kd.d};
+    const bool gained[5] = {true, false, true, false, true};
     for (int i = 0; i < 5; ++i) {
-        const int G2 = fc_gemmco_grid(nts[i], 4);
+        const int most = fc_gemmco_most(32, kin[i], gained[i]);
+        int G2 = p->nw[i];
+        const int own = G2 > 0 ? G2 / p->ks[i] : 0;
+        if (own < 1 || (nts[i] + own - 1) / own > most) G2 = fc_gemmco_grid(nts[i], most);
         int k2 = p->ks[i];
-        while (k2 > 1 && (G2 % k2 || G2 / k2 > nts[i] || (nts[i] + G2 / k2 - 1) / (G2 / k2) > 4)) k2 >>= 1;
+        while (k2 > 1 && (G2 % k2 || G2 / k2 > nts[i] || (nts[i] + G2 / k2 - 1) / (G2 / k2) > most)) k2 >>= 1;
         p->nw2[i] = G2; p->ks2[i] = k2;
     }
 }

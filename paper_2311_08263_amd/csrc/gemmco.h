@@ -16,7 +16,7 @@ struct GemmCoArgs {
     int32_t layer, H, Hkv, B, S, Wn, kvp;
     float* amax_val; int32_t* amax_idx;   // LM head: winners per workgroup [workgroups][16 or 32 rows]
     int32_t ks;            // EPI_RESID only: workgroups per column owner, each taking 1/ks of K (1..8)
-    float* xpart;          // ks > 1: partial tiles [workgroup][8][64 lanes][4]
+    float* xpart;          // ks > 1: partial tiles [workgroup][8 or 16 (more than 8 output tiles)][64 lanes][4]
     int32_t* xcnt;         // ks > 1: one arrival counter per owner, zero between launches
     int32_t rotate;        // walk the K batches in a per-wave rotated order (spreads the streams over the memory channels)
     int32_t single_buffer; // one batch in flight per wave (fewer registers: two workgroups per CU) instead of two
@@ -26,5 +26,8 @@ struct GemmCoArgs {
 // 8; fc_gemmco_grid picks one workgroup per CU (all resident, one round) unless the matrix is wider than
 // 8 n-tiles per CU
 int fc_gemmco_grid(int NT, int most = 8);
+// most n-tiles a workgroup may own so that its partial tiles (8 waves x n-tiles x row tiles x 1 KB) and, with a
+// norm in front, the gain vector (K floats) fit the LDS of a CU
+int fc_gemmco_most(int M, int K, bool gain);
 int fc_num_cus();      // compute units of the current device
 hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st);

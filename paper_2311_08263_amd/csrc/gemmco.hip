@@ -33,8 +33,8 @@ template <int NW, int KB, int MT> struct Batch {
     float4 xa[KB][MT][2];
 };
 
-// NW * MT <= 8 output tiles per workgroup: after the K slices of the eight waves have met in LDS, wave
-// ti finishes tile ti = j * MT + mt (n-tile j of the workgroup, row tile mt).
+// NW * MT <= 16 output tiles per workgroup: after the K slices of the eight waves have met in LDS, wave
+// w finishes tiles ti = w and w + 8, tile ti = j * MT + mt (n-tile j of the workgroup, row tile mt).
 template <int EPI, int NW, int KB, bool DB, int MT>
 __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     extern __shared__ float lds[];
@@ -181,30 +181,42 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     }
     __syncthreads();
 
-    // waves 0..TW-1 finish one tile each: lane holds row mt*16 + lm, columns nt*16 + 4*g4 + r
-    const int tj = w / MT, tm = w % MT;
-    const int nt = nt0 + tj;
-    const bool fin = w < TW && nt < nt1;
-    f32x4_t v = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-    float rs = 1.0f;
-    if (fin) {
-#pragma unroll
-        for (int q = 0; q < 8; ++q) v += lds_part[(q * TW + w) * 64 + lane];
-        if (a.gain) {
-            float s = 0.f;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) s += lds_ss[(q * MT + tm) * 16 + lm];
-            rs = 1.0f / sqrtf(s / (float)a.K + a.eps);
-        }
-        v *= rs;
-    }
+    // wave w finishes tiles w and (with more than 8 tiles) w + 8: lane holds row tm*16 + lm, columns
+    // nt*16 + 4*g4 + r.  MT divides 8, so both tiles of a wave belong to the same row tile tm.
+    constexpr int NF = (TW + 7) / 8;
+    const int tm = w % MT;
     const int m = tm * 16 + lm;
+    int ntf[NF];
+    bool fin[NF];
+    f32x4_t v[NF];
+    float rs = 1.0f;
+    if (a.gain) {
+        float s = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s += lds_ss[(q * MT + tm) * 16 + lm];
+        rs = 1.0f / sqrtf(s / (float)a.K + a.eps);
+    }
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        const int ti = w + 8 * f;
+        ntf[f] = nt0 + ti / MT;
+        fin[f] = ti < TW && ntf[f] < nt1;
+        v[f] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+        if (fin[f]) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[f] += lds_part[(q * TW + ti) * 64 + lane];
+            v[f] *= rs;
+        }
+    }
     if (EPI == EPI_RESID && ks > 1) {
         // partial tiles of the ks slices meet through memory; the last workgroup to arrive adds them
-        float* mine = a.xpart + ((size_t)blockIdx.x * 8 + w) * 256 + lane * 4;
-        if (fin) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) st_agent_f32(mine + r, v[r]);
+        for (int f = 0; f < NF; ++f) {
+            float* mine = a.xpart + ((size_t)blockIdx.x * (8 * NF) + w + 8 * f) * 256 + lane * 4;
+            if (fin[f]) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) st_agent_f32(mine + r, v[f][r]);
+            }
         }
         wait_vmem_done();
         __syncthreads();
@@ -212,40 +224,45 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         if (tid == 0) *flag = arrive_agent(a.xcnt + owner);
         __syncthreads();
         if (*flag != ks - 1) return;
-        if (fin) {
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            if (!fin[f]) continue;
             f32x4_t part[8];
 #pragma unroll
             for (int s2 = 0; s2 < 8; ++s2) {
-                const float* src = a.xpart + ((size_t)(owner * ks + (s2 < ks ? s2 : 0)) * 8 + w) * 256 + lane * 4;
+                const float* src = a.xpart + ((size_t)(owner * ks + (s2 < ks ? s2 : 0)) * (8 * NF) + w + 8 * f) * 256 + lane * 4;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) part[s2][r] = ld_agent_f32(src + r);
             }
-            v = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+            v[f] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s2 = 0; s2 < 8; ++s2) if (s2 < ks) v += part[s2];
+            for (int s2 = 0; s2 < 8; ++s2) if (s2 < ks) v[f] += part[s2];
         }
         if (tid == 0) st_agent_i32(a.xcnt + owner, 0);
     }
-    if (EPI == EPI_RESID) {
-        if (fin && m < a.M) {
-            f32x4_t* o = (f32x4_t*)(a.out + (size_t)m * a.ldo + nt * 16 + 4 * g4);
-            *o = *o + v;
-        }
-    } else if (EPI == EPI_SWIGLU) {
-        // columns 0..7 of a tile: gate of features 8*nt..; columns 8..15: their up values (lane ^ 32)
-        if (fin) {
+    float best = -3.0e38f; int bi = 0x7fffffff;          // LM head: the wave's winner per row over its tiles
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        const int nt = ntf[f];
+        const f32x4_t vv = v[f];
+        if (!fin[f]) continue;
+        if (EPI == EPI_RESID) {
+            if (m < a.M) {
+                f32x4_t* o = (f32x4_t*)(a.out + (size_t)m * a.ldo + nt * 16 + 4 * g4);
+                *o = *o + vv;
+            }
+        } else if (EPI == EPI_SWIGLU) {
+            // columns 0..7 of a tile: gate of features 8*nt..; columns 8..15: their up values (lane ^ 32)
             f32x4_t h;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float other = __shfl_xor(v[r], 32, 64);
-                h[r] = v[r] / (1.0f + expf(-v[r])) * other;
+                const float other = __shfl_xor(vv[r], 32, 64);
+                h[r] = vv[r] / (1.0f + expf(-vv[r])) * other;
             }
             if (g4 < 2 && m < a.M) *(f32x4_t*)(a.out + (size_t)m * a.ldo + nt * 8 + 4 * g4) = h;
-        }
-    } else if (EPI == EPI_QKV) {
-        // q/k heads: tile t of a head holds elements 8t..8t+7 (columns 0..7) and their rotary partners
-        // 64+8t.. (columns 8..15, lane ^ 32); v heads are in natural order
-        if (fin) {
+        } else if (EPI == EPI_QKV) {
+            // q/k heads: tile t of a head holds elements 8t..8t+7 (columns 0..7) and their rotary partners
+            // 64+8t.. (columns 8..15, lane ^ 32); v heads are in natural order
             const int hh = nt >> 3, t = nt & 7;
             const int b = m / a.Wn, j = m % a.Wn;
             const int pos = m < a.M ? a.n_state[b] + j : a.S;
@@ -256,10 +273,10 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
                 f32x4_t r;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float other = __shfl_xor(v[e], 32, 64);
+                    const float other = __shfl_xor(vv[e], 32, 64);
                     const float c = ok ? a.cosT[(size_t)pos * 64 + i0 + e] : 1.0f;
                     const float s = ok ? a.sinT[(size_t)pos * 64 + i0 + e] : 0.0f;
-                    r[e] = g4 < 2 ? v[e] * c - other * s : v[e] * c + other * s;
+                    r[e] = g4 < 2 ? vv[e] * c - other * s : vv[e] * c + other * s;
                 }
                 const int el = (g4 < 2 ? 0 : 64) + i0;          // element index within the head
                 if (ok) {
@@ -283,28 +300,27 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
                 bf16_t* vr = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + v_index(16 * t + 4 * g4, pos, 128);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const uint32_t h0 = rne16(v[e]);
+                    const uint32_t h0 = rne16(vv[e]);
                     vr[e * 8] = (bf16_t)h0;
-                    if (a.kvp == 2) vr[e * 8 + plane] = (bf16_t)rne16(v[e] - up16(h0));
+                    if (a.kvp == 2) vr[e * 8 + plane] = (bf16_t)rne16(vv[e] - up16(h0));
                 }
             }
-        }
-    } else if (EPI == EPI_LMHEAD) {
-        float best = -3.0e38f; int bi = 0x7fffffff;
-        if (fin) {
+        } else if (EPI == EPI_LMHEAD) {
             const int n0 = nt * 16 + 4 * g4;
-            if (a.out && m < a.M) *(f32x4_t*)(a.out + (size_t)m * a.ldo + n0) = v;
+            if (a.out && m < a.M) *(f32x4_t*)(a.out + (size_t)m * a.ldo + n0) = vv;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) if (v[r] > best) { best = v[r]; bi = n0 + r; }
+            for (int r = 0; r < 4; ++r) if (vv[r] > best || (vv[r] == best && n0 + r < bi)) { best = vv[r]; bi = n0 + r; }
+        }
+    }
+    if (EPI == EPI_LMHEAD) {
 #pragma unroll
-            for (int o = 16; o <= 32; o <<= 1) {
-                const float ov = __shfl_xor(best, o, 64); const int oi = __shfl_xor(bi, o, 64);
-                if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
-            }
+        for (int o = 16; o <= 32; o <<= 1) {
+            const float ov = __shfl_xor(best, o, 64); const int oi = __shfl_xor(bi, o, 64);
+            if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
         }
         if (g4 == 0) { lds_amv[w * 16 + lm] = best; lds_ami[w * 16 + lm] = bi; }
         __syncthreads();
-        if (tid < 16 * MT) {                 // row tid: the waves whose tile is row tile tid / 16
+        if (tid < 16 * MT) {                 // row tid: the waves whose tiles are row tile tid / 16
             const int rt = tid >> 4, r16 = tid & 15;
             float bv = -3.0e38f; int bx = 0x7fffffff;
 #pragma unroll
@@ -331,8 +347,8 @@ static int num_cus() {
 
 int fc_num_cus() { return num_cus(); }
 
-// grid: one workgroup per CU unless that would give a workgroup more than `most` n-tiles (8 for up
-// to 16 rows, 4 for up to 32 rows: a workgroup finishes at most 8 output tiles)
+// grid: one workgroup per CU unless that would give a workgroup more than `most` n-tiles (at most 8: with two
+// row tiles a workgroup then finishes 16 output tiles, whose partial sums take 128 KB of LDS)
 int fc_gemmco_grid(int NT, int most) {
     int G = num_cus();
     if (G > NT) G = NT;
@@ -340,9 +356,19 @@ int fc_gemmco_grid(int NT, int most) {
     return G;
 }
 
+static size_t co_lds_bytes(int nw, int mt, int K, bool gain) {
+    return (size_t)8 * nw * mt * 1024 + (size_t)(8 * mt * 16 + 2 * 8 * 16) * 4 + (gain ? (size_t)K * 4 : 0) + 64;
+}
+
+int fc_gemmco_most(int M, int K, bool gain) {
+    int most = 8;
+    while (most > 1 && co_lds_bytes(most, M > 16 ? 2 : 1, K, gain) > 150 * 1024) --most;
+    return most;
+}
+
 template <int EPI, int NW, int KB, bool DB, int MT>
 static hipError_t launch_k(const GemmCoArgs& a, int G, hipStream_t st) {
-    const size_t lds = (size_t)8 * NW * MT * 1024 + (size_t)(8 * MT * 16 + 2 * 8 * 16) * 4 + (a.gain ? (size_t)a.K * 4 : 0) + 64;
+    const size_t lds = co_lds_bytes(NW, MT, a.K, a.gain != nullptr);
     static bool raised = false;
     if (!raised) {
         hipError_t e = hipFuncSetAttribute((const void*)k_gemmco<EPI, NW, KB, DB, MT>, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
@@ -357,12 +383,14 @@ template <int EPI>
 static hipError_t launch_epi(const GemmCoArgs& a, int G, hipStream_t st) {
     const int owners = G / (a.ks > 1 ? a.ks : 1);
     const int nw = (a.NT + owners - 1) / owners;  // most n-tiles any workgroup owns
-    if (a.M > 16) {                               // two row tiles: at most 4 n-tiles per workgroup
+    if (a.M > 16) {                               // two row tiles
         switch (nw) {
             case 1: return launch_k<EPI, 1, 4, false, 2>(a, G, st);
             case 2: return launch_k<EPI, 2, 4, false, 2>(a, G, st);
             case 3: return launch_k<EPI, 3, 2, false, 2>(a, G, st);
             case 4: return launch_k<EPI, 4, 2, false, 2>(a, G, st);
+            case 5: case 6: return launch_k<EPI, 6, 2, false, 2>(a, G, st);
+            case 7: case 8: return launch_k<EPI, 8, 2, false, 2>(a, G, st);
         }
         return hipErrorInvalidValue;
     }
@@ -389,7 +417,7 @@ static hipError_t launch_epi(const GemmCoArgs& a, int G, hipStream_t st) {
 }
 
 hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st) {
-    const int ks = a.ks > 1 ? a.ks : 1, most = a.M > 16 ? 4 : 8;
+    const int ks = a.ks > 1 ? a.ks : 1, most = 8;
     if (a.M < 1 || a.M > 32 || a.K % 256 || a.NT < 1 || G < 1 || ks > 8 || G % ks || G / ks > a.NT ||
         (a.NT + G / ks - 1) / (G / ks) > most || a.K / 256 < ks)
         return hipErrorInvalidValue;
