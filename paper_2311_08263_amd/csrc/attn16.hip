@@ -23,17 +23,12 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 union Frag { u32x4_t u; bf16x8_t v; };
 
-__device__ inline uint32_t rne16(float f) {
-    uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-__device__ inline float up16(uint32_t b) { return __uint_as_float(b << 16); }
 __device__ inline void split8(const float* v, Frag& hi, Frag& lo) {
-    uint32_t h[8], l[8];
+    uint32_t h[4], l[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { h[e] = rne16(v[e]); l[e] = rne16(v[e] - up16(h[e])); }
-    hi.u = (u32x4_t){h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
-    lo.u = (u32x4_t){l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+    for (int e = 0; e < 4; ++e) pk_bf16_hilo(v[2 * e], v[2 * e + 1], h[e], l[e]);
+    hi.u = (u32x4_t){h[0], h[1], h[2], h[3]};
+    lo.u = (u32x4_t){l[0], l[1], l[2], l[3]};
 }
 
 #define NEG_BIG (-1.0e30f)

@@ -17,6 +17,21 @@ __host__ __device__ inline bf16_t f32_to_bf16(float f) {  // round to nearest ev
     return (bf16_t)(v.u >> 16);
 }
 
+#if defined(__HIPCC__)
+// Two floats -> one word of two bf16 (a in the low half), round to nearest even: one v_cvt_pk_bf16_f32.
+__device__ inline uint32_t pk_bf16(float a, float b) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+// hi + lo split of a pair: hi = bf16(a), bf16(b); lo = bf16 of what the hi parts leave over
+__device__ inline void pk_bf16_hilo(float a, float b, uint32_t& hi, uint32_t& lo) {
+    hi = pk_bf16(a, b);
+    lo = pk_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
+}
+#endif
+
 // ------------------------------------------------------------------ packed weights
 // A fused matrix has K rows (inputs) and NP columns (outputs, padded to a multiple of 16).
 // fp32 models keep it row-major [K][NP].  bf16 models keep it in MFMA fragment order: the

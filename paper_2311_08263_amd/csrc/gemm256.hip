@@ -76,11 +76,11 @@ __global__ __launch_bounds__(512) void k_split(const float* X, int ldx, int M, i
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = v[e] * scale * g[e];
         }
-        uint32_t h[8], l[8];
+        uint32_t h[4], l[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { h[e] = rne16(v[e]); l[e] = rne16(v[e] - up16(h[e])); }
-        dst[(size_t)kt * 128] = (u32x4_t){h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
-        dst[(size_t)kt * 128 + 64] = (u32x4_t){l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+        for (int e = 0; e < 4; ++e) pk_bf16_hilo(v[2 * e], v[2 * e + 1], h[e], l[e]);
+        dst[(size_t)kt * 128] = (u32x4_t){h[0], h[1], h[2], h[3]};
+        dst[(size_t)kt * 128 + 64] = (u32x4_t){l[0], l[1], l[2], l[3]};
     }
 }
 

@@ -121,11 +121,11 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { v[e] *= keep; ss[mt] += v[e] * v[e]; }
                 if (a.gain) { v[0] *= g0.x; v[1] *= g0.y; v[2] *= g0.z; v[3] *= g0.w; v[4] *= g1.x; v[5] *= g1.y; v[6] *= g1.z; v[7] *= g1.w; }
-                uint32_t h[8], l[8];
+                uint32_t h[4], l[4];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) { h[e] = rne16(v[e]); l[e] = rne16(v[e] - up16(h[e])); }
-                hi[mt].u = (u32x4_t){h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
-                lo[mt].u = (u32x4_t){l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+                for (int e = 0; e < 4; ++e) pk_bf16_hilo(v[2 * e], v[2 * e + 1], h[e], l[e]);
+                hi[mt].u = (u32x4_t){h[0], h[1], h[2], h[3]};
+                lo[mt].u = (u32x4_t){l[0], l[1], l[2], l[3]};
             }
 #pragma unroll
             for (int j = 0; j < NW; ++j) {
