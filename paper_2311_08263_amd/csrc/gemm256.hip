@@ -8,12 +8,13 @@
 // straight from global memory, 4 k-tiles ahead) feeds 8.  Activation fragments of 4 k-tiles at a
 // time are copied global -> LDS by the whole workgroup, double buffered (2 x 32 KB), one barrier per
 // stage.  The four workgroups of a column block re-read the same weights: HBM sees them once, the
-// repeats come from L2.  What bounds the kernel at 256 rows is latency (measured: MFMA busy 38 %, no bank
-// conflicts, 2.6 % of wave time waiting on LDS instructions, 54 % on any instruction): weights and the next
-// stage's activations are requested about 1.7 us before their use, less than an L2 round trip under this load.
-// Two variants that halved a bandwidth instead were slower: 128-row tiles with both operands staged through
-// LDS (half the L2 -> CU traffic; gate/up 170 us against 156 us) and 8 x 2 tiles per wave (half the LDS bytes
-// per MFMA, weights only two k-tiles ahead; 182 us).  Workgroup ids are mapped so that the row blocks of one column block run on
+// repeats come from L2.  What bounds the kernel at 256 rows (measured with per-workgroup time stamps at the
+// 13B gate/up shape): MFMA issue at 21-23 cycles per MFMA instead of 16 plus the L2 -> CU load path (96 KB per
+// workgroup and stage; with most loads removed the loop is a quarter faster).  A workgroup alone on a CU runs
+// its 40 stages in 70 us, two on a CU finish after 86 and 118 us (the arbiter favours the older waves).  Not the
+// bound: LDS read latency (software-pipelined reads changed nothing), MFMA busy is 38 %, no bank conflicts.
+// Variants that were slower: 128-row tiles with both operands staged through LDS (gate/up 170 us against
+// 156 us) and 8 x 2 tiles per wave (182 us).  Workgroup ids are mapped so that the row blocks of one column block run on
 // the same XCD (ids that are equal mod 8 share an XCD and its L2), back to back.  Matrices with few
 // columns (O and down projections) are also split along K so that the launch fills the chip; the
 // slices store partial tiles and k_resid_reduce adds them to the residual stream in slice order.
