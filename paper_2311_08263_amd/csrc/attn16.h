@@ -9,8 +9,10 @@ struct AttnArgs {
     const bf16_t* vc;      // V cache, transposed [L][B][Hkv][planes][128][S]
     int32_t layer, B, H, Hkv, S, W, kvp;
     const int32_t* n_state;   // committed length per sequence
-    float* out;            // [rows][ldo], head h at column h*128
+    float* out;            // [rows][ldo], head h at column h*128 (may be NULL when ofrag is given)
     int32_t ldo;
+    bf16_t* ofrag;         // not NULL: the output also as bf16 hi + lo B-fragments [row tile][H*128/32][hi|lo][64][8],
+                           // the layout the many-row O projection reads
     float* part;           // split partials
     int32_t* cnt;          // one arrival counter per (sequence, head), zero between launches
     int32_t bpw;           // key blocks (of 32) per workgroup that decide how many of the launched splits are used

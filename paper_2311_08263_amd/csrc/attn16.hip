@@ -297,9 +297,26 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
         const int j = qt * 16 + lm;
         if (j < Wr) {
             const float inv = 1.0f / lw[qt];
-            float* o = a.out + (size_t)(b * a.W + row0 + j) * a.ldo + h * 128 + 4 * g;
+            const int row = b * a.W + row0 + j;
+            if (a.out) {
+                float* o = a.out + (size_t)row * a.ldo + h * 128 + 4 * g;
 #pragma unroll
-            for (int t = 0; t < 2; ++t) *(f32x4_t*)(o + 16 * (2 * wv + t)) = o2[qt][t] * inv;
+                for (int t = 0; t < 2; ++t) *(f32x4_t*)(o + 16 * (2 * wv + t)) = o2[qt][t] * inv;
+            }
+            if (a.ofrag) {
+                // head elements 32 * wv + 16 * t + 4 * g + r: k-tile 4 * h + wv, octet 2 * t + g / 2, elements 4 * (g % 2) + r
+                const size_t KTo = (size_t)a.H * 4;
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const f32x4_t v = o2[qt][t] * inv;
+                    uint32_t h0, l0, h1, l1;
+                    pk_bf16_hilo(v[0], v[1], h0, l0);
+                    pk_bf16_hilo(v[2], v[3], h1, l1);
+                    char* dst = (char*)a.ofrag + ((((size_t)(row >> 4) * KTo + 4 * h + wv) * 2) * 64 + (row & 15) + 16 * (2 * t + (g >> 1))) * 16 + 8 * (g & 1);
+                    *(uint2*)dst = make_uint2(h0, h1);
+                    *(uint2*)(dst + 1024) = make_uint2(l0, l1);
+                }
+            }
         }
     }
 }

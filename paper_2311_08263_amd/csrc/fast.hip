@@ -79,6 +79,21 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     }
 }
 
+// Layout of the many-row (more than 32 rows) part of the GEMM scratch, offsets in bytes
+struct ManyRowScratch { size_t af_x, af_att, af_h, ssq, part, end; };
+static ManyRowScratch many_row_scratch(const KernelDims& kd) {
+    auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    ManyRowScratch m;
+    const size_t MP = (size_t)((kd.M + 15) / 16) * 16;
+    m.af_x = 0;
+    m.af_att = m.af_x + up(fc_split_bytes(kd.M, kd.d));
+    m.af_h = m.af_att + up(fc_split_bytes(kd.M, kd.H * kd.Dh));
+    m.ssq = m.af_h + up(fc_split_bytes(kd.M, kd.F));
+    m.part = m.ssq + up((size_t)(kd.d / 256 + 1) * MP * 4);
+    m.end = m.part + (size_t)FC_GEMM256_MAX_SK * kd.M * kd.d * 4;
+    return m;
+}
+
 void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t* attn_part_bytes) {
     // partial tiles: (column groups x slices) x 8 waves x 2 row tiles x 1 KB, sized for the widest matrix
     int nmax = 2 * kd.F;
@@ -87,10 +102,8 @@ void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t
     const size_t ncg = (size_t)(nmax / 16 + 7) / 8;
     *gemm_part_bytes = ncg * FC_MAX_SK * (8 * 2 * 1024 + 2 * 16 * 4) + 4096;
     if (*gemm_part_bytes < fc_persist_part_bytes(kd)) *gemm_part_bytes = fc_persist_part_bytes(kd);
-    // many-row path: the split activations of one GEMM (widest input) live in the same scratch
-    int kmax = kd.F > kd.d ? kd.F : kd.d;
-    if (kd.H * kd.Dh > kmax) kmax = kd.H * kd.Dh;
-    const size_t big = fc_split_bytes(kd.M, kmax) + (size_t)FC_GEMM256_MAX_SK * kd.M * kd.d * 4 + 4096;
+    // many-row path: activation fragments, row statistics and split-K partial tiles live in the same scratch
+    const size_t big = many_row_scratch(kd).end + 4096;
     if (*gemm_part_bytes < big) *gemm_part_bytes = big;
     *attn_part_bytes = fc_attn16_part_bytes(kd.B * kd.H, FC_MAX_ATTN_SPLITS, kd.Wcap > kd.W ? kd.Wcap : kd.W) + 4096;
 }
@@ -130,7 +143,17 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     big.M = M; big.n_state = g.n_state; big.cosT = g.cosT; big.sinT = g.sinT; big.kc = g.kc; big.vc = g.vc;
     big.H = kd.H; big.Hkv = kd.Hkv; big.B = kd.B; big.S = kd.S; big.Wn = kd.W; big.kvp = kd.kvp;
     big.amax_stride = (M + 15) / 16 * 16;
-    big.part = (float*)(ws + wm.gemm_part + ((fc_split_bytes(kd.M, kd.F > qd ? (kd.F > d ? kd.F : d) : (qd > d ? qd : d)) + 255) & ~(size_t)255));
+    // many-row scratch: the fragments of x, of the attention output and of the hidden activations, the partial
+    // row sums of squares of x, then the split-K partial tiles
+    const ManyRowScratch mrs = many_row_scratch(kd);
+    bf16_t* af_x = (bf16_t*)(ws + wm.gemm_part + mrs.af_x); bf16_t* af_att = (bf16_t*)(ws + wm.gemm_part + mrs.af_att);
+    bf16_t* af_h = (bf16_t*)(ws + wm.gemm_part + mrs.af_h); float* ssq = (float*)(ws + wm.gemm_part + mrs.ssq);
+    big.part = (float*)(ws + wm.gemm_part + mrs.part);
+    big.eps = kd.eps;
+    // which fragment buffers hold what their fp32 twin would: x (with the gain of the norm that comes next, row
+    // scale still to be applied by the consumer), attention output, hidden activations
+    bool x_frag = false, att_frag = false, h_frag = false;
+    const float* next_gain = nullptr;          // gain the next reduction folds into the fragments of x
     // LM head: one winner per row and column block (16 n-tiles, or 4 with the narrow tiles)
     const int lm_ncb = fc_gemm256_narrow(EPI_LMHEAD, M, kd.V / 16) ? (kd.V / 16 + 3) / 4 : (kd.V / 16 + 15) / 16;
     big.amax_val = g.amax_val; big.amax_idx = (int32_t*)(g.amax_val + (size_t)lm_ncb * big.amax_stride);
@@ -150,11 +173,26 @@ hipError_t fc_fast_forward(const FastArgs& a) {
             return fc_gemmco(epi, co, nw, a.st);
         }
         if (M > 32) {        // matrix-core bound: activations split once, tiles of 64 rows x 256 columns
-            bf16_t* af = (bf16_t*)(ws + wm.gemm_part);
-            hipError_t e = fc_split(X, ldx, M, K, gain, kd.eps, af, a.st);
-            if (e != hipSuccess) return e;
+            // the input: fragments a producer has already written (x after a fused reduction, attention output,
+            // hidden activations), else split here (RMSNorm included)
+            bf16_t* af = X == x ? af_x : (X == att ? af_att : af_h);
+            const bool ready = X == x ? x_frag : (X == att ? att_frag : h_frag);
+            big.ssq = nullptr; big.nssq = 0;
+            if (!ready) {
+                hipError_t e = fc_split(X, ldx, M, K, gain, kd.eps, af, a.st);
+                if (e != hipSuccess) return e;
+            } else if (X == x) { big.ssq = ssq; big.nssq = d / 256; }
             big.sk = epi == EPI_RESID ? fc_gemm256_sk(M, K, N / 16) : 1;
             big.W = (const bf16_t*)W; big.K = K; big.NT = N / 16; big.AF = af; big.out = out; big.ldo = ldo; big.layer = g.layer;
+            big.hfrag = nullptr; big.rf_AF = nullptr; big.rf_gain = nullptr; big.rf_ssq = nullptr;
+            if (epi == EPI_SWIGLU) {            // the hidden activations leave as fragments (fp32 copy only for debugging)
+                big.hfrag = af_h; h_frag = true;
+                if (a.dbg_stop < 0) big.out = nullptr;
+            }
+            if (epi == EPI_RESID) {
+                x_frag = big.sk > 1 && d % 256 == 0 && next_gain != nullptr;
+                if (x_frag) { big.rf_AF = af_x; big.rf_gain = next_gain; big.rf_ssq = ssq; }
+            }
             return fc_gemm256(epi, big, a.st);
         }
         // split-K kernel, at most 32 rows
@@ -175,15 +213,21 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         gi = 0;
         FLAUNCH(KK_QKV, gemm(EPI_QKV, a.plan->qkv, lb + mm.qkv.off, d, kd.qkvN, x, d, (const float*)(lb + mm.g1_off), q, qd));
         DBG_STOP();
+        if (M > 32) {                  // the many-row O projection reads fragments: attention writes them itself
+            at.ofrag = af_att; att_frag = true;
+            at.out = a.dbg_stop >= 0 ? att : nullptr;
+        }
         FLAUNCH(KK_ATTN, fc_attn16(at, a.Bact, a.plan->attn_splits, a.st));
         DBG_STOP();
         gi = 1;
+        next_gain = (const float*)(lb + mm.g2_off);
         FLAUNCH(KK_O, gemm(EPI_RESID, a.plan->o, lb + mm.o.off, qd, d, att, qd, nullptr, x, d));
         DBG_STOP();
         gi = 2;
         FLAUNCH(KK_GU, gemm(EPI_SWIGLU, a.plan->gu, lb + mm.gu.off, d, 2 * kd.F, x, d, (const float*)(lb + mm.g2_off), h, kd.F));
         DBG_STOP();
         gi = 3;
+        next_gain = l + 1 < kd.L ? (const float*)(wt + mm.layers_off + (size_t)(l + 1) * mm.layer_stride + mm.g1_off) : (const float*)(wt + mm.gf_off);
         FLAUNCH(KK_DOWN, gemm(EPI_RESID, a.plan->down, lb + mm.down.off, kd.F, d, h, kd.F, nullptr, x, d));
     }
     if (a.dbg_stop >= 0 && nstage >= a.dbg_stop) return hipSuccess;

@@ -17,6 +17,16 @@ struct Gemm256Args {
     int32_t sk;            // K slices (RESID only when > 1: partial tiles to `part`, then added in slice order)
     float* part;           // [sk][M][NT*16] fp32
     int32_t cw;            // n-tiles per wave: 0 = chosen from the shape, 1 or 4 = forced
+    // Activations that arrive without their RMSNorm row scale (fragments written by fc_gemm256's own reduction,
+    // see rf_AF): ssq [nssq][row tiles * 16] partial row sums of squares; the epilogue multiplies row m by
+    // 1 / sqrt(sum_c ssq[c][m] / K + eps) before anything else.  NULL = the fragments are final.
+    const float* ssq; int32_t nssq; float eps;
+    // SWIGLU: also (or, with out == NULL, only) write the hidden activations as hi + lo fragments for the
+    // down projection, [row tile][F / 32][hi|lo][64][8]
+    bf16_t* hfrag;
+    // RESID with sk > 1: the reduction also writes the new residual rows times rf_gain (the next norm's gain)
+    // as hi + lo fragments to rf_AF and their partial sums of squares to rf_ssq [N / 256][row tiles * 16]
+    bf16_t* rf_AF; const float* rf_gain; float* rf_ssq;
 };
 #define FC_GEMM256_MAX_SK 8
 bool fc_gemm256_narrow(int epi, int M, int NT);     // true: 64 x 64 tiles (few rows x few columns), else 64 x 256

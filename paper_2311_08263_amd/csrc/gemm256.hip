@@ -101,6 +101,7 @@ hipError_t fc_split(const float* X, int ldx, int M, int K, const float* gain, fl
 template <int EPI, int CW>
 __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
     __shared__ u32x4_t stage[2][4][4][2][64];           // [buffer][k-tile][row tile][hi|lo][lane]: 2 x 32 KB
+    __shared__ float rowscale[64];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int lm = lane & 15, g4 = lane >> 4;
     const int KT = a.K >> 5, NS = KT >> 2, MT = (a.M + 15) >> 4;
@@ -152,6 +153,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
     stage_load(sr, s_lo);
     wload(W0, 4 * s_lo); wload(W1, 4 * s_lo + 1); wload(W2, 4 * s_lo + 2); wload(W3, 4 * s_lo + 3);
     stage_store(sr, 0);
+    if (a.ssq && tid < 64) {                              // row scales of the 64 rows (activations without their norm scale)
+        const int MP = MT * 16;
+        const int row = mt0 * 16 + tid < MP ? mt0 * 16 + tid : MP - 1;
+        float ssum = 0.f;
+        for (int c = 0; c < a.nssq; ++c) ssum += a.ssq[(size_t)c * MP + row];
+        rowscale[tid] = 1.0f / sqrtf(ssum / (float)a.K + a.eps);
+    }
     __syncthreads();
 
 #define STEP(WSET, U)                                                                               \
@@ -195,7 +203,8 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
         for (int j = 0; j < CW; ++j) {
             const int nt = nt0 + j;
             const bool ok = rok && nt < a.NT;
-            const f32x4_t v = acc[j][m];
+            f32x4_t v = acc[j][m];
+            if (EPI != EPI_RESID && a.ssq) v *= rowscale[m * 16 + lm];
             if (EPI == EPI_RESID) {
                 if (ok) {
                     if (a.sk > 1) *(f32x4_t*)(a.part + ((size_t)ks * a.M + row) * (a.NT * 16) + nt * 16 + 4 * g4) = v;
@@ -211,7 +220,19 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
                     const float other = __shfl_xor(v[r], 32, 64);
                     h[r] = v[r] / (1.0f + expf(-v[r])) * other;
                 }
-                if (ok && g4 < 2) *(f32x4_t*)(a.out + (size_t)row * a.ldo + nt * 8 + 4 * g4) = h;
+                if (ok && g4 < 2) {
+                    if (a.out) *(f32x4_t*)(a.out + (size_t)row * a.ldo + nt * 8 + 4 * g4) = h;
+                    if (a.hfrag) {
+                        // features 8 * nt + 4 * g4 + r of row `row`: k-tile nt / 4, octet nt % 4, elements 4 * g4 + r
+                        uint32_t h0, l0, h1, l1;
+                        pk_bf16_hilo(h[0], h[1], h0, l0);
+                        pk_bf16_hilo(h[2], h[3], h1, l1);
+                        const size_t KTh = (size_t)(a.ldo >> 5);
+                        char* dst = (char*)a.hfrag + ((((size_t)(mt0 + m) * KTh + (nt >> 2)) * 2) * 64 + lm + 16 * (nt & 3)) * 16 + 8 * g4;
+                        *(uint2*)dst = make_uint2(h0, h1);
+                        *(uint2*)(dst + 1024) = make_uint2(l0, l1);
+                    }
+                }
             } else if (EPI == EPI_QKV) {
                 const int hh = nt >> 3, t = nt & 7;
                 const int b = rok ? row / a.Wn : 0, jj = rok ? row % a.Wn : 0;
@@ -304,6 +325,51 @@ __global__ __launch_bounds__(256) void k_resid_reduce(const float* part, int sk,
     *o = *o + s;
 }
 
+// The same sum, and in the same pass the input of the next GEMM: the new residual rows times the next norm's
+// gain as bf16 hi + lo B-fragments, plus partial row sums of squares (the consumer applies the norm's row scale
+// in its epilogue).  grid (row tiles, N / 256); wave w of a workgroup converts k-tile 8 * blockIdx.y + w; lane
+// (row lm, octet g4) as in the fragment.  Rows past M of the last row tile are not written.
+__global__ __launch_bounds__(512) void k_resid_reduce_split(const float* part, int sk, int M, int N, float* out, int ldo,
+                                                            const float* gain, bf16_t* AF, float* ssq) {
+    __shared__ float red[8][16];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int lm = lane & 15, g4 = lane >> 4;
+    const int mt = blockIdx.x, KT = N >> 5, kt = blockIdx.y * 8 + w, MP = gridDim.x * 16;
+    const int m = mt * 16 + lm, c = kt * 32 + 8 * g4;
+    float ss = 0.f;
+    if (m < M) {
+        f32x4_t s0 = *(const f32x4_t*)(part + (size_t)m * N + c), s1 = *(const f32x4_t*)(part + (size_t)m * N + c + 4);
+        for (int k = 1; k < sk; ++k) {
+            s0 = s0 + *(const f32x4_t*)(part + ((size_t)k * M + m) * N + c);
+            s1 = s1 + *(const f32x4_t*)(part + ((size_t)k * M + m) * N + c + 4);
+        }
+        f32x4_t* o = (f32x4_t*)(out + (size_t)m * ldo + c);
+        const f32x4_t x0 = o[0] + s0, x1 = o[1] + s1;
+        o[0] = x0; o[1] = x1;
+        const f32x4_t g0 = *(const f32x4_t*)(gain + c), g1 = *(const f32x4_t*)(gain + c + 4);
+        uint32_t h[4], l[4];
+        pk_bf16_hilo(x0[0] * g0[0], x0[1] * g0[1], h[0], l[0]);
+        pk_bf16_hilo(x0[2] * g0[2], x0[3] * g0[3], h[1], l[1]);
+        pk_bf16_hilo(x1[0] * g1[0], x1[1] * g1[1], h[2], l[2]);
+        pk_bf16_hilo(x1[2] * g1[2], x1[3] * g1[3], h[3], l[3]);
+        u32x4_t* dst = (u32x4_t*)AF + (((size_t)mt * KT + kt) * 2) * 64 + lane;
+        dst[0] = (u32x4_t){h[0], h[1], h[2], h[3]};
+        dst[64] = (u32x4_t){l[0], l[1], l[2], l[3]};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ss += x0[e] * x0[e] + x1[e] * x1[e];
+    }
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (g4 == 0) red[w][lm] = ss;
+    __syncthreads();
+    if (tid < 16) {
+        float t = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) t += red[q][tid];
+        ssq[(size_t)blockIdx.y * MP + mt * 16 + tid] = t;
+    }
+}
+
 // narrow tiles where the wide ones would give fewer than 200 workgroups and K cannot be split instead
 // (the residual GEMMs fill the chip with K slices, which keeps the reuse of the wide tile)
 bool fc_gemm256_narrow(int epi, int M, int NT) {
@@ -343,7 +409,12 @@ hipError_t fc_gemm256(int epi, const Gemm256Args& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     if (a.sk > 1) {
         const size_t n = (size_t)a.M * (a.NT * 4);
-        k_resid_reduce<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a.part, a.sk, a.M, a.NT * 16, a.out, a.ldo);
+        if (a.rf_AF) {
+            if ((a.NT * 16) % 256 || !a.rf_gain || !a.rf_ssq) return hipErrorInvalidValue;
+            k_resid_reduce_split<<<dim3((a.M + 15) / 16, a.NT * 16 / 256), 512, 0, st>>>(a.part, a.sk, a.M, a.NT * 16, a.out, a.ldo,
+                                                                                       a.rf_gain, a.rf_AF, a.rf_ssq);
+        } else
+            k_resid_reduce<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a.part, a.sk, a.M, a.NT * 16, a.out, a.ldo);
     }
     return hipGetLastError();
 }
