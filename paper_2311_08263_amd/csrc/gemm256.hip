@@ -101,7 +101,7 @@ hipError_t fc_split(const float* X, int ldx, int M, int K, const float* gain, fl
 template <int EPI, int CW>
 __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
     __shared__ u32x4_t stage[2][4][4][2][64];           // [buffer][k-tile][row tile][hi|lo][lane]: 2 x 32 KB
-    __shared__ float rowscale[64];
+    __shared__ float rowpart[4][64];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int lm = lane & 15, g4 = lane >> 4;
     const int KT = a.K >> 5, NS = KT >> 2, MT = (a.M + 15) >> 4;
@@ -153,12 +153,15 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
     stage_load(sr, s_lo);
     wload(W0, 4 * s_lo); wload(W1, 4 * s_lo + 1); wload(W2, 4 * s_lo + 2); wload(W3, 4 * s_lo + 3);
     stage_store(sr, 0);
-    if (a.ssq && tid < 64) {                              // row scales of the 64 rows (activations without their norm scale)
+    if (a.ssq) {
+        // row statistics of the 64 rows (activations that come without their norm scale): wave w adds every
+        // fourth partial sum, all its loads in flight together; the epilogue adds the four
         const int MP = MT * 16;
-        const int row = mt0 * 16 + tid < MP ? mt0 * 16 + tid : MP - 1;
+        const int row = mt0 * 16 + lane < MP ? mt0 * 16 + lane : MP - 1;
         float ssum = 0.f;
-        for (int c = 0; c < a.nssq; ++c) ssum += a.ssq[(size_t)c * MP + row];
-        rowscale[tid] = 1.0f / sqrtf(ssum / (float)a.K + a.eps);
+#pragma unroll 8
+        for (int c = w; c < a.nssq; c += 4) ssum += a.ssq[(size_t)c * MP + row];
+        rowpart[w][lane] = ssum;
     }
     __syncthreads();
 
@@ -193,8 +196,16 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
 
     // ---- epilogue: acc[j][m]: rows (mt0 + m) * 16 + lm, columns (nt0 + j) * 16 + 4 * g4 + r
     float best[4]; int bidx[4];
+    float rscale[4];
 #pragma unroll
-    for (int m = 0; m < 4; ++m) { best[m] = -3.0e38f; bidx[m] = 0x7fffffff; }
+    for (int m = 0; m < 4; ++m) {
+        best[m] = -3.0e38f; bidx[m] = 0x7fffffff;
+        rscale[m] = 1.0f;
+        if (EPI != EPI_RESID && a.ssq) {
+            const int r = m * 16 + lm;
+            rscale[m] = 1.0f / sqrtf((rowpart[0][r] + rowpart[1][r] + rowpart[2][r] + rowpart[3][r]) / (float)a.K + a.eps);
+        }
+    }
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         const int row = (mt0 + m) * 16 + lm;
@@ -204,7 +215,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
             const int nt = nt0 + j;
             const bool ok = rok && nt < a.NT;
             f32x4_t v = acc[j][m];
-            if (EPI != EPI_RESID && a.ssq) v *= rowscale[m * 16 + lm];
+            if (EPI != EPI_RESID && a.ssq) v *= rscale[m];
             if (EPI == EPI_RESID) {
                 if (ok) {
                     if (a.sk > 1) *(f32x4_t*)(a.part + ((size_t)ks * a.M + row) * (a.NT * 16) + nt * 16 + 4 * g4) = v;
