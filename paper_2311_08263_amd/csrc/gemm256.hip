@@ -113,18 +113,23 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
     const int s_lo = (int)((unsigned)NS * (unsigned)ks / (unsigned)a.sk), s_hi = (int)((unsigned)NS * (unsigned)(ks + 1) / (unsigned)a.sk);
     const int nt0 = cb * (4 * CW) + CW * w;              // this wave's CW n-tiles
     const int mt0 = rb * 4;
-    const u32x4_t* AFp = (const u32x4_t*)a.AF;
-    const u32x4_t* Wp = (const u32x4_t*)a.W + lane;
 
-    // stage copy: 32 fragments of 1 KB per stage, 8 x 16 bytes per thread
-    auto stage_load = [&](u32x4_t (&r)[8], int s) {
+    // stage copy: 32 fragments of 1 KB per stage, 8 x 16 bytes per thread.  Addresses are a uniform 64-bit base
+    // (scalar registers, advanced per stage) plus a per-thread 32-bit byte offset fixed for the whole kernel:
+    // no 64-bit vector arithmetic in the loop.
+    const char* AFb = (const char*)a.AF;
+    uint32_t aoff[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int idx = tid + 256 * i, f = idx >> 6, ln = idx & 63;
-            const int ktl = f >> 3, mtl = (f >> 1) & 3, part = f & 1;
-            const int mt = mt0 + mtl < MT ? mt0 + mtl : MT - 1;
-            r[i] = AFp[(((size_t)mt * KT + 4 * s + ktl) * 2 + part) * 64 + ln];
-        }
+    for (int i = 0; i < 8; ++i) {
+        const int idx = tid + 256 * i, f = idx >> 6, ln = idx & 63;
+        const int ktl = f >> 3, mtl = (f >> 1) & 3, part = f & 1;
+        const int mt = mt0 + mtl < MT ? mt0 + mtl : MT - 1;
+        aoff[i] = ((((uint32_t)mt * KT + ktl) * 2 + part) * 64 + ln) * 16;
+    }
+    auto stage_load = [&](u32x4_t (&r)[8], int s) {
+        const char* base = AFb + (size_t)s * 8192;            // 4 k-tiles x (hi, lo) x 1 KB
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = *(const u32x4_t*)(base + aoff[i]);
     };
     auto stage_store = [&](const u32x4_t (&r)[8], int buf) {
 #pragma unroll
@@ -133,13 +138,18 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
             stage[buf][f >> 3][(f >> 1) & 3][f & 1][ln] = r[i];
         }
     };
+    const char* Wb = (const char*)a.W;
+    uint32_t woff[CW];
+#pragma unroll
+    for (int j = 0; j < CW; ++j) {
+        const int nt = nt0 + j < a.NT ? nt0 + j : a.NT - 1;
+        woff[j] = ((uint32_t)nt * KT * 64 + lane) * 16;
+    }
     auto wload = [&](u32x4_t (&wt)[CW], int kt) {
         const int kc = kt < KT ? kt : KT - 1;                 // past the end: re-read the last k-tile (never used)
+        const char* base = Wb + (size_t)kc * 1024;
 #pragma unroll
-        for (int j = 0; j < CW; ++j) {
-            const int nt = nt0 + j < a.NT ? nt0 + j : a.NT - 1;
-            wt[j] = Wp[((size_t)nt * KT + kc) * 64];       // plain loads: the row blocks of a column block share these lines in L2
-        }
+        for (int j = 0; j < CW; ++j) wt[j] = *(const u32x4_t*)(base + woff[j]);   // plain loads: the row blocks of a column block share these lines in L2
     };
 
     f32x4_t acc[CW][4];
@@ -411,6 +421,8 @@ static hipError_t launch256(int epi, const Gemm256Args& a, dim3 grid, hipStream_
 hipError_t fc_gemm256(int epi, const Gemm256Args& a, hipStream_t st) {
     if (a.M < 1 || a.K % 256 || a.NT < 1 || a.sk < 1 || a.sk > FC_GEMM256_MAX_SK || a.sk > a.K / 128) return hipErrorInvalidValue;
     if (a.sk > 1 && (epi != EPI_RESID || !a.part)) return hipErrorInvalidValue;
+    // the kernel addresses weights and fragments with 32-bit byte offsets from their bases
+    if ((size_t)a.NT * 16 * a.K * 2 >= ((size_t)1 << 32) || (size_t)((a.M + 15) / 16) * 16 * a.K * 4 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
     // narrow tiles when wide ones would leave most of the chip idle
     const int nrb = ((a.M + 15) / 16 + 3) / 4;
     const int cw = (fc_gemm256_narrow(epi, a.M, a.NT) && a.cw != 4) || a.cw == 1 ? 1 : 4;
