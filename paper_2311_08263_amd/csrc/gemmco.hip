@@ -39,8 +39,8 @@ template <int EPI, int NW, int KB, bool DB, int MT>
 __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     extern __shared__ float lds[];
     constexpr int TW = NW * MT;                          // output tiles per workgroup
-    f32x4_t* lds_part = (f32x4_t*)lds;                  // [8 waves][TW][64 lanes]
-    float* lds_ss = lds + 8 * TW * 256;                 // [8][MT * 16]
+    f32x4_t* lds_part = (f32x4_t*)lds;                  // [4 wave pairs][TW][64 lanes]
+    float* lds_ss = lds + 4 * TW * 256;                 // [8][MT * 16]
     float* lds_amv = lds_ss + 8 * MT * 16;              // [8][16]
     int* lds_ami = (int*)(lds_amv + 8 * 16);            // [8][16]
     float* lds_gain = (float*)(lds_ami + 8 * 16);       // [K] (only with a norm in front)
@@ -170,14 +170,33 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         }
     }
 
-    // the eight K slices meet in LDS
+    // the eight K slices meet in LDS, in two rounds so that four partial sets (4 x TW KB) are enough: waves
+    // 4..7 publish, waves 0..3 add those to their own and publish the sums
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         ss[mt] += __shfl_xor(ss[mt], 16, 64);
         ss[mt] += __shfl_xor(ss[mt], 32, 64);
         if (g4 == 0) lds_ss[(w * MT + mt) * 16 + lm] = ss[mt];
+    }
+    if (w >= 4) {
 #pragma unroll
-        for (int j = 0; j < NW; ++j) lds_part[(w * TW + j * MT + mt) * 64 + lane] = acc[j][mt];
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < NW; ++j) lds_part[((w - 4) * TW + j * MT + mt) * 64 + lane] = acc[j][mt];
+    }
+    __syncthreads();
+    if (w < 4) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < NW; ++j) acc[j][mt] += lds_part[(w * TW + j * MT + mt) * 64 + lane];
+    }
+    __syncthreads();
+    if (w < 4) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < NW; ++j) lds_part[(w * TW + j * MT + mt) * 64 + lane] = acc[j][mt];
     }
     __syncthreads();
 
@@ -204,7 +223,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         v[f] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
         if (fin[f]) {
 #pragma unroll
-            for (int q = 0; q < 8; ++q) v[f] += lds_part[(q * TW + ti) * 64 + lane];
+            for (int q = 0; q < 4; ++q) v[f] += lds_part[(q * TW + ti) * 64 + lane];
             v[f] *= rs;
         }
     }
@@ -348,7 +367,7 @@ static int num_cus() {
 int fc_num_cus() { return num_cus(); }
 
 // grid: one workgroup per CU unless that would give a workgroup more than `most` n-tiles (at most 8: with two
-// row tiles a workgroup then finishes 16 output tiles, whose partial sums take 128 KB of LDS)
+// row tiles a workgroup then finishes 16 output tiles, whose partial sums take 64 KB of LDS)
 int fc_gemmco_grid(int NT, int most) {
     int G = num_cus();
     if (G > NT) G = NT;
@@ -357,13 +376,16 @@ int fc_gemmco_grid(int NT, int most) {
 }
 
 static size_t co_lds_bytes(int nw, int mt, int K, bool gain) {
-    return (size_t)8 * nw * mt * 1024 + (size_t)(8 * mt * 16 + 2 * 8 * 16) * 4 + (gain ? (size_t)K * 4 : 0) + 64;
+    return (size_t)4 * nw * mt * 1024 + (size_t)(8 * mt * 16 + 2 * 8 * 16) * 4 + (gain ? (size_t)K * 4 : 0) + 64;
 }
 
 int fc_gemmco_most(int M, int K, bool gain) {
-    int most = 8;
-    while (most > 1 && co_lds_bytes(most, M > 16 ? 2 : 1, K, gain) > 150 * 1024) --most;
-    return most;
+    // the kernel is instantiated for 1, 2, 3, 4, 6 and 8 n-tiles per workgroup (5 runs as 6, 7 as 8) and
+    // sizes its LDS for the instantiated count
+    const int inst[6] = {8, 6, 4, 3, 2, 1};
+    for (int i = 0; i < 6; ++i)
+        if (co_lds_bytes(inst[i], M > 16 ? 2 : 1, K, gain) <= 150 * 1024) return inst[i];
+    return 1;
 }
 
 template <int EPI, int NW, int KB, bool DB, int MT>
