@@ -166,7 +166,9 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         if (nw > 0) {
             co.W = (const bf16_t*)W; co.K = K; co.NT = N / 16; co.X = X; co.ldx = ldx; co.gain = gain; co.out = out; co.ldo = ldo;
             co.layer = g.layer; co.ks = epi == EPI_RESID ? ksl : 1;
-            co.single_buffer = a.plan->co_single == 2 ? !(gi == 3 || gi == 4) : a.plan->co_single;
+            // one or two weight batches in flight per wave, measured per GEMM (7B and 13B shapes): up to 16 rows two
+            // for down and LM head, with 17..32 rows also for gate/up
+            co.single_buffer = a.plan->co_single == 2 ? (M > 16 ? gi < 2 : !(gi == 3 || gi == 4)) : a.plan->co_single;
             co.rotate = gi >= 2;          // gate/up, down, LM head
             co.xpart = (float*)(ws + wm.gemm_part); co.xcnt = (int32_t*)(ws + wm.gemm_cnt);
             co.amax_idx = (int32_t*)(co.amax_val + (size_t)nw * (M > 16 ? 32 : 16));

@@ -405,6 +405,17 @@ template <int EPI>
 static hipError_t launch_epi(const GemmCoArgs& a, int G, hipStream_t st) {
     const int owners = G / (a.ks > 1 ? a.ks : 1);
     const int nw = (a.NT + owners - 1) / owners;  // most n-tiles any workgroup owns
+    if (a.M > 16 && !a.single_buffer) {           // two row tiles, two batches in flight
+        switch (nw) {
+            case 1: return launch_k<EPI, 1, 2, true, 2>(a, G, st);
+            case 2: return launch_k<EPI, 2, 2, true, 2>(a, G, st);
+            case 3: return launch_k<EPI, 3, 2, true, 2>(a, G, st);
+            case 4: return launch_k<EPI, 4, 1, true, 2>(a, G, st);
+            case 5: case 6: return launch_k<EPI, 6, 1, true, 2>(a, G, st);
+            case 7: case 8: return launch_k<EPI, 8, 1, true, 2>(a, G, st);
+        }
+        return hipErrorInvalidValue;
+    }
     if (a.M > 16) {                               // two row tiles
         switch (nw) {
             case 1: return launch_k<EPI, 1, 4, false, 2>(a, G, st);
