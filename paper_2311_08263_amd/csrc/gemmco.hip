@@ -139,6 +139,35 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         }
     };
 
+    // What the epilogue will need from memory is requested now, a whole K loop ahead of its use: the rotary
+    // factors of this wave's output tiles (behind a dependent load of the sequence length) and the residual
+    // tile that the result is added to.
+    constexpr int NF = (TW + 7) / 8;
+    float rcos[NF][4], rsin[NF][4];
+    f32x4_t xold[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        const int ti = w + 8 * f, nt = nt0 + ti / MT, m = (w % MT) * 16 + lm;
+        const bool mine = ti < TW && nt < nt1 && m < a.M;
+        xold[f] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { rcos[f][e] = 1.0f; rsin[f][e] = 0.0f; }
+        if (EPI == EPI_RESID) {
+            if (mine) xold[f] = *(const f32x4_t*)(a.out + (size_t)m * a.ldo + nt * 16 + 4 * g4);
+        } else if (EPI == EPI_QKV) {
+            const int hh = nt >> 3, t = nt & 7;
+            if (mine && hh < a.H + a.Hkv) {
+                const int pos = a.n_state[m / a.Wn] + m % a.Wn;
+                if (pos < a.S) {
+                    const f32x4_t c4 = *(const f32x4_t*)(a.cosT + (size_t)pos * 64 + 8 * t + 4 * (g4 & 1));
+                    const f32x4_t s4 = *(const f32x4_t*)(a.sinT + (size_t)pos * 64 + 8 * t + 4 * (g4 & 1));
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { rcos[f][e] = c4[e]; rsin[f][e] = s4[e]; }
+                }
+            }
+        }
+    }
+
     // two batches in flight per wave: the next one is requested before the current one is used
     // (DB = false keeps one batch per wave in flight and fewer registers, so that two workgroups
     // share a CU and overlap each other's phases instead)
@@ -202,7 +231,6 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
 
     // wave w finishes tiles w and (with more than 8 tiles) w + 8: lane holds row tm*16 + lm, columns
     // nt*16 + 4*g4 + r.  MT divides 8, so both tiles of a wave belong to the same row tile tm.
-    constexpr int NF = (TW + 7) / 8;
     const int tm = w % MT;
     const int m = tm * 16 + lm;
     int ntf[NF];
@@ -266,10 +294,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         const f32x4_t vv = v[f];
         if (!fin[f]) continue;
         if (EPI == EPI_RESID) {
-            if (m < a.M) {
-                f32x4_t* o = (f32x4_t*)(a.out + (size_t)m * a.ldo + nt * 16 + 4 * g4);
-                *o = *o + vv;
-            }
+            if (m < a.M) *(f32x4_t*)(a.out + (size_t)m * a.ldo + nt * 16 + 4 * g4) = xold[f] + vv;
         } else if (EPI == EPI_SWIGLU) {
             // columns 0..7 of a tile: gate of features 8*nt..; columns 8..15: their up values (lane ^ 32)
             f32x4_t h;
@@ -293,8 +318,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float other = __shfl_xor(vv[e], 32, 64);
-                    const float c = ok ? a.cosT[(size_t)pos * 64 + i0 + e] : 1.0f;
-                    const float s = ok ? a.sinT[(size_t)pos * 64 + i0 + e] : 0.0f;
+                    const float c = rcos[f][e], s = rsin[f][e];
                     r[e] = g4 < 2 ? vv[e] * c - other * s : vv[e] * c + other * s;
                 }
                 const int el = (g4 < 2 ? 0 : 64) + i0;          // element index within the head
@@ -439,7 +463,7 @@ static hipError_t launch_epi(const GemmCoArgs& a, int G, hipStream_t st) {
         return hipErrorInvalidValue;
     }
     switch (nw) {
-        case 1: return launch_k<EPI, 1, 6, true, 1>(a, G, st);
+        case 1: return launch_k<EPI, 1, 4, true, 1>(a, G, st);
         case 2: return launch_k<EPI, 2, 4, true, 1>(a, G, st);
         case 3: return launch_k<EPI, 3, 3, true, 1>(a, G, st);
         case 4: return launch_k<EPI, 4, 2, true, 1>(a, G, st);
