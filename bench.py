@@ -294,10 +294,13 @@ def main():
     prof = ctx.profile_step(args.profile_iters)
     wb = weight_bytes_per_step(shape, esz)
     table = []
+    empty_ms = prof.pop("empty_kernel", (0.0, 0))[0]      # the event pair around a kernel that does nothing
     for kind, (ms, cnt) in prof.items():
         b = wb.get(kind)
         table.append((kind, ms, cnt, b))
         log(f"kernel {kind:14s} {cnt:4d}/step  {ms * 1e3:9.2f} us" + (f"  {b / (ms * 1e-3) / 1e9:7.0f} GB/s" if b else ""))
+    log(f"event pair around an empty kernel: {empty_ms * 1e3:.2f} us (the floor of these event intervals; a profiler's begin-to-end "
+        "durations of the long kernels are 2-3 us shorter than the figures above)")
     cands = [t for t in table if t[3]]
     if not cands:      # persistent kernel: the whole step is one launch
         ms, cnt = prof["persistent_step"]
@@ -319,6 +322,10 @@ def main():
                     "flops_per_launch": flops, "issued_flops_per_launch": 2 * flops, "avg_launch_ms": round(dom[1], 5),
                     "step_algorithmic_bytes": int(alg), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4)}
 
+    # launch durations above are HIP-event intervals, which start when the previous event completes: they
+    # contain the launch latency that a profiler's begin-to-end duration leaves out.  The same pair around an
+    # empty kernel (same pass) is reported as the floor of such intervals.
+    roofline["empty_kernel_event_ms"] = round(empty_ms, 5)
     extra = None
     if not args.no_extras and not args.plain and shape.dtype == "bf16":
         extra = extras(torch, fc, synthgen, packed, log)

@@ -182,7 +182,8 @@ int fastcot_step_times(fastcot_ctx* ctx, float* ms, int32_t cap, int32_t* n_step
 
 /* Runs `iters` forward passes of the current state (no accept, state unchanged), launching
  * kernels one by one with a HIP event pair around each, and reports per kernel kind the mean
- * duration of one launch in ms and the launches per step.  kinds: see fastcot_kernel_name().
+ * duration of one launch in ms and the launches per step.  kinds: see fastcot_kernel_name(); kind
+ * "empty_kernel" is the same event pair around a kernel that does nothing (what the pair itself adds).
  * Host outputs sized FASTCOT_N_KERNEL_KINDS. */
 enum { FASTCOT_N_KERNEL_KINDS = 16 };
 int fastcot_profile_step(fastcot_ctx* ctx, int32_t iters, float* mean_ms, int32_t* launches_per_step);
