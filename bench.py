@@ -24,8 +24,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain
-# copy kernel of known size (profiles/hbm_traffic_7b_w16.md); None where no counter run exists
-MEASURED_TRAFFIC = {("7b", "gemm_gate_up"): 183.4e6}
+# copy kernel of known size (profiles/hbm_traffic_7b_w16.md, hbm_traffic_13b_b8_w32.md); None where no counter
+# run exists
+MEASURED_TRAFFIC = {("7b", "gemm_gate_up"): 183.4e6, ("13b", "gemm_gate_up"): 398.1e6}
 WORKLOADS = {
     # name: (shape, batch, prompt, window, new tokens)
     "7b": ("7b", 1, 256, 16, 256),
@@ -318,7 +319,7 @@ def main():
         flops = 2.0 * B * W * dom[3] / esz
         tf = flops / (dom[1] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": dom[0], "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get((args.workload, dom[0])),
                     "flops_per_launch": flops, "issued_flops_per_launch": 2 * flops, "avg_launch_ms": round(dom[1], 5),
                     "step_algorithmic_bytes": int(alg), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4)}
 
