@@ -166,6 +166,12 @@ enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLAN
        FASTCOT_OPT_KS_O = 32, FASTCOT_OPT_KS_DOWN = 33,
        FASTCOT_OPT_CO_SINGLE = 27,   /* weight batches in flight per wave of the column-owner GEMM: 1 = one, 0 = two,
                                       * 2 (default) = chosen per GEMM */
+       /* 1 (default): at the first fastcot_prefill of a step shape with at most 32 rows, every column-owner
+        * GEMM is timed on the model's own matrices (a few ms) with one / two batches in flight, plain / rotated
+        * batch order and 1 / 2 / 4 K slices per owner, and the fastest combination is kept (results do not
+        * depend on the choice beyond the order of a few fp32 additions).  Setting any of the NW, KS or CO_SINGLE
+        * options turns it off: explicit choices win. */
+       FASTCOT_OPT_AUTOTUNE = 34,
        /* debug: run only the first `value` stages of a forward (per layer: QKV, attention, O,
         * gate/up, down); negative = all */
        FASTCOT_OPT_DEBUG_STAGES = 30 };

@@ -22,6 +22,8 @@ struct fastcot_ctx {
     hipStream_t st;
     int Bact;            // sequences of the current run
     int prefilled, generated;
+    int opt_tune;        // measure the plan's per-GEMM choices at prefill
+    int tuned_rows[2];   // rows per step the plan's per-GEMM choices were last measured for (up to 16 / 17..32 rows)
     int last_eos;        // eos_id of the last fastcot_generate (-1 = none)
     int buf_len;
     int opt_plain, opt_graph, opt_persist, dbg_stop;
@@ -210,7 +212,7 @@ extern "C" int fastcot_init(const fastcot_config* cfg, const void* d_packed, voi
     if (fc_build_maps(cfg, &c->mm, &c->wm, &c->kd) != 0) { delete c; return fail(nullptr, FASTCOT_EINVAL, "invalid configuration%s"); }
     if (workspace_bytes < c->wm.total) { delete c; return fail(nullptr, FASTCOT_ECAPACITY, "workspace too small%s"); }
     c->cfg = *cfg; c->weights = (const char*)d_packed; c->ws = (char*)d_workspace; c->st = (hipStream_t)hip_stream;
-    c->Bact = 0; c->prefilled = 0; c->generated = 0; c->buf_len = 0;
+    c->Bact = 0; c->prefilled = 0; c->generated = 0; c->buf_len = 0; c->opt_tune = 1;
     c->opt_plain = (cfg->dtype == FASTCOT_F32); c->opt_graph = 1; c->opt_persist = 0; c->dbg_stop = -1; c->dbg_logits = nullptr;
     c->graph_exec = nullptr; c->graph = nullptr; c->graph_valid = 0; c->prof_on = 0; c->prof_used = 0;
     c->pinned = nullptr; c->err[0] = 0;
@@ -280,17 +282,19 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
         const int gi = option - FASTCOT_OPT_NW_QKV, ks = c->plan.ks[gi] > 1 ? c->plan.ks[gi] : 1;
         if (value > 0 && (value % ks || value / ks > NT || (NT + value / ks - 1) / (value / ks) > 8))
             return fail(c, FASTCOT_EINVAL, "workgroups of the column-owner GEMM do not fit its K slices per owner%s");
-        c->plan.nw[gi] = value;
+        c->plan.nw[gi] = value; c->opt_tune = 0;
     } else if (option == FASTCOT_OPT_KS_O || option == FASTCOT_OPT_KS_DOWN) {
         const int gi = option == FASTCOT_OPT_KS_O ? 1 : 3, NT = c->kd.d / 16, nw = c->plan.nw[gi];
         const int K = gi == 1 ? c->kd.H * c->kd.Dh : c->kd.F;
         if (value < 1 || value > 8 || K / 256 < value) return fail(c, FASTCOT_EINVAL, "K slices per owner out of range%s");
         if (nw > 0 && (nw % value || nw / value > NT || nw / value < 1 || (NT + nw / value - 1) / (nw / value) > 8))
             return fail(c, FASTCOT_EINVAL, "K slices per owner do not fit the workgroup count of that GEMM%s");
-        c->plan.ks[gi] = value;
+        c->plan.ks[gi] = value; c->opt_tune = 0;
     } else if (option == FASTCOT_OPT_CO_SINGLE) {
         if (value < 0 || value > 2) return fail(c, FASTCOT_EINVAL, "buffering of the column-owner GEMM: 0, 1 or 2%s");
-        c->plan.co_single = value;
+        c->plan.co_single = value; c->opt_tune = 0;
+    } else if (option == FASTCOT_OPT_AUTOTUNE) {
+        c->opt_tune = value != 0; c->tuned_rows[0] = c->tuned_rows[1] = 0;
     }
     else if (option == FASTCOT_OPT_ATTN_SPLITS) {
         if (value < 1 || value > FC_MAX_ATTN_SPLITS) return fail(c, FASTCOT_EINVAL, "attention splits out of range%s");
@@ -456,6 +460,20 @@ extern "C" int fastcot_prefill(fastcot_ctx* c, int32_t B, const int32_t* prompts
     HIPCHK(c, hipMemset(stp + sm.n, 0, (size_t)kd.B * 4));
     if (B != c->Bact) drop_graph(c);
     c->Bact = B; c->buf_len = buf_len; c->prefilled = 0; c->generated = 0;
+    // the plan's per-GEMM choices are measured once per step shape, on this model's own matrices (the buffers
+    // hold nothing yet that the passes below do not overwrite)
+    {
+        const int rows = B * kd.W, cls = rows > 16;
+        if (c->opt_tune && !c->opt_plain && !c->opt_persist && c->plan.co_single == 2 && rows <= 32 && c->tuned_rows[cls] != rows &&
+            fc_fast_supported(kd, rows)) {
+            FastArgs a;
+            a.kd = kd; a.kd.M = rows; a.Bact = B; a.mm = &c->mm; a.wm = &c->wm; a.weights = c->weights; a.ws = c->ws;
+            a.dbg_logits = nullptr; a.plan = &c->plan; a.st = c->st; a.lmhead = 1; a.dbg_stop = -1; a.prof = nullptr; a.prof_mark = nullptr;
+            HIPCHK(c, fc_fast_tune(a, &c->plan));
+            c->tuned_rows[cls] = rows;
+            drop_graph(c);
+        }
+    }
     // passes of R rows per sequence over prompt tokens 0 .. maxlen-2 (the last prompt token becomes slot 0
     // of the first window); the plain path keeps R = window
     const int rows_cap = (c->opt_plain || !fc_fast_supported(kd, B * kd.W)) ? kd.W : kd.Wcap;

@@ -64,6 +64,7 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     // bytes than weight bytes; K slices per owner cut that (measured at the 7B shape)
     if (kd.F >= 2 * kd.d && kd.F >= 4096 && p->nw[3] % 4 == 0 && p->nw[3] / 4 <= nts[3] && (nts[3] + p->nw[3] / 4 - 1) / (p->nw[3] / 4) <= 8) p->ks[3] = 4;
     p->co_single = 2;    // measured (7B and 70B shapes): down and LM head 2-4 % faster with two batches in flight, QKV and O slower
+    for (int i = 0; i < 5; ++i) { p->co_sb[0][i] = !(i == 3 || i == 4); p->co_sb[1][i] = i < 2; p->co_rot[0][i] = p->co_rot[1][i] = i >= 2; }
     // 17..32 rows (two row tiles per workgroup, up to 16 output tiles): the same grids where the partial tiles
     // fit the LDS, K slices halved until they divide the grid
     const int kin[5] = {kd.d, kd.H * kd.Dh, kd.d, kd.F, kd.d};
@@ -162,14 +163,14 @@ hipError_t fc_fast_forward(const FastArgs& a) {
                     float* out, int ldo) {
         // workgroups of the column-owner kernel (0 = split-K kernel) and its K slices per owner
         const int nw = M <= 16 ? a.plan->nw[gi] : (M <= 32 ? a.plan->nw2[gi] : 0);
-        const int ksl = M <= 16 ? a.plan->ks[gi] : a.plan->ks2[gi];
+        const int ksl = a.tune_gi >= 0 ? a.tune_ks : (M <= 16 ? a.plan->ks[gi] : a.plan->ks2[gi]);
         if (nw > 0) {
             co.W = (const bf16_t*)W; co.K = K; co.NT = N / 16; co.X = X; co.ldx = ldx; co.gain = gain; co.out = out; co.ldo = ldo;
             co.layer = g.layer; co.ks = epi == EPI_RESID ? ksl : 1;
-            // one or two weight batches in flight per wave, measured per GEMM (7B and 13B shapes): up to 16 rows two
-            // for down and LM head, with 17..32 rows also for gate/up
-            co.single_buffer = a.plan->co_single == 2 ? (M > 16 ? gi < 2 : !(gi == 3 || gi == 4)) : a.plan->co_single;
-            co.rotate = gi >= 2;          // gate/up, down, LM head
+            // one or two weight batches in flight per wave: which is faster depends on the GEMM and on the shape
+            // (7B: two for down and LM head; 13B: two for QKV and gate/up, one for down), so it is a plan entry
+            co.single_buffer = a.tune_gi >= 0 ? a.tune_sb : (a.plan->co_single == 2 ? a.plan->co_sb[M > 16][gi] : a.plan->co_single);
+            co.rotate = a.tune_gi >= 0 ? a.tune_rot : a.plan->co_rot[M > 16][gi];
             co.xpart = (float*)(ws + wm.gemm_part); co.xcnt = (int32_t*)(ws + wm.gemm_cnt);
             co.amax_idx = (int32_t*)(co.amax_val + (size_t)nw * (M > 16 ? 32 : 16));
             return fc_gemmco(epi, co, nw, a.st);
@@ -205,6 +206,18 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         return fc_gemm16(epi, g, pl.ncg, a.st);
     };
 
+    if (a.tune_gi >= 0) {            // timing run of one GEMM (layer 0 weights, whatever the buffers hold)
+        const char* lb = wt + mm.layers_off;
+        g.layer = 0; gi = a.tune_gi;
+        switch (gi) {
+            case 0: return gemm(EPI_QKV, a.plan->qkv, lb + mm.qkv.off, d, kd.qkvN, x, d, (const float*)(lb + mm.g1_off), q, qd);
+            case 1: return gemm(EPI_RESID, a.plan->o, lb + mm.o.off, qd, d, att, qd, nullptr, x, d);
+            case 2: return gemm(EPI_SWIGLU, a.plan->gu, lb + mm.gu.off, d, 2 * kd.F, x, d, (const float*)(lb + mm.g2_off), h, kd.F);
+            case 3: return gemm(EPI_RESID, a.plan->down, lb + mm.down.off, kd.F, d, h, kd.F, nullptr, x, d);
+            case 4: return gemm(EPI_LMHEAD, a.plan->lm, wt + mm.lm.off, d, kd.V, x, d, (const float*)(wt + mm.gf_off), nullptr, kd.V);
+        }
+        return hipErrorInvalidValue;
+    }
     FLAUNCH(KK_EMBED, fc_embed(wt + mm.emb_off, FASTCOT_BF16, stp + wm.st.win, x, M, d, kd.V, a.st));
     int nstage = 0;
 #define DBG_STOP() do { if (a.dbg_stop >= 0 && nstage++ >= a.dbg_stop) return hipSuccess; } while (0)
@@ -248,6 +261,58 @@ hipError_t fc_fast_forward(const FastArgs& a) {
                                                stp + wm.st.o, (float*)(ws + wm.topv), a.st));
     }
     return hipSuccess;
+}
+
+hipError_t fc_fast_tune(FastArgs a, FastPlan* plan) {
+    const int M = a.kd.M;
+    if (M < 1 || M > 32) return hipSuccess;
+    const int cls = M > 16;
+    a.prof = nullptr; a.prof_mark = nullptr; a.dbg_stop = -1; a.plan = plan;
+    hipEvent_t e0, e1;
+    hipError_t e = hipEventCreate(&e0);
+    if (e != hipSuccess) return e;
+    if ((e = hipEventCreate(&e1)) != hipSuccess) { (void)hipEventDestroy(e0); return e; }
+    // mean of 5 launches after 2 untimed ones; hipErrorInvalidValue from the first launch = the launcher
+    // rejected the combination (nothing ran)
+    auto measure = [&](float* ms) -> hipError_t {
+        hipError_t r = fc_fast_forward(a);
+        if (r != hipSuccess) return r;
+        r = fc_fast_forward(a);
+        if (r == hipSuccess) r = hipEventRecord(e0, a.st);
+        for (int i = 0; i < 5 && r == hipSuccess; ++i) r = fc_fast_forward(a);
+        if (r == hipSuccess) r = hipEventRecord(e1, a.st);
+        if (r == hipSuccess) r = hipEventSynchronize(e1);
+        if (r == hipSuccess) r = hipEventElapsedTime(ms, e0, e1);
+        return r;
+    };
+    for (int gi = 0; gi < 5 && e == hipSuccess; ++gi) {
+        const int nw = cls ? plan->nw2[gi] : plan->nw[gi];
+        if (nw <= 0) continue;                      // not a column-owner launch
+        const bool resid = gi == 1 || gi == 3;
+        float best = 1e30f;
+        int best_sb = plan->co_sb[cls][gi], best_rot = plan->co_rot[cls][gi], best_ks = cls ? plan->ks2[gi] : plan->ks[gi];
+        a.tune_gi = gi;
+        for (int ks = 1; ks <= (resid ? 4 : 1) && e == hipSuccess; ks *= 2)
+            for (int rot = 0; rot < 2 && e == hipSuccess; ++rot)
+                for (int sb = 0; sb < 2 && e == hipSuccess; ++sb) {
+                    a.tune_ks = ks; a.tune_rot = rot; a.tune_sb = sb;
+                    float t = 1e30f;
+                    for (int rep = 0; rep < 3 && e == hipSuccess; ++rep) {
+                        float ms = 0.f;
+                        const hipError_t r = measure(&ms);
+                        if (r == hipErrorInvalidValue) { t = 1e30f; break; }
+                        e = r;
+                        if (e == hipSuccess && ms < t) t = ms;
+                    }
+                    if (e == hipSuccess && t < best) { best = t; best_sb = sb; best_rot = rot; best_ks = ks; }
+                }
+        if (e == hipSuccess && best < 1e29f) {
+            plan->co_sb[cls][gi] = best_sb; plan->co_rot[cls][gi] = best_rot;
+            if (cls) plan->ks2[gi] = best_ks; else plan->ks[gi] = best_ks;
+        }
+    }
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    return e;
 }
 
 // ------------------------------------------------------------------ isolation launchers

@@ -54,6 +54,22 @@ def test_follow_mode_small_models(fc, shape, B, W, P, persistent):
     assert r["max_err"] < 2e-3          # far inside the bf16 bar thanks to hi/lo activations
 
 
+@pytest.mark.parametrize("W", [16, 24])
+def test_without_autotune(fc, W):
+    """The plan's defaults (no timing runs at prefill: option 34 = 0) pass the same bar as the measured plan."""
+    shape, B, P, N = SMALL, 2, 37, 48
+    say(f"bf16 follow without autotune W={W}")
+    S = ((P + N + 2 * W + 31) // 32) * 32
+    ctx, om = setup(fc, shape, B, S, W)
+    ctx.set_option(34, 0)
+    lens = [P, P - 4]
+    prompts = synthgen.prompts(B, P, shape.vocab, seed=61)
+    buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=62)
+    ctx.prefill(prompts, lens, buf)
+    r = follow_steps(ctx, om, prompts, lens, 4, TOL)
+    assert r["max_err"] < 2e-3
+
+
 def test_fast_path_matches_plain_path_and_oracle_stream(fc):
     """Same model through the MFMA kernels and through the plain kernels: same tokens; and the
     accepted stream is the oracle's greedy continuation up to the first low-margin row."""
