@@ -90,9 +90,8 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
     struct KV { Frag kf[KVP][2][4], vf[KVP][8]; };
     auto load = [&](KV& r, int blk_want) {
         const int blk = blk_want < NB ? blk_want : NB - 1;       // past the end: a valid block, never used
-        const int kb = blk << 5;
         Frag (&kf)[KVP][2][4] = r.kf; Frag (&vf)[KVP][8] = r.vf;
-        // K tiles (A operand): tile t row r=lm <-> key kb + 8*(lm/4) + 4*t + lm%4 ; dh 32*g + 8*s..
+        // K tiles (A operand): tile t row r=lm <-> key 32*blk + 8*(lm/4) + 4*t + lm%4 ; dh 32*g + 8*s..
         // (the cache stores each block as these eight fragments, one contiguous kilobyte each; the loads are
         // non-temporal: K and V are read once per step, and letting them allocate in L2 cost 40% at batch 8)
 #pragma unroll
