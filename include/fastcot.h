@@ -172,6 +172,10 @@ enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLAN
         * depend on the choice beyond the order of a few fp32 additions).  Setting any of the NW, KS or CO_SINGLE
         * options turns it off: explicit choices win. */
        FASTCOT_OPT_AUTOTUNE = 34,
+       /* 1 (default): whenever fastcot_generate finds finished sequences at one of its checks, they trade slots
+        * (state and K/V cache) with unfinished ones so that the following steps run only the unfinished
+        * sequences' rows; the order is restored before it returns.  0: finished sequences keep their rows. */
+       FASTCOT_OPT_COMPACT = 35,
        /* debug: run only the first `value` stages of a forward (per layer: QKV, attention, O,
         * gate/up, down); negative = all */
        FASTCOT_OPT_DEBUG_STAGES = 30 };

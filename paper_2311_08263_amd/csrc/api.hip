@@ -22,6 +22,7 @@ struct fastcot_ctx {
     hipStream_t st;
     int Bact;            // sequences of the current run
     int prefilled, generated;
+    int opt_compact;     // fastcot_generate moves finished sequences out of the way so that later steps run fewer rows
     int opt_tune;        // measure the plan's per-GEMM choices at prefill
     int tuned_rows[2];   // rows per step the plan's per-GEMM choices were last measured for (up to 16 / 17..32 rows)
     int last_eos;        // eos_id of the last fastcot_generate (-1 = none)
@@ -212,7 +213,7 @@ extern "C" int fastcot_init(const fastcot_config* cfg, const void* d_packed, voi
     if (fc_build_maps(cfg, &c->mm, &c->wm, &c->kd) != 0) { delete c; return fail(nullptr, FASTCOT_EINVAL, "invalid configuration%s"); }
     if (workspace_bytes < c->wm.total) { delete c; return fail(nullptr, FASTCOT_ECAPACITY, "workspace too small%s"); }
     c->cfg = *cfg; c->weights = (const char*)d_packed; c->ws = (char*)d_workspace; c->st = (hipStream_t)hip_stream;
-    c->Bact = 0; c->prefilled = 0; c->generated = 0; c->buf_len = 0; c->opt_tune = 1;
+    c->Bact = 0; c->prefilled = 0; c->generated = 0; c->buf_len = 0; c->opt_tune = 1; c->opt_compact = 1;
     c->opt_plain = (cfg->dtype == FASTCOT_F32); c->opt_graph = 1; c->opt_persist = 0; c->dbg_stop = -1; c->dbg_logits = nullptr;
     c->graph_exec = nullptr; c->graph = nullptr; c->graph_valid = 0; c->prof_on = 0; c->prof_used = 0;
     c->pinned = nullptr; c->err[0] = 0;
@@ -293,6 +294,8 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
     } else if (option == FASTCOT_OPT_CO_SINGLE) {
         if (value < 0 || value > 2) return fail(c, FASTCOT_EINVAL, "buffering of the column-owner GEMM: 0, 1 or 2%s");
         c->plan.co_single = value; c->opt_tune = 0;
+    } else if (option == FASTCOT_OPT_COMPACT) {
+        c->opt_compact = value != 0;
     } else if (option == FASTCOT_OPT_AUTOTUNE) {
         c->opt_tune = value != 0; c->tuned_rows[0] = c->tuned_rows[1] = 0;
     }
@@ -582,10 +585,20 @@ extern "C" int fastcot_generate(fastcot_ctx* c, int32_t max_new, int32_t max_ste
     hipEvent_t ev;
     HIPCHK(c, next_event(&ev));
     if (ev) HIPCHK(c, hipEventRecord(ev, c->st));
+    // Ragged finish: sequences that are done trade slots with unfinished ones further back, so that the
+    // unfinished ones sit in slots 0..Bcur-1 and the following steps run Bcur * W rows (every kernel works on
+    // the first Bact slots).  The trades are undone before returning: callers see their own order.
+    int Bcur = B;
+    std::vector<std::pair<int, int>> trades;
+    const size_t seq_bytes = (size_t)kd.Hkv * kd.kvp * kd.S * kd.Dh * kd.esz;
+    auto trade = [&](int b1, int b2) -> hipError_t {
+        return fc_swap_sequences(stp, sm, b1, b2, W, kd.S, c->ws + c->wm.kc, c->ws + c->wm.vc, seq_bytes, kd.L,
+                                 (size_t)kd.B * seq_bytes, c->st);
+    };
     while (!all_done) {
         // every unfinished sequence needs at least ceil((max_new - g) / W) more steps: enqueue that many
         int need = 1;
-        for (int b = 0; b < B; ++b) {
+        for (int b = 0; b < Bcur; ++b) {
             int r = (max_new - hg[b] + W - 1) / W;
             if (total_steps == 0 || !hdone[b]) need = r > need ? r : need;
         }
@@ -605,7 +618,32 @@ extern "C" int fastcot_generate(fastcot_ctx* c, int32_t max_new, int32_t max_ste
         { int rc = check_abort(c); if (rc) return rc; }
         all_done = c->pinned[2 * B + FLAG_ALL_DONE] != 0;
         for (int b = 0; b < B; ++b) { hg[b] = c->pinned[b]; hdone[b] = c->pinned[B + b]; }
-        if (c->pinned[2 * B + FLAG_ERROR]) return fail(c, FASTCOT_ECAPACITY, "a sequence ran out of cache or buffer capacity%s");
+        if (c->pinned[2 * B + FLAG_ERROR]) {
+            for (size_t i = trades.size(); i-- > 0;) (void)trade(trades[i].first, trades[i].second);
+            c->Bact = B; drop_graph(c);
+            return fail(c, FASTCOT_ECAPACITY, "a sequence ran out of cache or buffer capacity%s");
+        }
+        if (!all_done && c->opt_compact && !use_persist(c) && !(max_steps > 0 && total_steps >= max_steps)) {
+            int lo = 0, hi = Bcur - 1, moved = 0;
+            for (;;) {
+                while (lo < hi && !hdone[lo]) ++lo;          // first finished slot
+                while (hi > lo && hdone[hi]) --hi;           // last unfinished slot
+                if (lo >= hi) break;
+                HIPCHK(c, trade(lo, hi));
+                trades.push_back({lo, hi});
+                std::swap(hg[lo], hg[hi]); std::swap(hdone[lo], hdone[hi]);
+                ++moved;
+            }
+            int nact = 0;
+            while (nact < Bcur && !hdone[nact]) ++nact;
+            if (nact >= 1 && nact < Bcur) { Bcur = nact; c->Bact = nact; drop_graph(c); }
+            (void)moved;
+        }
+    }
+    if (!trades.empty() || c->Bact != B) {
+        for (size_t i = trades.size(); i-- > 0;) HIPCHK(c, trade(trades[i].first, trades[i].second));
+        c->Bact = B; drop_graph(c);
+        HIPCHK(c, hipStreamSynchronize(c->st));
     }
     for (size_t i = 0; i + 1 < ev_used; ++i) {
         float ms = 0; HIPCHK(c, hipEventElapsedTime(&ms, c->step_ev[i], c->step_ev[i + 1]));

@@ -20,6 +20,9 @@ hipError_t fc_prefill_advance(int32_t* state, const StateMap& sm, int B, int W, 
                               hipStream_t st);
 hipError_t fc_rewindow(int32_t* state, const StateMap& sm, int B, int W, int S, hipStream_t st);
 hipError_t fc_accept_commit(int32_t* state, const StateMap& sm, int B, int W, int S, hipStream_t st);
+// sequences b1 and b2 trade slots: state entries and K/V cache (seq_bytes per sequence and layer, layers layer_stride_bytes apart)
+hipError_t fc_swap_sequences(int32_t* state, const StateMap& sm, int b1, int b2, int W, int S, void* kc, void* vc,
+                             size_t seq_bytes, int layers, size_t layer_stride_bytes, hipStream_t st);
 
 // ---- weight packing
 hipError_t fc_pack(const void* src, int dt, int rows, int cols, void* dst_base, const FusedMat& fm, int col_off,

@@ -107,3 +107,47 @@ hipError_t fc_accept_commit(int32_t* state, const StateMap& sm, int B, int W, in
     k_accept_commit<<<1, 64, 0, st>>>(state, sm, B, W, S);
     return hipGetLastError();
 }
+
+// ------------------------------------------------------------------ sequence slots
+// Two sequences trade slots: every per-sequence entry of the state block (one workgroup) ...
+__global__ void k_swap_seq(int32_t* st, StateMap sm, int b1, int b2, int W, int S) {
+    const int t = threadIdx.x;
+    if (t < 8) {
+        const int32_t offs[8] = {sm.n, sm.g, sm.done, sm.steps, sm.newest, sm.lastK, sm.plen, sm.olen};
+        const int32_t v1 = st[offs[t] + b1], v2 = st[offs[t] + b2];
+        st[offs[t] + b1] = v2; st[offs[t] + b2] = v1;
+    }
+    for (int j = t; j < W; j += blockDim.x) {
+        const int32_t v1 = st[sm.win + b1 * W + j], v2 = st[sm.win + b2 * W + j];
+        st[sm.win + b1 * W + j] = v2; st[sm.win + b2 * W + j] = v1;
+    }
+    const int32_t rows[3] = {sm.buf, sm.out, sm.prompt};
+    for (int r = 0; r < 3; ++r)
+        for (int j = t; j < S; j += blockDim.x) {
+            const int32_t v1 = st[rows[r] + b1 * S + j], v2 = st[rows[r] + b2 * S + j];
+            st[rows[r] + b1 * S + j] = v2; st[rows[r] + b2 * S + j] = v1;
+        }
+}
+// ... and their K/V cache: `count` chunks of n16 sixteen-byte words, chunk i at a + i * stride16 and b + i * stride16
+__global__ void k_swap_chunks(uint4* a, uint4* b, size_t n16, size_t stride16) {
+    uint4* pa = a + (size_t)blockIdx.y * stride16; uint4* pb = b + (size_t)blockIdx.y * stride16;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) {
+        const uint4 va = pa[i], vb = pb[i];
+        pa[i] = vb; pb[i] = va;
+    }
+}
+hipError_t fc_swap_sequences(int32_t* state, const StateMap& sm, int b1, int b2, int W, int S, void* kc, void* vc,
+                             size_t seq_bytes, int layers, size_t layer_stride_bytes, hipStream_t st) {
+    if (b1 == b2) return hipSuccess;
+    if (seq_bytes % 16 || layer_stride_bytes % 16) return hipErrorInvalidValue;
+    k_swap_seq<<<1, 256, 0, st>>>(state, sm, b1, b2, W, S);
+    const size_t n16 = seq_bytes / 16;
+    unsigned gx = (unsigned)((n16 + 255) / 256);
+    if (gx > 2048) gx = 2048;
+    for (int which = 0; which < 2; ++which) {
+        char* base = (char*)(which ? vc : kc);
+        k_swap_chunks<<<dim3(gx, (unsigned)layers), 256, 0, st>>>((uint4*)(base + (size_t)b1 * seq_bytes), (uint4*)(base + (size_t)b2 * seq_bytes),
+                                                                 n16, layer_stride_bytes / 16);
+    }
+    return hipGetLastError();
+}

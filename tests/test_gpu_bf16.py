@@ -136,6 +136,32 @@ def test_answer_phase_bf16(fc):
         print(f"answer phase seq {b}: {upto} of {NA} tokens above the margin, all equal")
 
 
+def test_early_finishers_bf16(fc):
+    """bf16 model, batch of three of which one has a perfect draft: after it has left the batch the other two run
+    through the kernels for fewer rows; every sequence's accepted stream is still the oracle's greedy continuation
+    up to its first low-margin row."""
+    shape, W, P, N, B = SMALL, 16, 40, 64, 3
+    S = ((P + N + 2 * W + 31) // 32) * 32
+    ctx, om = setup(fc, shape, B, S, W)
+    prompts = synthgen.prompts(B, P, shape.vocab, seed=81)
+    buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=82)
+    lens = [P, P - 6, P - 1]
+    greedy = [om.greedy_ar(prompts[b, :lens[b]], N + 2 * W) for b in range(B)]
+    buf[1, :] = greedy[1]                              # slot j of a window drafts generated token g + j - 1
+    say("bf16 batch with an early finisher")
+    ctx.prefill(prompts, lens, buf)
+    out = ctx.generate(N)
+    assert out["steps"][1] <= N // W + 2 and out["steps"][0] > 2 * out["steps"][1]
+    for b in range(B):
+        ss = om.session(S)
+        if lens[b] > 1: ss.forward(prompts[b, :lens[b] - 1], 0, want_logits=False)
+        lg, _, _ = ss.forward(np.concatenate([prompts[b, lens[b] - 1:lens[b]], greedy[b][:N - 1]]), lens[b] - 1)
+        low = np.where(margins(lg) <= 0.05)[0]
+        upto = int(low[0]) if len(low) else N
+        assert (out["ids"][b, :upto] == greedy[b][:upto]).all(), (b, upto)
+        print(f"sequence {b}: {out['steps'][b]} steps, {upto} of {N} tokens above the margin, all equal")
+
+
 def test_deterministic_replay(fc):
     shape, W, P, N = SMALL, 16, 30, 40
     S = ((P + N + 2 * W + 31) // 32) * 32

@@ -129,6 +129,39 @@ def test_ragged_batch_eos_and_cap(env):
         assert out["steps"][b] == 3 and out["len"][b] == L and (out["ids"][b, :L] == refs[b]["ids"]).all()
 
 
+def test_finished_sequences_leave_the_batch(env):
+    """Sequences that finish early (a perfect draft needs N / W steps, a random buffer about N) trade slots with
+    unfinished ones inside fastcot_generate, so later steps run fewer rows; outputs, step counts, tails and the
+    state afterwards are those of the run without the trades and of the oracle, in the caller's order, and the
+    answer phase still finds every sequence's cache."""
+    fc, om = env
+    W, N, B, P = 4, 32, 5, 11
+    lens = [11, 7, 9, 11, 5]
+    prompts = synthgen.prompts(B, P, TINY.vocab, seed=71)
+    buf = synthgen.buffer_init(B, N + 2 * W, TINY.vocab, seed=72)
+    for b in (0, 3):                                   # perfect drafts: these finish after N / W steps
+        buf[b, :] = om.greedy_ar(prompts[b, :lens[b]], N + 2 * W)      # slot j of a window drafts generated token g + j - 1
+    refs = [om.jacobi_generate(prompts[b, :lens[b]], buf[b], W, N) for b in range(B)]
+    assert refs[0]["steps"] == N // W and refs[1]["steps"] > 2 * refs[0]["steps"]
+    say("tiny batch with early finishers")
+    ctx = make_ctx(fc, B, P + N + 4 * W + 16, W)
+    res = {}
+    trigger = np.array([3, 14, 15], dtype=np.int32)
+    for compact in (1, 0):
+        ctx.set_option(35, compact)
+        ctx.prefill(prompts, lens, buf)
+        out = ctx.generate(N)
+        res[compact] = (out, ctx.state(), ctx.answer(trigger, 6))
+    for b in range(B):
+        assert (res[1][0]["ids"][b] == refs[b]["ids"]).all() and res[1][0]["steps"][b] == refs[b]["steps"], b
+        assert (res[1][0]["tail"][b] == refs[b]["tail"]).all()
+    for k in ("ids", "len", "steps", "tail"):
+        assert (res[1][0][k] == res[0][0][k]).all(), k
+    for k in ("n", "g", "done", "window"):
+        assert (res[1][1][k] == res[0][1][k]).all(), k
+    assert (res[1][2]["ids"] == res[0][2]["ids"]).all() and (res[1][2]["len"] == res[0][2]["len"]).all()
+
+
 def test_graph_and_eager_agree_and_are_deterministic(env):
     fc, om = env
     P, W, N = 16, 8, 32
