@@ -155,8 +155,9 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     // scale still to be applied by the consumer), attention output, hidden activations
     bool x_frag = false, att_frag = false, h_frag = false;
     const float* next_gain = nullptr;          // gain the next reduction folds into the fragments of x
-    // LM head: one winner per row and column block (16 n-tiles, or 4 with the narrow tiles)
-    const int lm_ncb = fc_gemm256_narrow(EPI_LMHEAD, M, kd.V / 16) ? (kd.V / 16 + 3) / 4 : (kd.V / 16 + 15) / 16;
+    // LM head: one winner per row and column block (16, 8 or 4 n-tiles)
+    const int lm_cw = fc_gemm256_cw(EPI_LMHEAD, M, kd.V / 16);
+    const int lm_ncb = (kd.V / 16 + 4 * lm_cw - 1) / (4 * lm_cw);
     big.amax_val = g.amax_val; big.amax_idx = (int32_t*)(g.amax_val + (size_t)lm_ncb * big.amax_stride);
     int gi = 0;        // which GEMM of the plan
     auto gemm = [&](int epi, const GemmPlan& pl, const void* W, int K, int N, const float* X, int ldx, const float* gain,

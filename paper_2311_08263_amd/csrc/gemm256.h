@@ -16,7 +16,7 @@ struct Gemm256Args {
     int32_t amax_stride;
     int32_t sk;            // K slices (RESID only when > 1: partial tiles to `part`, then added in slice order)
     float* part;           // [sk][M][NT*16] fp32
-    int32_t cw;            // n-tiles per wave: 0 = chosen from the shape, 1 or 4 = forced
+    int32_t cw;            // n-tiles per wave: 0 = chosen from the shape, 1, 2 or 4 = forced
     // Activations that arrive without their RMSNorm row scale (fragments written by fc_gemm256's own reduction,
     // see rf_AF): ssq [nssq][row tiles * 16] partial row sums of squares; the epilogue multiplies row m by
     // 1 / sqrt(sum_c ssq[c][m] / K + eps) before anything else.  NULL = the fragments are final.
@@ -29,7 +29,7 @@ struct Gemm256Args {
     bf16_t* rf_AF; const float* rf_gain; float* rf_ssq;
 };
 #define FC_GEMM256_MAX_SK 8
-bool fc_gemm256_narrow(int epi, int M, int NT);     // true: 64 x 64 tiles (few rows x few columns), else 64 x 256
+int fc_gemm256_cw(int epi, int M, int NT);          // n-tiles per wave the launcher picks: 4, 2 or 1 (64 x 256, 64 x 128, 64 x 64 tiles)
 int fc_gemm256_sk(int M, int K, int NT);   // slices that fill the chip for a matrix with few columns
 
 // X [M][ldx] fp32 -> AF; gain != NULL applies RMSNorm (fp32 statistics over the K inputs) first

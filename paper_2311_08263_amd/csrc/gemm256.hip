@@ -96,8 +96,8 @@ hipError_t fc_split(const float* X, int ldx, int M, int K, const float* gain, fl
 
 // ------------------------------------------------------------------ the GEMM
 // CW = n-tiles per wave: 4 (tiles of 64 rows x 256 columns) where that gives the chip enough workgroups,
-// 1 (64 x 64) for few rows x few columns, where the GEMM is still a weight stream and needs the
-// workgroups more than the reuse.
+// 2 or 1 (64 x 128, 64 x 64) for few rows x few columns, where the GEMM is still a weight stream and needs
+// the workgroups more than the reuse.
 template <int EPI, int CW>
 __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
     __shared__ u32x4_t stage[2][4][4][2][64];           // [buffer][k-tile][row tile][hi|lo][lane]: 2 x 32 KB
@@ -391,10 +391,17 @@ __global__ __launch_bounds__(512) void k_resid_reduce_split(const float* part, i
     }
 }
 
-// narrow tiles where the wide ones would give fewer than 200 workgroups and K cannot be split instead
-// (the residual GEMMs fill the chip with K slices, which keeps the reuse of the wide tile)
-bool fc_gemm256_narrow(int epi, int M, int NT) {
-    return epi != EPI_RESID && ((NT + 15) / 16) * (((M + 15) / 16 + 3) / 4) < 200;
+// n-tiles per wave: the widest tile (4, 2 or 1, i.e. 256, 128 or 64 columns per workgroup) that still gives about
+// two thirds of the CUs a workgroup; with fewer the GEMM, still a weight stream at these row counts, starves
+// (measured at the 7B shape, gate/up with 64 rows: 86 workgroups 69.9 us, 172 51.9 us, 344 63.1 us; with 128
+// rows: 172 workgroups 69.7 us, 344 77.6 us, 688 92.5 us).  The residual GEMMs fill the chip with K slices
+// instead, which keeps the reuse of the wide tile.
+int fc_gemm256_cw(int epi, int M, int NT) {
+    if (epi == EPI_RESID) return 4;
+    const int nrb = ((M + 15) / 16 + 3) / 4;
+    for (int cw = 4; cw > 1; cw >>= 1)
+        if (((NT + 4 * cw - 1) / (4 * cw)) * nrb >= 160) return cw;
+    return 1;
 }
 
 int fc_gemm256_sk(int M, int K, int NT) {
@@ -425,10 +432,10 @@ hipError_t fc_gemm256(int epi, const Gemm256Args& a, hipStream_t st) {
     if ((size_t)a.NT * 16 * a.K * 2 >= ((size_t)1 << 32) || (size_t)((a.M + 15) / 16) * 16 * a.K * 4 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
     // narrow tiles when wide ones would leave most of the chip idle
     const int nrb = ((a.M + 15) / 16 + 3) / 4;
-    const int cw = (fc_gemm256_narrow(epi, a.M, a.NT) && a.cw != 4) || a.cw == 1 ? 1 : 4;
+    const int cw = (a.cw == 1 || a.cw == 2 || a.cw == 4) ? a.cw : fc_gemm256_cw(epi, a.M, a.NT);
     const int units = ((a.NT + 4 * cw - 1) / (4 * cw)) * a.sk;
     dim3 grid((unsigned)((units + 7) / 8) * 8 * nrb);
-    hipError_t e = cw == 1 ? launch256<1>(epi, a, grid, st) : launch256<4>(epi, a, grid, st);
+    hipError_t e = cw == 1 ? launch256<1>(epi, a, grid, st) : (cw == 2 ? launch256<2>(epi, a, grid, st) : launch256<4>(epi, a, grid, st));
     if (e != hipSuccess) return e;
     if (a.sk > 1) {
         const size_t n = (size_t)a.M * (a.NT * 4);
