@@ -15,7 +15,7 @@ struct FastPlan {
     int32_t attn_splits;
     int32_t attn_bpw;  // key blocks of 32 per attention workgroup (decides at run time how many of the splits work)
     int32_t co_single; // column-owner GEMM: 1 = one weight batch in flight per wave, 0 = two, 2 = chosen per GEMM
-    int32_t co_sb[2][5];   // the per-GEMM choice (1 = one batch) for up to 16 rows [0] and 17..32 rows [1]: defaults
+    int32_t co_sb[2][5];   // the per-GEMM choice (1 = one batch, 0 = two, 2 = whole slice) for up to 16 rows [0] and 17..32 rows [1]: defaults
                            // from the 7B shape, replaced by fc_fast_tune's measurement on the actual shape
     int32_t co_rot[2][5];  // per-GEMM: walk the K batches in a per-wave rotated order (same defaults / measurement)
     int32_t ks[5];     // column-owner GEMM: K slices per owner (residual GEMMs only; 1 elsewhere)
@@ -46,7 +46,7 @@ void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t
 void fc_fast_plan(const KernelDims& kd, FastPlan* plan);
 hipError_t fc_fast_forward(const FastArgs& a);
 // Times every column-owner GEMM of the pass shape a.kd (at most 32 rows) with one and with two weight batches in
-// flight per wave, plain and rotated batch order and, for the residual GEMMs, 1, 2 or 4 K slices per owner, and
+// flight per wave or the wave's whole K slice at once, plain and rotated batch order and, for the residual GEMMs, 1, 2 or 4 K slices per owner, and
 // records the fastest combination in the plan.  Overwrites activations and layer 0's first cache rows:
 // call it before a prefill.  Synchronises the stream.
 hipError_t fc_fast_tune(FastArgs a, FastPlan* plan);

@@ -295,7 +295,8 @@ hipError_t fc_fast_tune(FastArgs a, FastPlan* plan) {
         a.tune_gi = gi;
         for (int ks = 1; ks <= (resid ? 4 : 1) && e == hipSuccess; ks *= 2)
             for (int rot = 0; rot < 2 && e == hipSuccess; ++rot)
-                for (int sb = 0; sb < 2 && e == hipSuccess; ++sb) {
+                for (int sb = 0; sb < 3 && e == hipSuccess; ++sb) {      // two batches, one batch, the whole slice at once
+                    if (sb == 2 && rot) continue;                          // (which has no batch order)
                     a.tune_ks = ks; a.tune_rot = rot; a.tune_sb = sb;
                     float t = 1e30f;
                     for (int rep = 0; rep < 3 && e == hipSuccess; ++rep) {

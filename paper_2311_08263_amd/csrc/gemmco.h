@@ -19,7 +19,8 @@ struct GemmCoArgs {
     float* xpart;          // ks > 1: partial tiles [workgroup][8 or 16 (more than 8 output tiles)][64 lanes][4]
     int32_t* xcnt;         // ks > 1: one arrival counter per owner, zero between launches
     int32_t rotate;        // walk the K batches in a per-wave rotated order (spreads the streams over the memory channels)
-    int32_t single_buffer; // one batch in flight per wave (fewer registers: two workgroups per CU) instead of two
+    int32_t single_buffer; // weights in flight per wave: 1 = one batch, 0 = two batches, 2 = the wave's whole K slice requested up front
+                           // (QKV and residual GEMMs, up to 16 rows, slices of at most 16 k-tiles per wave; else rejected)
 };
 
 // G workgroups = G / ks owners x ks K slices; owner i owns n-tiles [i*NT/owners, (i+1)*NT/owners), at most

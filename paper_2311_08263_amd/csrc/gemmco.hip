@@ -29,13 +29,15 @@ __device__ inline float up16(uint32_t b) { return __uint_as_float(b << 16); }
 
 // One batch = KB k-tiles: the wave's weight tiles for its n-tiles and its activation octets.
 template <int NW, int KB, int MT> struct Batch {
-    u32x4_t wt[NW][KB];
+    u32x4_t wt[KB][NW];
     float4 xa[KB][MT][2];
 };
 
 // NW * MT <= 16 output tiles per workgroup: after the K slices of the eight waves have met in LDS, wave
 // w finishes tiles ti = w and w + 8, tile ti = j * MT + mt (n-tile j of the workgroup, row tile mt).
-template <int EPI, int NW, int KB, bool DB, int MT>
+// KW > 0 selects the up-front variant for K slices of at most KW k-tiles per wave (see the main loop); KB and DB
+// are ignored then.
+template <int EPI, int NW, int KB, bool DB, int MT, int KW = 0>
 __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     extern __shared__ float lds[];
     constexpr int TW = NW * MT;                          // output tiles per workgroup
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
 #pragma unroll
             for (int j = 0; j < NW; ++j) {
                 const bool v = kv && nt0 + j < nt1;
-                b.wt[j][t] = __builtin_nontemporal_load(wbase + (v ? ((size_t)(nt0 + j) * KT + kt) * 64 : 0));
+                b.wt[t][j] = __builtin_nontemporal_load(wbase + (v ? ((size_t)(nt0 + j) * KT + kt) * 64 : 0));
             }
         }
 #pragma unroll
@@ -105,37 +107,40 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         for (int j = 0; j < NW; ++j) acc[j][mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
     }
 
+    // one k-tile: activations -> bf16 hi + lo fragments (row statistics on the way), then NW x MT x 2 MFMAs
+    auto ktile = [&](const u32x4_t (&wk)[NW], const float4 (&x)[MT][2], int kt, bool valid) {
+        const float keep = valid ? 1.0f : 0.0f;
+        const int kc = valid ? kt : kt_begin;
+        float4 g0, g1;
+        if (a.gain) { g0 = *(const float4*)(lds_gain + kc * 32 + 8 * g4); g1 = *(const float4*)(lds_gain + kc * 32 + 8 * g4 + 4); }
+        Frag hi[MT], lo[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            float v[8] = {x[mt][0].x, x[mt][0].y, x[mt][0].z, x[mt][0].w, x[mt][1].x, x[mt][1].y, x[mt][1].z, x[mt][1].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { v[e] *= keep; ss[mt] += v[e] * v[e]; }
+            if (a.gain) { v[0] *= g0.x; v[1] *= g0.y; v[2] *= g0.z; v[3] *= g0.w; v[4] *= g1.x; v[5] *= g1.y; v[6] *= g1.z; v[7] *= g1.w; }
+            uint32_t h[4], l[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) pk_bf16_hilo(v[2 * e], v[2 * e + 1], h[e], l[e]);
+            hi[mt].u = (u32x4_t){h[0], h[1], h[2], h[3]};
+            lo[mt].u = (u32x4_t){l[0], l[1], l[2], l[3]};
+        }
+#pragma unroll
+        for (int j = 0; j < NW; ++j) {
+            Frag wf; wf.u = wk[j];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, hi[mt].v, acc[j][mt], 0, 0, 0);
+                acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, lo[mt].v, acc[j][mt], 0, 0, 0);
+            }
+        }
+    };
     auto compute = [&](const Batch<NW, KB, MT>& b, int ib) {
 #pragma unroll
         for (int t = 0; t < KB; ++t) {
             const int kt = kt_begin + rot_batch(ib) * KB + t;
-            const float keep = (ib < nb && kt < kt_end) ? 1.0f : 0.0f;
-            const int kc = keep != 0.0f ? kt : kt_begin;
-            float4 g0, g1;
-            if (a.gain) { g0 = *(const float4*)(lds_gain + kc * 32 + 8 * g4); g1 = *(const float4*)(lds_gain + kc * 32 + 8 * g4 + 4); }
-            Frag hi[MT], lo[MT];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                float v[8] = {b.xa[t][mt][0].x, b.xa[t][mt][0].y, b.xa[t][mt][0].z, b.xa[t][mt][0].w,
-                              b.xa[t][mt][1].x, b.xa[t][mt][1].y, b.xa[t][mt][1].z, b.xa[t][mt][1].w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) { v[e] *= keep; ss[mt] += v[e] * v[e]; }
-                if (a.gain) { v[0] *= g0.x; v[1] *= g0.y; v[2] *= g0.z; v[3] *= g0.w; v[4] *= g1.x; v[5] *= g1.y; v[6] *= g1.z; v[7] *= g1.w; }
-                uint32_t h[4], l[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) pk_bf16_hilo(v[2 * e], v[2 * e + 1], h[e], l[e]);
-                hi[mt].u = (u32x4_t){h[0], h[1], h[2], h[3]};
-                lo[mt].u = (u32x4_t){l[0], l[1], l[2], l[3]};
-            }
-#pragma unroll
-            for (int j = 0; j < NW; ++j) {
-                Frag wf; wf.u = b.wt[j][t];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, hi[mt].v, acc[j][mt], 0, 0, 0);
-                    acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, lo[mt].v, acc[j][mt], 0, 0, 0);
-                }
-            }
+            ktile(b.wt[t], b.xa[t], kt, ib < nb && kt < kt_end);
         }
     };
 
@@ -168,6 +173,48 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         }
     }
 
+    if constexpr (KW > 0) {
+        // Up-front variant for short K slices (at most KW k-tiles per wave): the wave requests its weights at
+        // once, as many k-tiles as 28-32 fragments of registers hold (KA), and refills the slot of a k-tile that
+        // has been used with the k-tile KA further on; the slice then costs about one memory round trip instead
+        // of one per batch.  Activations (L2 hits) travel one k-tile ahead.  (A ring of the same depth with a
+        // run-time trip count, with or without the activations travelling in the ring, was no faster than the
+        // batches: what pays is the burst at the start of the kernel.)
+        constexpr int FR = EPI == EPI_QKV ? 28 : 32;       // (the QKV epilogue keeps its rotary factors in registers too)
+        constexpr int KA = NW * KW <= FR ? KW : FR / NW;
+        u32x4_t wt[KA][NW];
+        auto wload = [&](u32x4_t (&wk)[NW], int t) {
+            const int kt = kt_begin + t;
+#pragma unroll
+            for (int j = 0; j < NW; ++j) {
+                const bool v = kt < kt_end && nt0 + j < nt1;
+                wk[j] = __builtin_nontemporal_load(wbase + (v ? ((size_t)(nt0 + j) * KT + kt) * 64 : 0));
+            }
+        };
+#pragma unroll
+        for (int t = 0; t < KA; ++t) wload(wt[t], t);
+        if (a.gain) {       // the norm gain goes through LDS once per workgroup
+            for (int i = tid * 4; i < a.K; i += 512 * 4) *(float4*)(lds_gain + i) = *(const float4*)(a.gain + i);
+            __syncthreads();
+        }
+        float4 xa[2][MT][2];
+        auto xload = [&](float4 (&x)[MT][2], int t) {
+            const int kt = kt_begin + t, kc = kt < kt_end ? kt : kt_begin;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                x[mt][0] = *(const float4*)(xr[mt] + kc * 32);
+                x[mt][1] = *(const float4*)(xr[mt] + kc * 32 + 4);
+            }
+        };
+        xload(xa[0], 0);
+#pragma unroll
+        for (int t = 0; t < KW; ++t) {
+            if (t + 1 < KW) xload(xa[(t + 1) & 1], t + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            ktile(wt[t % KA], xa[t & 1], kt_begin + t, kt_begin + t < kt_end);
+            if (t + KA < KW) wload(wt[t % KA], t + KA);
+        }
+    } else {
     // two batches in flight per wave: the next one is requested before the current one is used
     // (DB = false keeps one batch per wave in flight and fewer registers, so that two workgroups
     // share a CU and overlap each other's phases instead)
@@ -197,6 +244,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
             compute(A, ib);
             load(A, ib + 1);
         }
+    }
     }
 
     // the eight K slices meet in LDS, in two rounds so that four partial sets (4 x TW KB) are enough: waves
@@ -412,23 +460,50 @@ int fc_gemmco_most(int M, int K, bool gain) {
     return 1;
 }
 
-template <int EPI, int NW, int KB, bool DB, int MT>
+template <int EPI, int NW, int KB, bool DB, int MT, int KW = 0>
 static hipError_t launch_k(const GemmCoArgs& a, int G, hipStream_t st) {
     const size_t lds = co_lds_bytes(NW, MT, a.K, a.gain != nullptr);
     static bool raised = false;
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_gemmco<EPI, NW, KB, DB, MT>, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        hipError_t e = hipFuncSetAttribute((const void*)k_gemmco<EPI, NW, KB, DB, MT, KW>, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
         if (e != hipSuccess) return e;
         raised = true;
     }
     if (lds > 150 * 1024) return hipErrorInvalidValue;
-    k_gemmco<EPI, NW, KB, DB, MT><<<G, 512, lds, st>>>(a);
+    k_gemmco<EPI, NW, KB, DB, MT, KW><<<G, 512, lds, st>>>(a);
     return hipGetLastError();
+}
+// up-front variant: QKV and the residual GEMMs, up to 16 rows, K slices of at most 16 k-tiles per wave
+template <int EPI>
+static hipError_t launch_deep(const GemmCoArgs& a, int G, int nw, hipStream_t st) {
+    if constexpr (EPI == EPI_QKV || EPI == EPI_RESID) {
+        const int ks = a.ks > 1 ? a.ks : 1, KT = a.K >> 5;
+        const int kw = ((KT + ks - 1) / ks + 7) / 8;          // most k-tiles any wave owns
+        if (a.M > 16 || nw < 1) return hipErrorInvalidValue;
+        if (kw <= 8) switch (nw) {
+            case 1: return launch_k<EPI, 1, 1, false, 1, 8>(a, G, st);
+            case 2: return launch_k<EPI, 2, 1, false, 1, 8>(a, G, st);
+            case 3: return launch_k<EPI, 3, 1, false, 1, 8>(a, G, st);
+            case 4: return launch_k<EPI, 4, 1, false, 1, 8>(a, G, st);
+            case 5: case 6: return launch_k<EPI, 6, 1, false, 1, 8>(a, G, st);
+        } else if (kw <= 12) switch (nw) {
+            case 1: return launch_k<EPI, 1, 1, false, 1, 12>(a, G, st);
+            case 2: return launch_k<EPI, 2, 1, false, 1, 12>(a, G, st);
+            case 3: return launch_k<EPI, 3, 1, false, 1, 12>(a, G, st);
+            case 4: return launch_k<EPI, 4, 1, false, 1, 12>(a, G, st);
+        } else if (kw <= 16) switch (nw) {
+            case 1: return launch_k<EPI, 1, 1, false, 1, 16>(a, G, st);
+            case 2: return launch_k<EPI, 2, 1, false, 1, 16>(a, G, st);
+            case 3: return launch_k<EPI, 3, 1, false, 1, 16>(a, G, st);
+        }
+    }
+    return hipErrorInvalidValue;
 }
 template <int EPI>
 static hipError_t launch_epi(const GemmCoArgs& a, int G, hipStream_t st) {
     const int owners = G / (a.ks > 1 ? a.ks : 1);
     const int nw = (a.NT + owners - 1) / owners;  // most n-tiles any workgroup owns
+    if (a.single_buffer == 2) return launch_deep<EPI>(a, G, nw, st);
     if (a.M > 16 && !a.single_buffer) {           // two row tiles, two batches in flight
         switch (nw) {
             case 1: return launch_k<EPI, 1, 2, true, 2>(a, G, st);
