@@ -11,6 +11,8 @@ struct AttnArgs {
     const int32_t* n_state;   // committed length per sequence
     float* out;            // [rows][ldo], head h at column h*128 (may be NULL when ofrag is given)
     int32_t ldo;
+    int32_t subrows;       // rows per workgroup: 0 = 32 where the window has more than 16 rows (two query tiles per workgroup),
+                           // 16 = always one query tile (windows of 17..32 rows as two units that read K/V separately)
     bf16_t* ofrag;         // not NULL: the output also as bf16 hi + lo B-fragments [row tile][H*128/32][hi|lo][64][8],
                            // the layout the many-row O projection reads
     float* part;           // split partials

@@ -39,13 +39,14 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
     extern __shared__ float lds[];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int lm = lane & 15, g = lane >> 4;
-    // a window of more than 32 rows is cut into sub-windows of 32: sub-window `sub` of a sequence is a
+    // a window of more rows than a workgroup takes (16 per query tile) is cut into sub-windows: sub-window `sub` of a sequence is a
     // unit of its own whose rows see the committed positions plus the window rows up to their own (the
     // K/V of all window rows are already in the cache when this kernel starts)
-    const int nsub = (a.W + 31) >> 5;
+    constexpr int SUBR = 16 * QT;                            // rows of a unit
+    const int nsub = (a.W + SUBR - 1) / SUBR;
     const int bh = blockIdx.x, h = bh % a.H, sub = (bh / a.H) % nsub, b = bh / (a.H * nsub), kvh = h / (a.H / a.Hkv);
     const int sp = blockIdx.y, nsp_max = gridDim.y;
-    const int row0 = 32 * sub, Wr = a.W - row0 < 32 ? a.W - row0 : 32;      // rows of this unit
+    const int row0 = SUBR * sub, Wr = a.W - row0 < SUBR ? a.W - row0 : SUBR;      // rows of this unit
     const int n = a.n_state[b] + row0;                       // positions every row of the unit sees
     int T = n + Wr;
     if (T > a.S) T = a.S;                                    // capacity guard (the host checks first)
@@ -320,13 +321,13 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
     }
 }
 
-size_t fc_attn16_part_bytes(int BH, int nsplit, int W) {
-    const int QT = W > 16 ? 2 : 1, nsub = (W + 31) / 32;
-    return (size_t)BH * nsub * nsplit * QT * PART_FLOATS * 4;
+size_t fc_attn16_part_bytes(int BH, int nsplit, int W) {      // covers both unit sizes
+    const int tiles = W > 16 ? 2 * ((W + 31) / 32) : 1;
+    return (size_t)BH * tiles * nsplit * PART_FLOATS * 4;
 }
 
 hipError_t fc_attn16(const AttnArgs& a, int Bact, int nsplit, hipStream_t st) {
-    const int nsub = (a.W + 31) / 32;
+    const int QT = a.W > 16 && a.subrows != 16 ? 2 : 1, nsub = (a.W + 16 * QT - 1) / (16 * QT);
     if (a.W < 1 || nsplit < 1 || nsplit > FC_MAX_ATTN_SPLITS || Bact * nsub * a.H > FC_MAX_COUNTERS || a.S < 32 || a.S % 32 || a.bpw < 1)
         return hipErrorInvalidValue;
     dim3 grid(Bact * nsub * a.H, nsplit);
@@ -339,10 +340,10 @@ hipError_t fc_attn16(const AttnArgs& a, int Bact, int nsplit, hipStream_t st) {
         lds_ok = true;
     }
     if (a.kvp == 2) {
-        if (a.W > 16) k_attn16<2, 2><<<grid, 256, l2, st>>>(a);
+        if (QT == 2) k_attn16<2, 2><<<grid, 256, l2, st>>>(a);
         else k_attn16<1, 2><<<grid, 256, l1, st>>>(a);
     } else if (a.kvp == 1) {
-        if (a.W > 16) k_attn16<2, 1><<<grid, 256, l2, st>>>(a);
+        if (QT == 2) k_attn16<2, 1><<<grid, 256, l2, st>>>(a);
         else k_attn16<1, 1><<<grid, 256, l1, st>>>(a);
     } else return hipErrorInvalidValue;
     return hipGetLastError();
