@@ -233,13 +233,14 @@ hipError_t fc_fast_forward(const FastArgs& a) {
             at.ofrag = af_att; att_frag = true;
             at.out = a.dbg_stop >= 0 ? att : nullptr;
         }
-        // windows of 17..32 rows at a small batch: two workgroups of one query tile each instead of one with two
+        // windows of more than 16 rows at a small batch: workgroups of one query tile each instead of two
         // (they read K/V twice, which costs nothing while the launch is latency-bound: 7B, 32 rows, 17.4 -> 13.9 us)
         int attn_splits = a.plan->attn_splits;
         at.subrows = 0;
-        if (kd.W > 16 && kd.W <= 32 && a.Bact * kd.H * 2 <= fc_num_cus()) {
+        const int units16 = (kd.W + 15) / 16;
+        if (kd.W > 16 && a.Bact * kd.H * units16 <= fc_num_cus()) {
             at.subrows = 16;
-            while (attn_splits > 1 && a.Bact * kd.H * 2 * attn_splits > fc_num_cus()) --attn_splits;
+            while (attn_splits > 1 && a.Bact * kd.H * units16 * attn_splits > fc_num_cus()) --attn_splits;
         }
         FLAUNCH(KK_ATTN, fc_attn16(at, a.Bact, attn_splits, a.st));
         DBG_STOP();
