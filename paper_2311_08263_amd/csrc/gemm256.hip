@@ -22,6 +22,7 @@
 // k_split prepares the activations: optional RMSNorm (row statistics in fp32, gain applied), then
 // bf16 hi + lo, stored in B-fragment order [row tile][k-tile][hi|lo][lane][8].
 #include "gemm256.h"
+#include "gemmco.h"      // fc_num_cus
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
@@ -404,10 +405,16 @@ int fc_gemm256_cw(int epi, int M, int NT) {
     return 1;
 }
 
+// K slices for a matrix with few columns: as many as give every CU at most one workgroup (measured at 256 rows,
+// 13B O / down: 240 workgroups 41 / 77 us, 480 workgroups 46 / 81 us, 320 workgroups 50 / 99 us; 7B prefill of
+// 256 rows: 256 workgroups 9.4 ms, 384 10.0 ms, 512 9.9 ms: a second workgroup on a CU gains little and the
+// partial tiles cost); where one per CU would leave a quarter of the CUs idle, about two per CU instead
 int fc_gemm256_sk(int M, int K, int NT) {
     const int nwg = ((NT + 15) / 16) * (((M + 15) / 16 + 3) / 4), NS = K / 128;
     if (nwg >= 200) return 1;
-    int sk = (480 + nwg - 1) / nwg;
+    const int cus = fc_num_cus();
+    int sk = cus / nwg;
+    if (sk < 1 || nwg * sk < (3 * cus) / 4) sk = (2 * cus - 32 + nwg - 1) / nwg;
     if (sk > FC_GEMM256_MAX_SK) sk = FC_GEMM256_MAX_SK;
     if (sk > NS / 2) sk = NS / 2;
     return sk < 1 ? 1 : sk;
