@@ -99,11 +99,16 @@ hipError_t fc_split(const float* X, int ldx, int M, int K, const float* gain, fl
 // CW = n-tiles per wave: 4 (tiles of 64 rows x 256 columns) where that gives the chip enough workgroups,
 // 2 or 1 (64 x 128, 64 x 64) for few rows x few columns, where the GEMM is still a weight stream and needs
 // the workgroups more than the reuse.
-template <int EPI, int CW>
-__global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
+// KG = 2: eight waves per workgroup, two groups of four that take the even and the odd k-tiles of every stage
+// (each wave still its 4 x CW tiles) and add their accumulators through LDS at the end.  One such workgroup per
+// CU does what two four-wave workgroups of different tiles would, with one activation stage for both groups;
+// used where the launch has no more workgroups than CUs anyway.
+template <int EPI, int CW, int KG>
+__global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void k_gemm256(Gemm256Args a) {
     __shared__ u32x4_t stage[2][4][4][2][64];           // [buffer][k-tile][row tile][hi|lo][lane]: 2 x 32 KB
-    __shared__ float rowpart[4][64];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    __shared__ float rowpart[4 * KG][64];
+    constexpr int NTH = 256 * KG, SL = 8 / KG;           // threads, 16-byte stage loads per thread
+    const int tid = threadIdx.x, lane = tid & 63, w = (tid >> 6) & 3, kg = tid >> 8, w8 = tid >> 6;
     const int lm = lane & 15, g4 = lane >> 4;
     const int KT = a.K >> 5, NS = KT >> 2, MT = (a.M + 15) >> 4;
     // id -> (XCD x, sequence number q on that XCD) -> row block q % nrb of unit 8 * (q / nrb) + x
@@ -119,23 +124,23 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
     // (scalar registers, advanced per stage) plus a per-thread 32-bit byte offset fixed for the whole kernel:
     // no 64-bit vector arithmetic in the loop.
     const char* AFb = (const char*)a.AF;
-    uint32_t aoff[8];
+    uint32_t aoff[SL];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int idx = tid + 256 * i, f = idx >> 6, ln = idx & 63;
+    for (int i = 0; i < SL; ++i) {
+        const int idx = tid + NTH * i, f = idx >> 6, ln = idx & 63;
         const int ktl = f >> 3, mtl = (f >> 1) & 3, part = f & 1;
         const int mt = mt0 + mtl < MT ? mt0 + mtl : MT - 1;
         aoff[i] = ((((uint32_t)mt * KT + ktl) * 2 + part) * 64 + ln) * 16;
     }
-    auto stage_load = [&](u32x4_t (&r)[8], int s) {
+    auto stage_load = [&](u32x4_t (&r)[SL], int s) {
         const char* base = AFb + (size_t)s * 8192;            // 4 k-tiles x (hi, lo) x 1 KB
 #pragma unroll
-        for (int i = 0; i < 8; ++i) r[i] = *(const u32x4_t*)(base + aoff[i]);
+        for (int i = 0; i < SL; ++i) r[i] = *(const u32x4_t*)(base + aoff[i]);
     };
-    auto stage_store = [&](const u32x4_t (&r)[8], int buf) {
+    auto stage_store = [&](const u32x4_t (&r)[SL], int buf) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int idx = tid + 256 * i, f = idx >> 6, ln = idx & 63;
+        for (int i = 0; i < SL; ++i) {
+            const int idx = tid + NTH * i, f = idx >> 6, ln = idx & 63;
             stage[buf][f >> 3][(f >> 1) & 3][f & 1][ln] = r[i];
         }
     };
@@ -159,10 +164,11 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
 #pragma unroll
         for (int m = 0; m < 4; ++m) acc[j][m] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
-    u32x4_t sr[8];
-    u32x4_t W0[CW], W1[CW], W2[CW], W3[CW];
+    u32x4_t sr[SL];
+    u32x4_t W0[CW], W1[CW], W2[CW], W3[CW];              // KG = 2: W0, W1 hold k-tiles kg and kg + 2 of a stage
     stage_load(sr, s_lo);
-    wload(W0, 4 * s_lo); wload(W1, 4 * s_lo + 1); wload(W2, 4 * s_lo + 2); wload(W3, 4 * s_lo + 3);
+    if (KG == 1) { wload(W0, 4 * s_lo); wload(W1, 4 * s_lo + 1); wload(W2, 4 * s_lo + 2); wload(W3, 4 * s_lo + 3); }
+    else { wload(W0, 4 * s_lo + kg); wload(W1, 4 * s_lo + kg + 2); }
     stage_store(sr, 0);
     if (a.ssq) {
         // row statistics of the 64 rows (activations that come without their norm scale): wave w adds every
@@ -171,8 +177,8 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
         const int row = mt0 * 16 + lane < MP ? mt0 * 16 + lane : MP - 1;
         float ssum = 0.f;
 #pragma unroll 8
-        for (int c = w; c < a.nssq; c += 4) ssum += a.ssq[(size_t)c * MP + row];
-        rowpart[w][lane] = ssum;
+        for (int c = w8; c < a.nssq; c += 4 * KG) ssum += a.ssq[(size_t)c * MP + row];
+        rowpart[w8][lane] = ssum;
     }
     __syncthreads();
 
@@ -195,16 +201,41 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
     for (int s = s_lo; s < s_hi; ++s) {
         stage_load(sr, s + 1 < s_hi ? s + 1 : s);        // next stage's activations travel while this one is used
         __builtin_amdgcn_sched_barrier(0);               // (left alone the scheduler sinks all loads to the end of the stage)
-        STEP(W0, 0);
-        STEP(W1, 1);
-        STEP(W2, 2);
-        STEP(W3, 3);
+        if (KG == 1) {
+            STEP(W0, 0);
+            STEP(W1, 1);
+            STEP(W2, 2);
+            STEP(W3, 3);
+        } else {
+            STEP(W0, kg);
+            STEP(W1, kg + 2);
+        }
         stage_store(sr, buf ^ 1);
         __syncthreads();
         buf ^= 1;
     }
 #undef STEP
 
+    if (KG == 2) {
+        // the two k-groups meet: group 1 publishes its accumulators (16 KB per wave: exactly the stage buffers,
+        // free after the loop's last barrier), group 0 adds them and runs the epilogue alone
+        f32x4_t* red = (f32x4_t*)&stage[0][0][0][0][0];
+        if (kg == 1) {
+#pragma unroll
+            for (int j = 0; j < CW; ++j)
+#pragma unroll
+                for (int m = 0; m < 4; ++m) red[((w * 4 + j) * 4 + m) * 64 + lane] = acc[j][m];
+        }
+        __syncthreads();
+        if (kg == 0) {
+#pragma unroll
+            for (int j = 0; j < CW; ++j)
+#pragma unroll
+                for (int m = 0; m < 4; ++m) acc[j][m] += red[((w * 4 + j) * 4 + m) * 64 + lane];
+        }
+        __syncthreads();
+    }
+    const bool act = kg == 0;                            // waves that store results
     // ---- epilogue: acc[j][m]: rows (mt0 + m) * 16 + lm, columns (nt0 + j) * 16 + 4 * g4 + r
     float best[4]; int bidx[4];
     float rscale[4];
@@ -214,13 +245,16 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
         rscale[m] = 1.0f;
         if (EPI != EPI_RESID && a.ssq) {
             const int r = m * 16 + lm;
-            rscale[m] = 1.0f / sqrtf((rowpart[0][r] + rowpart[1][r] + rowpart[2][r] + rowpart[3][r]) / (float)a.K + a.eps);
+            float ssum = 0.f;
+#pragma unroll
+            for (int q = 0; q < 4 * KG; ++q) ssum += rowpart[q][r];
+            rscale[m] = 1.0f / sqrtf(ssum / (float)a.K + a.eps);
         }
     }
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         const int row = (mt0 + m) * 16 + lm;
-        const bool rok = mt0 + m < MT && row < a.M;
+        const bool rok = act && mt0 + m < MT && row < a.M;
 #pragma unroll
         for (int j = 0; j < CW; ++j) {
             const int nt = nt0 + j;
@@ -320,7 +354,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm256(Gemm256Args a) {
                 const float ov = __shfl_xor(best[m], o, 64); const int oi = __shfl_xor(bidx[m], o, 64);
                 if (ov > best[m] || (ov == best[m] && oi < bidx[m])) { best[m] = ov; bidx[m] = oi; }
             }
-            if (g4 == 0) { amv[w][m * 16 + lm] = best[m]; ami[w][m * 16 + lm] = bidx[m]; }
+            if (g4 == 0 && act) { amv[w][m * 16 + lm] = best[m]; ami[w][m * 16 + lm] = bidx[m]; }
         }
         __syncthreads();
         if (tid < 64) {
@@ -420,13 +454,13 @@ int fc_gemm256_sk(int M, int K, int NT) {
     return sk < 1 ? 1 : sk;
 }
 
-template <int CW>
+template <int CW, int KG>
 static hipError_t launch256(int epi, const Gemm256Args& a, dim3 grid, hipStream_t st) {
     switch (epi) {
-        case EPI_RESID: k_gemm256<EPI_RESID, CW><<<grid, 256, 0, st>>>(a); break;
-        case EPI_SWIGLU: k_gemm256<EPI_SWIGLU, CW><<<grid, 256, 0, st>>>(a); break;
-        case EPI_QKV: k_gemm256<EPI_QKV, CW><<<grid, 256, 0, st>>>(a); break;
-        case EPI_LMHEAD: k_gemm256<EPI_LMHEAD, CW><<<grid, 256, 0, st>>>(a); break;
+        case EPI_RESID: k_gemm256<EPI_RESID, CW, KG><<<grid, 256 * KG, 0, st>>>(a); break;
+        case EPI_SWIGLU: k_gemm256<EPI_SWIGLU, CW, KG><<<grid, 256 * KG, 0, st>>>(a); break;
+        case EPI_QKV: k_gemm256<EPI_QKV, CW, KG><<<grid, 256 * KG, 0, st>>>(a); break;
+        case EPI_LMHEAD: k_gemm256<EPI_LMHEAD, CW, KG><<<grid, 256 * KG, 0, st>>>(a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -442,7 +476,11 @@ hipError_t fc_gemm256(int epi, const Gemm256Args& a, hipStream_t st) {
     const int cw = (a.cw == 1 || a.cw == 2 || a.cw == 4) ? a.cw : fc_gemm256_cw(epi, a.M, a.NT);
     const int units = ((a.NT + 4 * cw - 1) / (4 * cw)) * a.sk;
     dim3 grid((unsigned)((units + 7) / 8) * 8 * nrb);
-    hipError_t e = cw == 1 ? launch256<1>(epi, a, grid, st) : (cw == 2 ? launch256<2>(epi, a, grid, st) : launch256<4>(epi, a, grid, st));
+    // eight waves per workgroup where every CU gets at most one workgroup anyway
+    const bool kg2 = units * nrb <= fc_num_cus() && a.K >= 512;      // (13B batch-8 step: 16.66 -> 16.36 ms)
+    hipError_t e;
+    if (kg2) e = cw == 1 ? launch256<1, 2>(epi, a, grid, st) : (cw == 2 ? launch256<2, 2>(epi, a, grid, st) : launch256<4, 2>(epi, a, grid, st));
+    else e = cw == 1 ? launch256<1, 1>(epi, a, grid, st) : (cw == 2 ? launch256<2, 1>(epi, a, grid, st) : launch256<4, 1>(epi, a, grid, st));
     if (e != hipSuccess) return e;
     if (a.sk > 1) {
         const size_t n = (size_t)a.M * (a.NT * 4);
