@@ -157,7 +157,8 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     const float* next_gain = nullptr;          // gain the next reduction folds into the fragments of x
     // LM head: one winner per row and column block (16, 8 or 4 n-tiles)
     const int lm_cw = fc_gemm256_cw(EPI_LMHEAD, M, kd.V / 16);
-    const int lm_ncb = (kd.V / 16 + 4 * lm_cw - 1) / (4 * lm_cw);
+    const int lm_cols = (fc_gemm256_mode(EPI_LMHEAD, M, d, kd.V / 16, 1, lm_cw) == 3 ? 8 : 4) * lm_cw;
+    const int lm_ncb = (kd.V / 16 + lm_cols - 1) / lm_cols;
     big.amax_val = g.amax_val; big.amax_idx = (int32_t*)(g.amax_val + (size_t)lm_ncb * big.amax_stride);
     int gi = 0;        // which GEMM of the plan
     auto gemm = [&](int epi, const GemmPlan& pl, const void* W, int K, int N, const float* X, int ldx, const float* gain,

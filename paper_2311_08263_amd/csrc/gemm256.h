@@ -30,6 +30,7 @@ struct Gemm256Args {
 };
 #define FC_GEMM256_MAX_SK 8
 int fc_gemm256_cw(int epi, int M, int NT);          // n-tiles per wave the launcher picks: 4, 2 or 1 (64 x 256, 64 x 128, 64 x 64 tiles)
+int fc_gemm256_mode(int epi, int M, int K, int NT, int sk, int cw);   // 1, 2 or 3: see gemm256.hip; 3 doubles the columns per workgroup
 int fc_gemm256_sk(int M, int K, int NT);   // slices that fill the chip for a matrix with few columns
 
 // X [M][ldx] fp32 -> AF; gain != NULL applies RMSNorm (fp32 statistics over the K inputs) first

@@ -103,21 +103,27 @@ hipError_t fc_split(const float* X, int ldx, int M, int K, const float* gain, fl
 // (each wave still its 4 x CW tiles) and add their accumulators through LDS at the end.  One such workgroup per
 // CU does what two four-wave workgroups of different tiles would, with one activation stage for both groups;
 // used where the launch has no more workgroups than CUs anyway.
+// KG = 3: eight waves per workgroup, two groups of four that take neighbouring column blocks (a tile of 64 rows x
+// 128 * CW columns) and share the activation stage; used where that brings the launch down to one workgroup per
+// CU (with four waves two workgroups would share a CU, each staging the same activations).
 template <int EPI, int CW, int KG>
-__global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void k_gemm256(Gemm256Args a) {
+__global__ __launch_bounds__(KG == 1 ? 256 : 512, KG == 1 ? 2 : 1) void k_gemm256(Gemm256Args a) {
     __shared__ u32x4_t stage[2][4][4][2][64];           // [buffer][k-tile][row tile][hi|lo][lane]: 2 x 32 KB
-    __shared__ float rowpart[4 * KG][64];
-    constexpr int NTH = 256 * KG, SL = 8 / KG;           // threads, 16-byte stage loads per thread
+    constexpr bool KSPLIT = KG == 2, CSPLIT = KG == 3;
+    constexpr int NWV = KG == 1 ? 4 : 8;                 // waves
+    __shared__ float rowpart[NWV][64];
+    constexpr int NTH = 64 * NWV, SL = 32 / NWV;         // threads, 16-byte stage loads per thread
     const int tid = threadIdx.x, lane = tid & 63, w = (tid >> 6) & 3, kg = tid >> 8, w8 = tid >> 6;
     const int lm = lane & 15, g4 = lane >> 4;
     const int KT = a.K >> 5, NS = KT >> 2, MT = (a.M + 15) >> 4;
     // id -> (XCD x, sequence number q on that XCD) -> row block q % nrb of unit 8 * (q / nrb) + x
-    const int nrb = (MT + 3) >> 2, ncb = (a.NT + 4 * CW - 1) / (4 * CW);
+    constexpr int WCOLS = CSPLIT ? 8 * CW : 4 * CW;      // n-tiles per workgroup
+    const int nrb = (MT + 3) >> 2, ncb = (a.NT + WCOLS - 1) / WCOLS;
     const int xq = blockIdx.x >> 3, unit = (xq / nrb) * 8 + (blockIdx.x & 7), rb = xq % nrb;
     if (unit >= ncb * a.sk) return;                      // grid padding (whole workgroup leaves together)
     const int cb = unit / a.sk, ks = unit % a.sk;
     const int s_lo = (int)((unsigned)NS * (unsigned)ks / (unsigned)a.sk), s_hi = (int)((unsigned)NS * (unsigned)(ks + 1) / (unsigned)a.sk);
-    const int nt0 = cb * (4 * CW) + CW * w;              // this wave's CW n-tiles
+    const int nt0 = cb * WCOLS + CW * (CSPLIT ? w8 : w);      // this wave's CW n-tiles
     const int mt0 = rb * 4;
 
     // stage copy: 32 fragments of 1 KB per stage, 8 x 16 bytes per thread.  Addresses are a uniform 64-bit base
@@ -167,7 +173,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void k_gemm256(Gemm256Ar
     u32x4_t sr[SL];
     u32x4_t W0[CW], W1[CW], W2[CW], W3[CW];              // KG = 2: W0, W1 hold k-tiles kg and kg + 2 of a stage
     stage_load(sr, s_lo);
-    if (KG == 1) { wload(W0, 4 * s_lo); wload(W1, 4 * s_lo + 1); wload(W2, 4 * s_lo + 2); wload(W3, 4 * s_lo + 3); }
+    if (!KSPLIT) { wload(W0, 4 * s_lo); wload(W1, 4 * s_lo + 1); wload(W2, 4 * s_lo + 2); wload(W3, 4 * s_lo + 3); }
     else { wload(W0, 4 * s_lo + kg); wload(W1, 4 * s_lo + kg + 2); }
     stage_store(sr, 0);
     if (a.ssq) {
@@ -177,7 +183,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void k_gemm256(Gemm256Ar
         const int row = mt0 * 16 + lane < MP ? mt0 * 16 + lane : MP - 1;
         float ssum = 0.f;
 #pragma unroll 8
-        for (int c = w8; c < a.nssq; c += 4 * KG) ssum += a.ssq[(size_t)c * MP + row];
+        for (int c = w8; c < a.nssq; c += NWV) ssum += a.ssq[(size_t)c * MP + row];
         rowpart[w8][lane] = ssum;
     }
     __syncthreads();
@@ -201,7 +207,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void k_gemm256(Gemm256Ar
     for (int s = s_lo; s < s_hi; ++s) {
         stage_load(sr, s + 1 < s_hi ? s + 1 : s);        // next stage's activations travel while this one is used
         __builtin_amdgcn_sched_barrier(0);               // (left alone the scheduler sinks all loads to the end of the stage)
-        if (KG == 1) {
+        if (!KSPLIT) {
             STEP(W0, 0);
             STEP(W1, 1);
             STEP(W2, 2);
@@ -216,7 +222,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void k_gemm256(Gemm256Ar
     }
 #undef STEP
 
-    if (KG == 2) {
+    if (KSPLIT) {
         // the two k-groups meet: group 1 publishes its accumulators (16 KB per wave: exactly the stage buffers,
         // free after the loop's last barrier), group 0 adds them and runs the epilogue alone
         f32x4_t* red = (f32x4_t*)&stage[0][0][0][0][0];
@@ -235,7 +241,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void k_gemm256(Gemm256Ar
         }
         __syncthreads();
     }
-    const bool act = kg == 0;                            // waves that store results
+    const bool act = !KSPLIT || kg == 0;                 // waves that store results
     // ---- epilogue: acc[j][m]: rows (mt0 + m) * 16 + lm, columns (nt0 + j) * 16 + 4 * g4 + r
     float best[4]; int bidx[4];
     float rscale[4];
@@ -247,7 +253,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void k_gemm256(Gemm256Ar
             const int r = m * 16 + lm;
             float ssum = 0.f;
 #pragma unroll
-            for (int q = 0; q < 4 * KG; ++q) ssum += rowpart[q][r];
+            for (int q = 0; q < NWV; ++q) ssum += rowpart[q][r];
             rscale[m] = 1.0f / sqrtf(ssum / (float)a.K + a.eps);
         }
     }
@@ -354,12 +360,12 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void k_gemm256(Gemm256Ar
                 const float ov = __shfl_xor(best[m], o, 64); const int oi = __shfl_xor(bidx[m], o, 64);
                 if (ov > best[m] || (ov == best[m] && oi < bidx[m])) { best[m] = ov; bidx[m] = oi; }
             }
-            if (g4 == 0 && act) { amv[w][m * 16 + lm] = best[m]; ami[w][m * 16 + lm] = bidx[m]; }
+            if (g4 == 0 && act) { amv[CSPLIT ? w8 : w][m * 16 + lm] = best[m]; ami[CSPLIT ? w8 : w][m * 16 + lm] = bidx[m]; }
         }
         __syncthreads();
         if (tid < 64) {
             float bv = amv[0][tid]; int bx = ami[0][tid];
-            for (int q = 1; q < 4; ++q)
+            for (int q = 1; q < (CSPLIT ? 8 : 4); ++q)
                 if (amv[q][tid] > bv || (amv[q][tid] == bv && ami[q][tid] < bx)) { bv = amv[q][tid]; bx = ami[q][tid]; }
             const int row = mt0 * 16 + tid;
             if (row < a.M) {
@@ -443,6 +449,17 @@ int fc_gemm256_cw(int epi, int M, int NT) {
 // 13B O / down: 240 workgroups 41 / 77 us, 480 workgroups 46 / 81 us, 320 workgroups 50 / 99 us; 7B prefill of
 // 256 rows: 256 workgroups 9.4 ms, 384 10.0 ms, 512 9.9 ms: a second workgroup on a CU gains little and the
 // partial tiles cost); where one per CU would leave a quarter of the CUs idle, about two per CU instead
+// workgroup shape: 1 = four waves; 2 = eight waves in two k-groups, where the launch has at most one workgroup
+// per CU anyway; 3 = eight waves over two neighbouring column blocks, where that brings it down to one per CU
+int fc_gemm256_mode(int epi, int M, int K, int NT, int sk, int cw) {
+    (void)epi;
+    const int nrb = ((M + 15) / 16 + 3) / 4, cus = fc_num_cus();
+    if (K < 512) return 1;
+    if (((NT + 4 * cw - 1) / (4 * cw)) * sk * nrb <= cus) return 2;
+    if (((NT + 8 * cw - 1) / (8 * cw)) * sk * nrb <= cus) return 3;
+    return 1;
+}
+
 int fc_gemm256_sk(int M, int K, int NT) {
     const int nwg = ((NT + 15) / 16) * (((M + 15) / 16 + 3) / 4), NS = K / 128;
     if (nwg >= 200) return 1;
@@ -457,10 +474,10 @@ int fc_gemm256_sk(int M, int K, int NT) {
 template <int CW, int KG>
 static hipError_t launch256(int epi, const Gemm256Args& a, dim3 grid, hipStream_t st) {
     switch (epi) {
-        case EPI_RESID: k_gemm256<EPI_RESID, CW, KG><<<grid, 256 * KG, 0, st>>>(a); break;
-        case EPI_SWIGLU: k_gemm256<EPI_SWIGLU, CW, KG><<<grid, 256 * KG, 0, st>>>(a); break;
-        case EPI_QKV: k_gemm256<EPI_QKV, CW, KG><<<grid, 256 * KG, 0, st>>>(a); break;
-        case EPI_LMHEAD: k_gemm256<EPI_LMHEAD, CW, KG><<<grid, 256 * KG, 0, st>>>(a); break;
+        case EPI_RESID: k_gemm256<EPI_RESID, CW, KG><<<grid, KG == 1 ? 256 : 512, 0, st>>>(a); break;
+        case EPI_SWIGLU: k_gemm256<EPI_SWIGLU, CW, KG><<<grid, KG == 1 ? 256 : 512, 0, st>>>(a); break;
+        case EPI_QKV: k_gemm256<EPI_QKV, CW, KG><<<grid, KG == 1 ? 256 : 512, 0, st>>>(a); break;
+        case EPI_LMHEAD: k_gemm256<EPI_LMHEAD, CW, KG><<<grid, KG == 1 ? 256 : 512, 0, st>>>(a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -474,12 +491,13 @@ hipError_t fc_gemm256(int epi, const Gemm256Args& a, hipStream_t st) {
     // narrow tiles when wide ones would leave most of the chip idle
     const int nrb = ((a.M + 15) / 16 + 3) / 4;
     const int cw = (a.cw == 1 || a.cw == 2 || a.cw == 4) ? a.cw : fc_gemm256_cw(epi, a.M, a.NT);
-    const int units = ((a.NT + 4 * cw - 1) / (4 * cw)) * a.sk;
+    const int mode = fc_gemm256_mode(epi, a.M, a.K, a.NT, a.sk, cw);
+    const int wcols = mode == 3 ? 8 * cw : 4 * cw;
+    const int units = ((a.NT + wcols - 1) / wcols) * a.sk;
     dim3 grid((unsigned)((units + 7) / 8) * 8 * nrb);
-    // eight waves per workgroup where every CU gets at most one workgroup anyway
-    const bool kg2 = units * nrb <= fc_num_cus() && a.K >= 512;      // (13B batch-8 step: 16.66 -> 16.36 ms)
     hipError_t e;
-    if (kg2) e = cw == 1 ? launch256<1, 2>(epi, a, grid, st) : (cw == 2 ? launch256<2, 2>(epi, a, grid, st) : launch256<4, 2>(epi, a, grid, st));
+    if (mode == 2) e = cw == 1 ? launch256<1, 2>(epi, a, grid, st) : (cw == 2 ? launch256<2, 2>(epi, a, grid, st) : launch256<4, 2>(epi, a, grid, st));
+    else if (mode == 3) e = cw == 1 ? launch256<1, 3>(epi, a, grid, st) : (cw == 2 ? launch256<2, 3>(epi, a, grid, st) : launch256<4, 3>(epi, a, grid, st));
     else e = cw == 1 ? launch256<1, 1>(epi, a, grid, st) : (cw == 2 ? launch256<2, 1>(epi, a, grid, st) : launch256<4, 1>(epi, a, grid, st));
     if (e != hipSuccess) return e;
     if (a.sk > 1) {
