@@ -239,7 +239,7 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         int attn_splits = a.plan->attn_splits;
         at.subrows = 0;
         const int units16 = (kd.W + 15) / 16;
-        if (kd.W > 16 && a.Bact * kd.H * units16 <= fc_num_cus()) {
+        if (kd.W > 16 && a.Bact * kd.H * units16 <= fc_num_cus() && kd.S <= 8192) {   // (long caches: K/V traffic counts)
             at.subrows = 16;
             while (attn_splits > 1 && a.Bact * kd.H * units16 * attn_splits > fc_num_cus()) --attn_splits;
         }
