@@ -450,13 +450,15 @@ int fc_gemm256_cw(int epi, int M, int NT) {
 // 256 rows: 256 workgroups 9.4 ms, 384 10.0 ms, 512 9.9 ms: a second workgroup on a CU gains little and the
 // partial tiles cost); where one per CU would leave a quarter of the CUs idle, about two per CU instead
 // workgroup shape: 1 = four waves; 2 = eight waves in two k-groups, where the launch has at most one workgroup
-// per CU anyway; 3 = eight waves over two neighbouring column blocks, where that brings it down to one per CU
+// per CU anyway; 3 = eight waves over two neighbouring column blocks, where that brings it down to one per CU or
+// where four-wave workgroups would come to more than two per CU
 int fc_gemm256_mode(int epi, int M, int K, int NT, int sk, int cw) {
     (void)epi;
     const int nrb = ((M + 15) / 16 + 3) / 4, cus = fc_num_cus();
     if (K < 512) return 1;
     if (((NT + 4 * cw - 1) / (4 * cw)) * sk * nrb <= cus) return 2;
     if (((NT + 8 * cw - 1) / (8 * cw)) * sk * nrb <= cus) return 3;
+    if (((NT + 4 * cw - 1) / (4 * cw)) * sk * nrb > 2 * cus) return 3;     // several rounds either way: the shared stage wins
     return 1;
 }
 
