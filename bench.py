@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain
 # copy kernel of known size (profiles/hbm_traffic_7b_w16.md, hbm_traffic_13b_b8_w32.md); None where no counter
 # run exists
-MEASURED_TRAFFIC = {("7b", "gemm_gate_up"): 183.4e6, ("13b", "gemm_gate_up"): 400.1e6}
+MEASURED_TRAFFIC = {("7b", "gemm_gate_up"): 183.4e6, ("13b", "gemm_gate_up"): 400.1e6, ("70b", "gemm_gate_up"): 945.8e6}
 WORKLOADS = {
     # name: (shape, batch, prompt, window, new tokens)
     "7b": ("7b", 1, 256, 16, 256),

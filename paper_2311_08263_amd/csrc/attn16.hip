@@ -44,7 +44,12 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
     // K/V of all window rows are already in the cache when this kernel starts)
     constexpr int SUBR = 16 * QT;                            // rows of a unit
     const int nsub = (a.W + SUBR - 1) / SUBR;
-    const int bh = blockIdx.x, h = bh % a.H, sub = (bh / a.H) % nsub, b = bh / (a.H * nsub), kvh = h / (a.H / a.Hkv);
+    // workgroups go to the eight XCDs (each with an L2 of its own) round robin by index, so with grouped
+    // K/V heads consecutive indices take different K/V heads: the query heads that share one then follow
+    // each other at a stride of Hkv, land on the same XCD when Hkv is a multiple of eight, and fetch the
+    // shared planes from memory once instead of once per query head
+    const int bh = blockIdx.x, hr = bh % a.H, G = a.H / a.Hkv, kvh = hr % a.Hkv, h = kvh * G + hr / a.Hkv;
+    const int sub = (bh / a.H) % nsub, b = bh / (a.H * nsub);
     const int sp = blockIdx.y, nsp_max = gridDim.y;
     const int row0 = SUBR * sub, Wr = a.W - row0 < SUBR ? a.W - row0 : SUBR;      // rows of this unit
     const int n = a.n_state[b] + row0;                       // positions every row of the unit sees
