@@ -126,6 +126,16 @@ int fastcot_get_state(fastcot_ctx* ctx, int32_t* n, int32_t* generated, int32_t*
  * (Sec. 4.1); the step count does.  This is the hook an adaptive-window controller needs (Limitations). */
 int fastcot_set_window(fastcot_ctx* ctx, int32_t window);
 
+/* Ragged batches (Sec. 5.3, Table 2: a padded batch otherwise runs until its longest member ends): between
+ * two fastcot_jacobi_step calls (not with fastcot_generate) a new sequence takes over slot `slot`, 0 <= slot <
+ * the batch of the last fastcot_prefill.  prompt: host, len >= 1 token ids; buffer_init: host, buf_len ids
+ * (the buf_len of that prefill).  The slot's former sequence is dropped; every other sequence keeps its state
+ * and, Eq. 2 coupling no two sequences, its stream.  The newcomer's prompt is run through the model as a batch
+ * of one (the sequence in slot 0 trades places with it meanwhile: two cache-to-cache copies of one sequence's
+ * K/V).  Synchronises the stream.  FASTCOT_ESTATE before a prefill, after fastcot_generate or with the
+ * persistent step kernel; FASTCOT_EINVAL / FASTCOT_ECAPACITY as for fastcot_prefill. */
+int fastcot_join(fastcot_ctx* ctx, int32_t slot, const int32_t* prompt, int32_t len, const int32_t* buffer_init);
+
 /* Answer phase (Sec. 4.4 "Trigger Answer"), after fastcot_generate has returned: every sequence continues
  * from its prompt and exact tokens (already in the cache), the approximate tokens still in its window
  * (the glimpse; none for a sequence that ended with the EOS given to fastcot_generate), and the n_trigger

@@ -63,6 +63,7 @@ SYMBOLS = {
     "fastcot_kernel_name": (ctypes.c_char_p, [i32]),
     "fastcot_attn_scratch_bytes": (sz, [i32, i32, i32]),
     "fastcot_set_window": (ctypes.c_int, [vp, i32]),
+    "fastcot_join": (ctypes.c_int, [vp, i32, vp, i32, vp]),
     "fastcot_answer": (ctypes.c_int, [vp, vp, i32, i32, i32, vp, vp]),
     "fastcot_stream_read": (ctypes.c_int, [vp, ctypes.c_size_t, vp, vp]),
     "fastcot_kv_scatter": (ctypes.c_int, [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]),
@@ -232,6 +233,11 @@ class Context:
         """Window size of the following steps (between step() calls only)."""
         _check(lib().fastcot_set_window(self.h, window), self.h)
         self.cfg.window = window
+
+    def join(self, slot: int, prompt, buffer_init) -> None:
+        """A new prompt takes over one slot of the running batch (between step() calls only)."""
+        prompt, buffer_init = _i32arr(prompt).reshape(-1), _i32arr(buffer_init).reshape(-1)
+        _check(lib().fastcot_join(self.h, slot, prompt.ctypes.data, int(prompt.size), buffer_init.ctypes.data), self.h)
 
     def answer(self, trigger_ids, max_new_tokens: int, eos_id: int = -1):
         """Answer phase after generate(): glimpse + trigger enter the cache, then greedy decoding."""

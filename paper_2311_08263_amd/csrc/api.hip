@@ -427,6 +427,35 @@ static int enqueue_step(fastcot_ctx* c) {
 }
 
 // ------------------------------------------------------------------ prefill
+// Passes of R rows per sequence over prompt tokens 0 .. maxlen-2 of the first B slots (the last prompt token
+// becomes slot 0 of the first window); the plain path keeps R = window.  Enqueues only.
+static int prefill_passes(fastcot_ctx* c, int B, int maxlen) {
+    const KernelDims& kd = c->kd; const StateMap& sm = c->wm.st;
+    int32_t* stp = state_ptr(c);
+    const int rows_cap = (c->opt_plain || !fc_fast_supported(kd, B * kd.W)) ? kd.W : kd.Wcap;
+    int p0 = 0;
+    do {
+        const int left = maxlen - 1 - p0;
+        int R = left < rows_cap ? ((left + 15) & ~15) : rows_cap;
+        if (R > rows_cap) R = rows_cap;
+        if (R < 1) R = rows_cap < 16 ? rows_cap : 16;          // 1-token prompts: no forward, only the window set-up
+        const bool last = p0 + R >= maxlen - 1;
+        HIPCHK(c, fc_prefill_window(stp, sm, B, R, kd.S, p0, c->st));
+        if (left > 0) { int rc = forward(c, 0, 0, R); if (rc) return rc; }
+        HIPCHK(c, fc_prefill_advance(stp, sm, B, kd.W, kd.S, p0 + R, last, c->st));
+        p0 += R;
+    } while (p0 < maxlen - 1);
+    return 0;
+}
+
+// two sequences trade slots: state rows and K/V cache
+static hipError_t trade_slots(fastcot_ctx* c, int b1, int b2) {
+    const KernelDims& kd = c->kd;
+    const size_t seq_bytes = (size_t)kd.Hkv * kd.kvp * kd.S * kd.Dh * kd.esz;
+    return fc_swap_sequences(state_ptr(c), c->wm.st, b1, b2, kd.W, kd.S, c->ws + c->wm.kc, c->ws + c->wm.vc, seq_bytes, kd.L,
+                             (size_t)kd.B * seq_bytes, c->st);
+}
+
 extern "C" int fastcot_prefill(fastcot_ctx* c, int32_t B, const int32_t* prompts, int32_t max_P, const int32_t* lens,
                                const int32_t* buffer_init, int32_t buf_len) {
     if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
@@ -477,21 +506,7 @@ extern "C" int fastcot_prefill(fastcot_ctx* c, int32_t B, const int32_t* prompts
             drop_graph(c);
         }
     }
-    // passes of R rows per sequence over prompt tokens 0 .. maxlen-2 (the last prompt token becomes slot 0
-    // of the first window); the plain path keeps R = window
-    const int rows_cap = (c->opt_plain || !fc_fast_supported(kd, B * kd.W)) ? kd.W : kd.Wcap;
-    int p0 = 0;
-    do {
-        const int left = maxlen - 1 - p0;
-        int R = left < rows_cap ? ((left + 15) & ~15) : rows_cap;
-        if (R > rows_cap) R = rows_cap;
-        if (R < 1) R = rows_cap < 16 ? rows_cap : 16;          // 1-token prompts: no forward, only the window set-up
-        const bool last = p0 + R >= maxlen - 1;
-        HIPCHK(c, fc_prefill_window(stp, sm, B, R, kd.S, p0, c->st));
-        if (left > 0) { int rc = forward(c, 0, 0, R); if (rc) return rc; }
-        HIPCHK(c, fc_prefill_advance(stp, sm, B, kd.W, kd.S, p0 + R, last, c->st));
-        p0 += R;
-    } while (p0 < maxlen - 1);
+    { int rc = prefill_passes(c, B, maxlen); if (rc) return rc; }
     HIPCHK(c, hipStreamSynchronize(c->st));
     { int rc = check_abort(c); if (rc) return rc; }
     c->prefilled = 1;
@@ -547,6 +562,56 @@ extern "C" int fastcot_set_window(fastcot_ctx* c, int32_t window) {
     return 0;
 }
 
+// ------------------------------------------------------------------ a sequence joins the running batch
+// Ragged batches (Sec. 5.3: a batch otherwise runs, padded, until its longest member ends): between two
+// fastcot_jacobi_step calls a new prompt takes over slot `slot`; the other sequences keep their state, and
+// since no term of Eq. 2 couples sequences, their streams are what they would have been.  The kernels work
+// on the first slots of the batch, so the newcomer is prefilled in slot 0 as a batch of one: the sequence
+// that lives there trades places with it for that long.
+extern "C" int fastcot_join(fastcot_ctx* c, int32_t slot, const int32_t* prompt, int32_t len, const int32_t* buffer_init) {
+    if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
+    if (!c->prefilled) return fail(c, FASTCOT_ESTATE, "fastcot_join before fastcot_prefill%s");
+    if (c->generated) return fail(c, FASTCOT_ESTATE, "fastcot_join after fastcot_generate%s");
+    if (use_persist(c)) return fail(c, FASTCOT_ESTATE, "fastcot_join is not available with the persistent step kernel%s");
+    if (!prompt || !buffer_init) return fail(c, FASTCOT_EINVAL, "NULL prompt or buffer%s");
+    const KernelDims& kd = c->kd; const StateMap& sm = c->wm.st; const int B = c->Bact;
+    if (slot < 0 || slot >= B) return fail(c, FASTCOT_EINVAL, "slot %s%ld outside the batch of %ld", "", (long)slot, (long)B);
+    if (len < 1 || len > kd.S) return fail(c, FASTCOT_EINVAL, "prompt length out of range%s");
+    if (len - 1 + 2 * kd.W > c->cfg.max_seq) return fail(c, FASTCOT_ECAPACITY, "prompt of %s%ld tokens does not fit max_seq %ld", "", (long)len, (long)c->cfg.max_seq);
+    for (int i = 0; i < len; ++i)
+        if (prompt[i] < 0 || prompt[i] >= kd.V) return fail(c, FASTCOT_EINVAL, "prompt token out of vocabulary%s");
+    for (int i = 0; i < c->buf_len; ++i)
+        if (buffer_init[i] < 0 || buffer_init[i] >= kd.V) return fail(c, FASTCOT_EINVAL, "buffer token out of vocabulary%s");
+    int32_t* stp = state_ptr(c);
+    if (slot != 0) HIPCHK(c, trade_slots(c, 0, slot));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    std::vector<int32_t> row((size_t)kd.S, 0);
+    memcpy(row.data(), prompt, (size_t)len * 4);
+    HIPCHK(c, hipMemcpy(stp + sm.prompt, row.data(), row.size() * 4, hipMemcpyHostToDevice));
+    std::fill(row.begin(), row.end(), 0);
+    memcpy(row.data(), buffer_init, (size_t)c->buf_len * 4);
+    HIPCHK(c, hipMemcpy(stp + sm.buf, row.data(), row.size() * 4, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(stp + sm.plen, &len, 4, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemset(stp + sm.n, 0, 4));
+    // a pass of R rows uses the first R window entries, which at R > W are the other sequences' windows
+    std::vector<int32_t> wins((size_t)B * kd.W);
+    HIPCHK(c, hipMemcpy(wins.data(), stp + sm.win, wins.size() * 4, hipMemcpyDeviceToHost));
+    c->Bact = 1;                                   // the step graph, captured for B sequences, is not touched
+    int rc = prefill_passes(c, 1, len);
+    c->Bact = B;
+    if (rc) return rc;
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    if (B > 1) HIPCHK(c, hipMemcpy(stp + sm.win + kd.W, wins.data() + kd.W, (size_t)(B - 1) * kd.W * 4, hipMemcpyHostToDevice));
+    if (slot != 0) HIPCHK(c, trade_slots(c, 0, slot));
+    // the flags speak for the whole batch: they stand only if a remaining sequence still has them raised
+    HIPCHK(c, hipMemcpyAsync(c->pinned, stp + sm.done, (size_t)B * 4, hipMemcpyDeviceToHost, c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    bool any_done = false;
+    for (int b = 0; b < B; ++b) any_done = any_done || c->pinned[b] != 0;
+    if (!any_done) { int32_t zeros[2] = {0, 0}; HIPCHK(c, hipMemcpy(stp + sm.flags, zeros, 8, hipMemcpyHostToDevice)); }
+    return check_abort(c);
+}
+
 // ------------------------------------------------------------------ generate
 extern "C" int fastcot_generate(fastcot_ctx* c, int32_t max_new, int32_t max_steps, int32_t eos_id, int32_t* out_ids,
                                 int32_t* out_len, int32_t* out_steps, int32_t* approx_tail) {
@@ -590,11 +655,7 @@ extern "C" int fastcot_generate(fastcot_ctx* c, int32_t max_new, int32_t max_ste
     // the first Bact slots).  The trades are undone before returning: callers see their own order.
     int Bcur = B;
     std::vector<std::pair<int, int>> trades;
-    const size_t seq_bytes = (size_t)kd.Hkv * kd.kvp * kd.S * kd.Dh * kd.esz;
-    auto trade = [&](int b1, int b2) -> hipError_t {
-        return fc_swap_sequences(stp, sm, b1, b2, W, kd.S, c->ws + c->wm.kc, c->ws + c->wm.vc, seq_bytes, kd.L,
-                                 (size_t)kd.B * seq_bytes, c->st);
-    };
+    auto trade = [&](int b1, int b2) -> hipError_t { return trade_slots(c, b1, b2); };
     while (!all_done) {
         // every unfinished sequence needs at least ceil((max_new - g) / W) more steps: enqueue that many
         int need = 1;

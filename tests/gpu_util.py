@@ -17,11 +17,13 @@ def margins(logits: np.ndarray) -> np.ndarray:
     return part[..., -1] - part[..., -2]
 
 
-def follow_steps(ctx, omodel, prompts, lens, n_steps, tol, margin=0.05, check_rows=None):
+def follow_steps(ctx, omodel, prompts, lens, n_steps, tol, margin=0.05, check_rows=None, joins=None):
     """Follow mode: at every step the oracle is fed the GPU's own window at the GPU's own
     committed length and must reproduce its logits (within tol), its argmax wherever the
     oracle's top-1/top-2 margin exceeds `margin`, and -- from the GPU's argmax row -- exactly
     its verified count, accepted tokens, next committed length and next window slot 0.
+    joins: {step: (slot, prompt, buffer)} -- before that step the prompt takes over the slot (and a
+    fresh oracle session its place).
     Returns dict(max_err, rows, low_margin_rows, K)."""
     B, W = ctx.B, ctx.cfg.window
     sessions = []
@@ -34,6 +36,15 @@ def follow_steps(ctx, omodel, prompts, lens, n_steps, tol, margin=0.05, check_ro
     st = ctx.state()
     max_err, rows, low, Ks = 0.0, 0, 0, []
     for step in range(n_steps):
+        if joins and step in joins:
+            slot, pr, bf = joins[step]
+            ctx.join(slot, pr, bf)
+            sessions[slot] = omodel.session(ctx.cfg.max_seq)
+            if len(pr) > 1:
+                sessions[slot].forward(np.asarray(pr[:-1]), 0, want_logits=False)
+            st = ctx.state()
+            assert st["n"][slot] == len(pr) - 1 and st["g"][slot] == 0 and st["window"][slot][0] == pr[-1]
+            assert (st["window"][slot][1:] == np.asarray(bf)[:W - 1]).all()
         win, n0 = st["window"].copy(), st["n"].copy()
         say(f"follow step {step} n={n0.tolist()}")
         nacc, acc, win_next = ctx.step()

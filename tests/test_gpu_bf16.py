@@ -162,6 +162,25 @@ def test_early_finishers_bf16(fc):
         print(f"sequence {b}: {out['steps'][b]} steps, {upto} of {N} tokens above the margin, all equal")
 
 
+def test_join_bf16(fc):
+    """bf16 model on the matrix-core path, follow mode: two prompts join a running batch of three (one into slot
+    2, with a prompt long enough for several prefill passes of a batch of one, one into slot 0); at every step
+    the logits of every sequence -- newcomers and the ones that stayed, whose caches moved aside and back -- are
+    the oracle's for that sequence's own context."""
+    shape, W, B, N = SMALL, 8, 3, 48
+    Pmax = 300
+    S = ((Pmax + N + 2 * W + 31) // 32) * 32
+    ctx, om = setup(fc, shape, B, S, W)
+    first = synthgen.prompts(B, 40, shape.vocab, seed=91)
+    lens = [40, 23, 31]
+    late = synthgen.prompts(2, Pmax, shape.vocab, seed=92)
+    bufs = synthgen.buffer_init(B + 2, N + 2 * W, shape.vocab, seed=93)
+    say("bf16 batch with joining sequences")
+    ctx.prefill(first, lens, bufs[:B])
+    r = follow_steps(ctx, om, first, lens, 10, TOL, joins={3: (2, late[0, :Pmax], bufs[3]), 6: (0, late[1, :17], bufs[4])})
+    print(f"join follow: max |dlogit| {r['max_err']:.2e} over {r['rows']} rows, {r['low_margin_rows']} low-margin")
+
+
 def test_deterministic_replay(fc):
     shape, W, P, N = SMALL, 16, 30, 40
     S = ((P + N + 2 * W + 31) // 32) * 32

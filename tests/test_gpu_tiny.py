@@ -263,3 +263,48 @@ def test_window_size_changes_between_steps(env):
         got.extend(acc[0][:nacc[0]].tolist())
         assert win[0][0] == got[-1]
     assert got == greedy[:len(got)].tolist()
+
+
+def test_sequences_join_a_running_batch(env):
+    """Eq. 2 couples no two sequences: a prompt that takes over a slot between two steps produces, step by
+    step, what it produces alone (accepted ids and verified counts of the oracle's run), and the sequences that
+    stay are not disturbed -- whether the newcomer goes to slot 0 or trades places with it for its prefill."""
+    fc, om = env
+    W, B, N = 4, 3, 64
+    L = N + 2 * W
+    first = synthgen.prompts(B, 13, TINY.vocab, seed=81)
+    lens = [13, 6, 10]
+    late = synthgen.prompts(3, 19, TINY.vocab, seed=82)
+    late_lens = [19, 1, 8]
+    bufs = synthgen.buffer_init(B + 3, L, TINY.vocab, seed=83)
+    bufs[4, :] = om.greedy_ar(late[1, :1], L)           # one newcomer with a perfect draft: W tokens per step
+    say("tiny batch with joining sequences")
+    ctx = make_ctx(fc, B, 19 + L + 16, W)
+    ctx.prefill(first, lens, bufs[:B])
+    occupant = [dict(prompt=first[b, :lens[b]], buf=bufs[b], ids=[], counts=[]) for b in range(B)]
+    finished = []
+    joins = {3: (1, 0), 5: (0, 1), 9: (2, 2)}            # before step s: (slot, which late prompt)
+    with pytest.raises(fc.FastcotError):
+        ctx.join(B, late[0, :19], bufs[3])
+    for s in range(14):
+        if s in joins:
+            slot, k = joins[s]
+            finished.append(occupant[slot])
+            ctx.join(slot, late[k, :late_lens[k]], bufs[B + k])
+            occupant[slot] = dict(prompt=late[k, :late_lens[k]], buf=bufs[B + k], ids=[], counts=[])
+        nacc, acc, win = ctx.step()
+        for b in range(B):
+            occupant[b]["ids"].extend(acc[b][:nacc[b]].tolist())
+            occupant[b]["counts"].append(int(nacc[b]))
+            assert win[b][0] == occupant[b]["ids"][-1]
+    for seq in finished + occupant:
+        steps = len(seq["counts"])
+        ref = om.jacobi_generate(seq["prompt"], seq["buf"], W, N, max_steps=steps)
+        assert steps >= 2 and ref["steps"] == steps
+        assert len(seq["ids"]) <= N and seq["ids"] == ref["ids"].tolist()
+        assert seq["counts"] == [k + 1 for k in ref["K"]]
+    assert max(occupant[0]["counts"]) == W                # the perfect draft was accepted whole
+    ctx.prefill(first, lens, bufs[:B])
+    ctx.generate(8)
+    with pytest.raises(fc.FastcotError):                  # generate runs its batch to the end
+        ctx.join(0, late[0, :19], bufs[3])
