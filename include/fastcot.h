@@ -126,6 +126,16 @@ int fastcot_get_state(fastcot_ctx* ctx, int32_t* n, int32_t* generated, int32_t*
  * (Sec. 4.1); the step count does.  This is the hook an adaptive-window controller needs (Limitations). */
 int fastcot_set_window(fastcot_ctx* ctx, int32_t window);
 
+/* Per-sequence window sizes (ragged batches, Sec. 5.3; the window enters Eq. 4 and Eq. 5 per sequence):
+ * windows: host, one entry per sequence of the last fastcot_prefill, 1 <= windows[b] <= the current batch
+ * window W.  From the next step on sequence b verifies (Eq. 5), accepts and writes back to its buffer only the
+ * first windows[b] rows of its W; its accepted stream, step count and approximate tokens are those of a run with
+ * that window alone.  The step still computes W rows for every sequence.  Call after fastcot_prefill (which
+ * resets every sequence to the batch window) and before fastcot_generate, or between fastcot_jacobi_step
+ * calls; fastcot_generate's approx_tail and fastcot_answer's glimpse then hold windows[b] - 1 valid entries for
+ * sequence b.  FASTCOT_ESTATE otherwise. */
+int fastcot_set_windows(fastcot_ctx* ctx, const int32_t* windows);
+
 /* Ragged batches (Sec. 5.3, Table 2: a padded batch otherwise runs until its longest member ends): between
  * two fastcot_jacobi_step calls (not with fastcot_generate) a new sequence takes over slot `slot`, 0 <= slot <
  * the batch of the last fastcot_prefill.  prompt: host, len >= 1 token ids; buffer_init: host, buf_len ids

@@ -64,6 +64,7 @@ SYMBOLS = {
     "fastcot_attn_scratch_bytes": (sz, [i32, i32, i32]),
     "fastcot_set_window": (ctypes.c_int, [vp, i32]),
     "fastcot_join": (ctypes.c_int, [vp, i32, vp, i32, vp]),
+    "fastcot_set_windows": (ctypes.c_int, [vp, vp]),
     "fastcot_answer": (ctypes.c_int, [vp, vp, i32, i32, i32, vp, vp]),
     "fastcot_stream_read": (ctypes.c_int, [vp, ctypes.c_size_t, vp, vp]),
     "fastcot_kv_scatter": (ctypes.c_int, [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]),
@@ -233,6 +234,12 @@ class Context:
         """Window size of the following steps (between step() calls only)."""
         _check(lib().fastcot_set_window(self.h, window), self.h)
         self.cfg.window = window
+
+    def set_windows(self, windows) -> None:
+        """Per-sequence window sizes (each at most the batch window) from the next step on."""
+        w = _i32arr(windows).reshape(-1)
+        assert w.size == self.B
+        _check(lib().fastcot_set_windows(self.h, w.ctypes.data), self.h)
 
     def join(self, slot: int, prompt, buffer_init) -> None:
         """A new prompt takes over one slot of the running batch (between step() calls only)."""

@@ -146,6 +146,7 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
         s.n = ti(k.B); s.g = ti(k.B); s.done = ti(k.B); s.steps = ti(k.B); s.newest = ti(k.B); s.lastK = ti(k.B);
         s.plen = ti(k.B); s.olen = ti(k.B); s.win = ti(k.B * k.Wcap); s.o = ti(k.B * k.Wcap);
         s.buf = ti(k.B * k.S); s.out = ti(k.B * k.S); s.prompt = ti(k.B * k.S); s.flags = ti(8); s.params = ti(8);
+        s.wseq = ti(k.B);
         s.words = w;
         wm->st = s;
         wm->state = take((size_t)w * 4);
@@ -490,6 +491,7 @@ extern "C" int fastcot_prefill(fastcot_ctx* c, int32_t B, const int32_t* prompts
     int32_t zeros[8] = {0};
     HIPCHK(c, hipMemcpy(stp + sm.flags, zeros, sizeof(zeros), hipMemcpyHostToDevice));
     HIPCHK(c, hipMemset(stp + sm.n, 0, (size_t)kd.B * 4));
+    HIPCHK(c, hipMemset(stp + sm.wseq, 0, (size_t)kd.B * 4));
     if (B != c->Bact) drop_graph(c);
     c->Bact = B; c->buf_len = buf_len; c->prefilled = 0; c->generated = 0;
     // the plan's per-GEMM choices are measured once per step shape, on this model's own matrices (the buffers
@@ -562,6 +564,22 @@ extern "C" int fastcot_set_window(fastcot_ctx* c, int32_t window) {
     return 0;
 }
 
+// Per-sequence window sizes (ragged batches, Sec. 5.3): sequence b verifies, accepts and writes back only the
+// first windows[b] rows of its share of the step.  The step still computes the batch's window for every
+// sequence (rows sit at b * W + j), so this changes what a sequence does per step, not what the step costs.
+extern "C" int fastcot_set_windows(fastcot_ctx* c, const int32_t* windows) {
+    if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
+    if (!c->prefilled) return fail(c, FASTCOT_ESTATE, "fastcot_set_windows before fastcot_prefill%s");
+    if (c->generated) return fail(c, FASTCOT_ESTATE, "fastcot_set_windows after fastcot_generate%s");
+    if (!windows) return fail(c, FASTCOT_EINVAL, "windows is NULL%s");
+    const int B = c->Bact;
+    for (int b = 0; b < B; ++b)
+        if (windows[b] < 1 || windows[b] > c->kd.W) return fail(c, FASTCOT_EINVAL, "window %s%ld outside 1..%ld", "", (long)windows[b], (long)c->kd.W);
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    HIPCHK(c, hipMemcpy(state_ptr(c) + c->wm.st.wseq, windows, (size_t)B * 4, hipMemcpyHostToDevice));
+    return 0;
+}
+
 // ------------------------------------------------------------------ a sequence joins the running batch
 // Ragged batches (Sec. 5.3: a batch otherwise runs, padded, until its longest member ends): between two
 // fastcot_jacobi_step calls a new prompt takes over slot `slot`; the other sequences keep their state, and
@@ -593,6 +611,7 @@ extern "C" int fastcot_join(fastcot_ctx* c, int32_t slot, const int32_t* prompt,
     HIPCHK(c, hipMemcpy(stp + sm.buf, row.data(), row.size() * 4, hipMemcpyHostToDevice));
     HIPCHK(c, hipMemcpy(stp + sm.plen, &len, 4, hipMemcpyHostToDevice));
     HIPCHK(c, hipMemset(stp + sm.n, 0, 4));
+    HIPCHK(c, hipMemset(stp + sm.wseq, 0, 4));       // the newcomer runs the batch's window
     // a pass of R rows uses the first R window entries, which at R > W are the other sequences' windows
     std::vector<int32_t> wins((size_t)B * kd.W);
     HIPCHK(c, hipMemcpy(wins.data(), stp + sm.win, wins.size() * 4, hipMemcpyDeviceToHost));
@@ -749,6 +768,8 @@ extern "C" int fastcot_answer(fastcot_ctx* c, const int32_t* trigger_ids, int32_
     HIPCHK(c, hipMemcpy(holen.data(), stp + sm.olen, (size_t)B * 4, hipMemcpyDeviceToHost));
     HIPCHK(c, hipMemcpy(hnew.data(), stp + sm.newest, (size_t)B * 4, hipMemcpyDeviceToHost));
     HIPCHK(c, hipMemcpy(hplen.data(), stp + sm.plen, (size_t)B * 4, hipMemcpyDeviceToHost));
+    std::vector<int32_t> hws(B);
+    HIPCHK(c, hipMemcpy(hws.data(), stp + sm.wseq, (size_t)B * 4, hipMemcpyDeviceToHost));
     HIPCHK(c, hipMemcpy(hwin.data(), stp + sm.win, hwin.size() * 4, hipMemcpyDeviceToHost));
     HIPCHK(c, hipMemcpy(hout.data(), stp + sm.out, hout.size() * 4, hipMemcpyDeviceToHost));
     // per sequence: the tokens that still have to enter the cache, and the committed length they start at
@@ -763,7 +784,8 @@ extern "C" int fastcot_answer(fastcot_ctx* c, const int32_t* trigger_ids, int32_
         } else {             // newest exact token (not in the cache yet), then the glimpse
             if (hn[b] != hplen[b] - 1 + hg[b]) return fail(c, FASTCOT_ESTATE, "inconsistent sequence state%s");
             t.push_back(hg[b] > 0 ? hnew[b] : hwin[(size_t)b * W]);
-            for (int j = 1; j < W; ++j) t.push_back(hwin[(size_t)b * W + j]);
+            const int Wb = hws[b] > 0 && hws[b] < W ? hws[b] : W;
+            for (int j = 1; j < Wb; ++j) t.push_back(hwin[(size_t)b * W + j]);
         }
         for (int i = 0; i < n_trigger; ++i) t.push_back(trigger_ids[i]);
         if ((int)t.size() - 1 > R) R = (int)t.size() - 1;

@@ -81,6 +81,7 @@ struct ModelMap {
 // ------------------------------------------------------------------ device state block (int32 words)
 struct StateMap {      // offsets in int32 words from the state base
     int32_t n, g, done, steps, newest, lastK, plen, olen, win, o, buf, out, prompt, flags, params;
+    int32_t wseq;      // per-sequence window size [B]: 0 = the batch's window, else the smaller of the two
     int32_t words;
 };
 enum { FLAG_ALL_DONE = 0, FLAG_ERROR = 1 };

@@ -654,9 +654,10 @@ __global__ __launch_bounds__(512) void k_step(PersistArgs a) {
         int32_t* buf = st + sm.buf + (size_t)b * S;
         int32_t* out = st + sm.out + (size_t)b * S;
         int n = st[sm.n + b], g = st[sm.g + b], steps = st[sm.steps + b];
+        const int ws = st[sm.wseq + b], Wb = ws > 0 && ws < W ? ws : W;     // the sequence's own window, if it has one
         int K = 0;
-        while (K < W - 1 && o[K] == wv[K + 1]) ++K;
-        for (int j = 0; j < W; ++j) if (g + j < buf_len) buf[g + j] = o[j];
+        while (K < Wb - 1 && o[K] == wv[K + 1]) ++K;
+        for (int j = 0; j < Wb; ++j) if (g + j < buf_len) buf[g + j] = o[j];
         int stop = 0, emitted = 0;
         for (int j = 0; j <= K && !stop; ++j) {
             if (g + j < max_new && g + j < S) { out[g + j] = o[j]; emitted = g + j + 1; }

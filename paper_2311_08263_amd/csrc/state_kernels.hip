@@ -62,9 +62,11 @@ __global__ void k_accept_commit(int32_t* st, StateMap sm, int B, int W, int S) {
         int32_t* buf = st + sm.buf + (size_t)b * S;
         int32_t* out = st + sm.out + (size_t)b * S;
         int n = st[sm.n + b], g = st[sm.g + b], steps = st[sm.steps + b];
+        // a sequence with a window of its own uses the first Wb rows of its W: the others are computed and ignored
+        const int ws = st[sm.wseq + b], Wb = ws > 0 && ws < W ? ws : W;
         int K = 0;
-        while (K < W - 1 && o[K] == w[K + 1]) ++K;
-        for (int j = 0; j < W; ++j) if (g + j < buf_len) buf[g + j] = o[j];
+        while (K < Wb - 1 && o[K] == w[K + 1]) ++K;
+        for (int j = 0; j < Wb; ++j) if (g + j < buf_len) buf[g + j] = o[j];
         int stop = 0, emitted = 0;
         for (int j = 0; j <= K && !stop; ++j) {
             if (g + j < max_new && g + j < S) { out[g + j] = o[j]; emitted = g + j + 1; }
@@ -112,8 +114,8 @@ hipError_t fc_accept_commit(int32_t* state, const StateMap& sm, int B, int W, in
 // Two sequences trade slots: every per-sequence entry of the state block (one workgroup) ...
 __global__ void k_swap_seq(int32_t* st, StateMap sm, int b1, int b2, int W, int S) {
     const int t = threadIdx.x;
-    if (t < 8) {
-        const int32_t offs[8] = {sm.n, sm.g, sm.done, sm.steps, sm.newest, sm.lastK, sm.plen, sm.olen};
+    if (t < 9) {
+        const int32_t offs[9] = {sm.n, sm.g, sm.done, sm.steps, sm.newest, sm.lastK, sm.plen, sm.olen, sm.wseq};
         const int32_t v1 = st[offs[t] + b1], v2 = st[offs[t] + b2];
         st[offs[t] + b1] = v2; st[offs[t] + b2] = v1;
     }

@@ -17,13 +17,14 @@ def margins(logits: np.ndarray) -> np.ndarray:
     return part[..., -1] - part[..., -2]
 
 
-def follow_steps(ctx, omodel, prompts, lens, n_steps, tol, margin=0.05, check_rows=None, joins=None):
+def follow_steps(ctx, omodel, prompts, lens, n_steps, tol, margin=0.05, check_rows=None, joins=None, wins=None):
     """Follow mode: at every step the oracle is fed the GPU's own window at the GPU's own
     committed length and must reproduce its logits (within tol), its argmax wherever the
     oracle's top-1/top-2 margin exceeds `margin`, and -- from the GPU's argmax row -- exactly
     its verified count, accepted tokens, next committed length and next window slot 0.
     joins: {step: (slot, prompt, buffer)} -- before that step the prompt takes over the slot (and a
-    fresh oracle session its place).
+    fresh oracle session its place).  wins: per-sequence window sizes the context was told to use (the
+    integer path then looks at the first wins[b] rows only).
     Returns dict(max_err, rows, low_margin_rows, K)."""
     B, W = ctx.B, ctx.cfg.window
     sessions = []
@@ -66,7 +67,8 @@ def follow_steps(ctx, omodel, prompts, lens, n_steps, tol, margin=0.05, check_ro
             rows += W
             low += int((~clear).sum())
             # integer path, recomputed by the oracle from the GPU's own argmax row: no tolerance
-            K = oracle.verify(win[b], o_gpu)
+            Wb = wins[b] if wins is not None else W
+            K = oracle.verify(win[b][:Wb], o_gpu[:Wb])
             assert st["K"][b] == K and nacc[b] == K + 1
             assert (acc[b, :K + 1] == o_gpu[:K + 1]).all()
             assert st["n"][b] == n0[b] + K + 1

@@ -181,6 +181,28 @@ def test_join_bf16(fc):
     print(f"join follow: max |dlogit| {r['max_err']:.2e} over {r['rows']} rows, {r['low_margin_rows']} low-margin")
 
 
+@pytest.mark.parametrize("persistent", [0, 1])
+def test_per_sequence_windows_bf16(fc, persistent):
+    """bf16 model, follow mode with per-sequence window sizes (per-stage kernels and the one-launch step): the
+    verified count, accepted tokens and committed length come from the first W_b rows of a sequence; one sequence
+    has a perfect draft so that the cut at W_b, not a mismatch, is what ends its verification."""
+    shape, W, B, P, N = SMALL, 8, 2, 30, 40
+    S = ((P + N + 2 * W + 31) // 32) * 32
+    ctx, om = setup(fc, shape, B, S, W)
+    ctx.set_option(4, persistent)
+    prompts = synthgen.prompts(B, P, shape.vocab, seed=111)
+    lens = [P, P - 5]
+    buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=112)
+    buf[1, :] = om.greedy_ar(prompts[1, :lens[1]], N + 2 * W)
+    say(f"bf16 per-sequence windows persistent={persistent}")
+    ctx.prefill(prompts, lens, buf)
+    ctx.set_windows([6, 3])
+    r = follow_steps(ctx, om, prompts, lens, 6, TOL, wins=[6, 3])
+    ks = r["K"][1::2]
+    assert max(ks) == 2 and max(r["K"][0::2]) <= 5
+    print(f"per-sequence windows: verified counts {r['K']}")
+
+
 def test_deterministic_replay(fc):
     shape, W, P, N = SMALL, 16, 30, 40
     S = ((P + N + 2 * W + 31) // 32) * 32

@@ -308,3 +308,48 @@ def test_sequences_join_a_running_batch(env):
     ctx.generate(8)
     with pytest.raises(fc.FastcotError):                  # generate runs its batch to the end
         ctx.join(0, late[0, :19], bufs[3])
+
+
+def test_per_sequence_window_sizes(env):
+    """The window enters Eq. 4 / Eq. 5 per sequence: in a batch whose step computes W rows for everyone, a
+    sequence told to use W_b of them produces the ids, step count and approximate tail of the oracle's run with
+    window W_b, and its answer phase sees W_b - 1 glimpse tokens."""
+    fc, om = env
+    W, B, N, P, NA = 8, 4, 24, 12, 5
+    wins = [8, 3, 1, 5]
+    lens = [12, 9, 4, 12]
+    prompts = synthgen.prompts(B, P, TINY.vocab, seed=101)
+    buf = synthgen.buffer_init(B, N + 2 * W, TINY.vocab, seed=102)
+    buf[3, :] = om.greedy_ar(prompts[3, :lens[3]], N + 2 * W)        # a perfect draft: W_b tokens per step
+    refs = [om.jacobi_generate(prompts[b, :lens[b]], buf[b], wins[b], N) for b in range(B)]
+    assert refs[2]["steps"] == N and refs[3]["steps"] == -(-N // wins[3])
+    say("tiny per-sequence windows")
+    ctx = make_ctx(fc, B, P + N + 4 * W + NA + 8, W)
+    ctx.prefill(prompts, lens, buf)
+    with pytest.raises(fc.FastcotError):
+        ctx.set_windows([8, 9, 1, 1])
+    ctx.set_windows(wins)
+    out = ctx.generate(N)
+    st = ctx.state()
+    for b in range(B):
+        assert out["len"][b] == N and (out["ids"][b] == refs[b]["ids"]).all(), b
+        assert out["steps"][b] == refs[b]["steps"], b
+        assert (out["tail"][b][:wins[b] - 1] == refs[b]["tail"]).all(), b
+    trigger = np.array([9, 500], dtype=np.int32)
+    ans = ctx.answer(trigger, NA)
+    for b in range(B):
+        g = int(st["g"][b])
+        exact = om.greedy_ar(prompts[b, :lens[b]], g)
+        combined = np.concatenate([prompts[b, :lens[b]], exact, st["window"][b][1:wins[b]], trigger]).astype(np.int32)
+        assert ans["ids"][b].tolist() == om.greedy_ar(combined, NA).tolist(), b
+    # step mode: counts per step, and a prefill puts every sequence back on the batch window
+    ctx.prefill(prompts, lens, buf)
+    ctx.set_windows(wins)
+    for s in range(3):
+        nacc, _, _ = ctx.step()
+        assert [int(x) - 1 for x in nacc] == [int(refs[b]["K"][s]) for b in range(B)]
+    ctx.prefill(prompts, lens, buf)
+    full = [om.jacobi_generate(prompts[b, :lens[b]], buf[b], W, N) for b in range(B)]
+    out = ctx.generate(N)
+    for b in range(B):
+        assert out["steps"][b] == full[b]["steps"] and (out["ids"][b] == full[b]["ids"]).all()
