@@ -1,6 +1,8 @@
 """Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
 sizes configurations, and rejects bad arguments before touching a GPU."""
 import ctypes
+
+import numpy as np
 import os
 import re
 
@@ -40,6 +42,11 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert L.fastcot_jacobi_step(None, None, None, None) == -1
     assert L.fastcot_generate(None, 1, 0, -1, None, None, None, None) == -1
     assert L.fastcot_get_state(None, None, None, None, None, None, None) == -1
+    one = np.ones(4, dtype=np.int32)
+    assert L.fastcot_set_window(None, 4) == -1
+    assert L.fastcot_set_windows(None, one.ctypes.data) == -1
+    assert L.fastcot_join(None, 0, one.ctypes.data, 4, one.ctypes.data) == -1
+    assert L.fastcot_answer(None, one.ctypes.data, 1, 4, -1, one.ctypes.data, one.ctypes.data) == -1
     assert b"NULL" in L.fastcot_last_error(None)
     cfg = binding.Config.from_shape(synthgen.SHAPES["tiny"], 1, 64, 4)
     out = ctypes.c_void_p()
