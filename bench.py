@@ -196,7 +196,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus above 1 is not supported "
-                 "(sequences are independent: a multi-GPU run would shard the batch, see DESIGN.md)")
+                 "(sequences are independent, Eq. 2: a multi-GPU run would give each GPU its share of the batch and a copy of the weights)")
 
     if args.window_sweep:
         return window_sweep(args)
