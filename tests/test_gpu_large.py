@@ -1,0 +1,138 @@
+"""Full-size checks of the two larger benchmark configurations, in the launch configuration the benchmark
+times: Llama-2-13B-shaped bf16, batch 8 x prompt 1024 x window 32 (256 rows per step, the many-row kernels), and
+Llama-2-70B-shaped bf16 (64 query heads on 8 K/V heads), batch 1 x prompt 512 x window 16.  One oracle step at
+these sizes is minutes to hours of host time, so the oracle's part is done at these layer shapes with two layers
+(test_gpu_shapes.py) and here the full-depth models are held to properties that hold at any size:
+
+* a sequence computes the same thing alone as inside a batch (Eq. 2 couples no two sequences) -- alone it runs
+  through the column-owner kernels, in the batch of 8 through the many-row kernels, so this is also a
+  cross-check of two independent kernel families at full depth;
+* the accepted stream does not depend on the window (Sec. 4.1: it is the greedy continuation, Eq. 1): window 1
+  against window 16;
+* every step accepts between 1 and W tokens and the counts add up; a perfect draft is accepted W at a time and
+  reproduces the stream.
+
+Two bf16 paths may differ by rounding: logits are compared to twice the 2e-2 bar each path has against the oracle,
+and token ids wherever the top-1 / top-2 margin of the logits exceeds 0.05 (afterwards the trajectories may fork).
+"""
+import numpy as np
+import pytest
+
+import synthgen
+from gpu_util import margins, say
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def perfect_draft_check(ctx, prompts, lens, buf, out, N, W):
+    """The stream itself as the buffer: W tokens per step while the two runs agree."""
+    B = len(lens)
+    draft = np.concatenate([out["ids"], buf[:, :2 * W]], axis=1)
+    ctx.prefill(prompts, lens, draft)
+    out2 = ctx.generate(N)
+    for b in range(B):
+        same = out2["ids"][b] == out["ids"][b]
+        first_diff = int(np.argmin(same)) if not same.all() else N
+        assert first_diff >= W, (b, first_diff)          # the first window at least is reproduced
+        if same.all():
+            assert out2["steps"][b] == (N + W - 1) // W, b
+    return out2
+
+
+@pytest.mark.timeout(600)
+def test_13b_batch8_full_size():
+    import paper_2311_08263_amd as fc
+    shape = synthgen.SHAPES["13b"]
+    B, P, W, N = 8, 1024, 32, 64
+    S = P + N + 2 * W + 32
+    say("13b full size: weights")
+    cfg = fc.Config.from_shape(shape, B, S, W)
+    packed = fc.load_synth_weights(cfg, shape)
+    prompts = synthgen.prompts(B, P, shape.vocab)
+    buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab)
+    lens = [P - 37 * b for b in range(B)]
+    ctx = fc.Context(cfg, packed)
+    say("13b full size: batch of 8, three steps with logits")
+    ctx.prefill(prompts, lens, buf)
+    dbg = ctx.debug_logits(True)
+    batch_steps = []
+    for s in range(3):
+        st = ctx.state()
+        nacc, acc, _ = ctx.step()
+        batch_steps.append((st["window"].copy(), st["n"].copy(), dbg.cpu().numpy().copy(), nacc.copy(), acc.copy()))
+        assert ((1 <= nacc) & (nacc <= W)).all()
+    ctx.debug_logits(False)
+    # the same sequences alone (32 rows per step: the column-owner kernels)
+    cfg1 = fc.Config.from_shape(shape, 1, S, W)
+    worst = 0.0
+    for b in (0, 5):
+        say(f"13b full size: sequence {b} alone")
+        one = fc.Context(cfg1, packed)
+        one.prefill(prompts[b:b + 1], [lens[b]], buf[b:b + 1])
+        d1 = one.debug_logits(True)
+        for s in range(3):
+            win, n, lg, nacc, acc = batch_steps[s]
+            st = one.state()
+            if not (st["window"][0] == win[b]).all() or st["n"][0] != n[b]:
+                break                                       # the trajectories have forked on a low-margin row
+            na1, ac1, _ = one.step()
+            l1 = d1.cpu().numpy()[:W]
+            lb = lg[b * W:(b + 1) * W]
+            err = float(np.abs(l1 - lb).max())
+            worst = max(worst, err)
+            assert err <= 2 * TOL, (b, s, err)
+            clear = (margins(lb) > 0.05) & (margins(l1) > 0.05)
+            assert (l1.argmax(-1)[clear] == lb.argmax(-1)[clear]).all(), (b, s)
+            if clear.all():
+                assert na1[0] == nacc[b] and (ac1[0][:na1[0]] == acc[b][:nacc[b]]).all()
+        assert s >= 1, "the two paths forked before the second step"
+        del one
+    print(f"13b full size: batch rows vs the same sequence alone, max |dlogit| {worst:.2e}")
+    say("13b full size: generate")
+    ctx.prefill(prompts, lens, buf)
+    out = ctx.generate(N)
+    st = ctx.state()
+    for b in range(B):
+        assert out["len"][b] == N and (N + W - 1) // W <= out["steps"][b] <= N
+        assert st["n"][b] == lens[b] - 1 + st["g"][b] and st["g"][b] >= N
+    say("13b full size: perfect draft")
+    perfect_draft_check(ctx, prompts, lens, buf, out, N, W)
+
+
+@pytest.mark.timeout(600)
+def test_70b_full_size():
+    import paper_2311_08263_amd as fc
+    shape = synthgen.SHAPES["70b"]
+    P, W, N = 512, 16, 32
+    S = P + N + 2 * W + 32
+    say("70b full size: weights")
+    cfg = fc.Config.from_shape(shape, 1, S, W)
+    packed = fc.load_synth_weights(cfg, shape)
+    prompts = synthgen.prompts(1, P, shape.vocab)
+    buf = synthgen.buffer_init(1, N + 2 * W, shape.vocab)
+    ctx = fc.Context(cfg, packed)
+    say("70b full size: generate with window 16")
+    ctx.prefill(prompts, [P], buf)
+    out = ctx.generate(N)
+    st = ctx.state()
+    assert out["len"][0] == N and (N + W - 1) // W <= out["steps"][0] <= N
+    assert st["n"][0] == P - 1 + st["g"][0]
+    say("70b full size: perfect draft")
+    perfect_draft_check(ctx, prompts, [P], buf, out, N, W)
+    # window 1 is plain greedy decoding (Eq. 1): one token per step, the same stream while the margins are clear
+    say("70b full size: window 1")
+    ctx.prefill(prompts, [P], buf)
+    ctx.set_window(1)
+    dbg = ctx.debug_logits(True)
+    upto = N
+    for i in range(N):
+        nacc, acc, _ = ctx.step()
+        lg = dbg.cpu().numpy()[0]
+        assert nacc[0] == 1 and acc[0][0] == lg.argmax()
+        if acc[0][0] != out["ids"][0][i]:                   # a fork is legitimate on a low-margin row only
+            assert margins(lg[None])[0] <= 0.05, (i, float(margins(lg[None])[0]))
+            upto = i
+            break
+    ctx.debug_logits(False)
+    print(f"70b full size: window 1 and window 16 agree on the first {upto} of {N} tokens")
