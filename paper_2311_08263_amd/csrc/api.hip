@@ -490,8 +490,8 @@ extern "C" int fastcot_prefill(fastcot_ctx* c, int32_t B, const int32_t* prompts
     HIPCHK(c, hipMemcpy(stp + sm.params, params, sizeof(params), hipMemcpyHostToDevice));
     int32_t zeros[8] = {0};
     HIPCHK(c, hipMemcpy(stp + sm.flags, zeros, sizeof(zeros), hipMemcpyHostToDevice));
-    HIPCHK(c, hipMemset(stp + sm.n, 0, (size_t)kd.B * 4));
-    HIPCHK(c, hipMemset(stp + sm.wseq, 0, (size_t)kd.B * 4));
+    HIPCHK(c, hipMemsetAsync(stp + sm.n, 0, (size_t)kd.B * 4, c->st));
+    HIPCHK(c, hipMemsetAsync(stp + sm.wseq, 0, (size_t)kd.B * 4, c->st));
     if (B != c->Bact) drop_graph(c);
     c->Bact = B; c->buf_len = buf_len; c->prefilled = 0; c->generated = 0;
     // the plan's per-GEMM choices are measured once per step shape, on this model's own matrices (the buffers
@@ -610,8 +610,8 @@ extern "C" int fastcot_join(fastcot_ctx* c, int32_t slot, const int32_t* prompt,
     memcpy(row.data(), buffer_init, (size_t)c->buf_len * 4);
     HIPCHK(c, hipMemcpy(stp + sm.buf, row.data(), row.size() * 4, hipMemcpyHostToDevice));
     HIPCHK(c, hipMemcpy(stp + sm.plen, &len, 4, hipMemcpyHostToDevice));
-    HIPCHK(c, hipMemset(stp + sm.n, 0, 4));
-    HIPCHK(c, hipMemset(stp + sm.wseq, 0, 4));       // the newcomer runs the batch's window
+    HIPCHK(c, hipMemsetAsync(stp + sm.n, 0, 4, c->st));
+    HIPCHK(c, hipMemsetAsync(stp + sm.wseq, 0, 4, c->st));    // the newcomer runs the batch's window
     // a pass of R rows uses the first R window entries, which at R > W are the other sequences' windows
     std::vector<int32_t> wins((size_t)B * kd.W);
     HIPCHK(c, hipMemcpy(wins.data(), stp + sm.win, wins.size() * 4, hipMemcpyDeviceToHost));
