@@ -327,6 +327,19 @@ def main():
     # contain the launch latency that a profiler's begin-to-end duration leaves out.  The same pair around an
     # empty kernel (same pass) is reported as the floor of such intervals.
     roofline["empty_kernel_event_ms"] = round(empty_ms, 5)
+    # What the event pairs add per launch, from this run alone: the intervals of all launches of a step add up
+    # to more than the graph-replayed step takes; the excess, spread over the launches, is the pairs' share.
+    # `achieved` and `frac` stay on the raw intervals; the net figures are what a profiler's durations show.
+    launches = sum(t[2] for t in table)
+    if launches and "persistent_step" not in prof:
+        over_ms = (sum(t[1] * t[2] for t in table) - ms_per_step) / launches
+        net_ms = dom[1] - over_ms
+        if over_ms > 0 and net_ms > 0:
+            roofline["event_overhead_ms_per_launch"] = round(over_ms, 5)
+            roofline["avg_launch_ms_net"] = round(net_ms, 5)
+            roofline["frac_net"] = round(roofline["frac"] * dom[1] / net_ms, 4)
+            log(f"event intervals exceed the replayed step by {over_ms * 1e3:.2f} us per launch; {dom[0]} net of that: "
+                f"{net_ms * 1e3:.2f} us ({100 * roofline['frac_net']:.1f} % of peak)")
     extra = None
     if not args.no_extras and not args.plain and shape.dtype == "bf16":
         extra = extras(torch, fc, synthgen, packed, log)
