@@ -125,6 +125,18 @@ __global__ __launch_bounds__(KG == 1 ? 256 : 512, KG == 1 ? 2 : 1) void k_gemm25
     const int s_lo = (int)((unsigned)NS * (unsigned)ks / (unsigned)a.sk), s_hi = (int)((unsigned)NS * (unsigned)(ks + 1) / (unsigned)a.sk);
     const int nt0 = cb * WCOLS + CW * (CSPLIT ? w8 : w);      // this wave's CW n-tiles
     const int mt0 = rb * 4;
+    // QKV: the cache positions of this wave's rows (a dependent load of the sequence length) are fetched here,
+    // a whole K loop ahead of the epilogue that needs them
+    int qpos[4], qb[4];
+    if (EPI == EPI_QKV) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int row = (mt0 + m) * 16 + lm;
+            const bool rok = (!KSPLIT || kg == 0) && mt0 + m < MT && row < a.M;
+            qb[m] = rok ? row / a.Wn : 0;
+            qpos[m] = rok ? a.n_state[qb[m]] + row % a.Wn : a.S;
+        }
+    }
 
     // stage copy: 32 fragments of 1 KB per stage, 8 x 16 bytes per thread.  Addresses are a uniform 64-bit base
     // (scalar registers, advanced per stage) plus a per-thread 32-bit byte offset fixed for the whole kernel:
@@ -257,10 +269,28 @@ __global__ __launch_bounds__(KG == 1 ? 256 : 512, KG == 1 ? 2 : 1) void k_gemm25
             rscale[m] = 1.0f / sqrtf(ssum / (float)a.K + a.eps);
         }
     }
+    // QKV: positions and rotary factors are requested a row tile ahead of their use, in front of the stores of
+    // the tile before (a load behind a store that might alias it is not moved up by the compiler, and sixteen
+    // tiles each waiting for their own factors cost sixteen round trips)
+    f32x4_t qc[2][CW], qs[2][CW];
+    auto qfactors = [&](int m, f32x4_t (&c)[CW], f32x4_t (&sn)[CW]) {
+#pragma unroll
+        for (int j = 0; j < CW; ++j) {
+            const int nt = nt0 + j, hh = nt >> 3, t = nt & 7;
+            c[j] = (f32x4_t){1.0f, 1.0f, 1.0f, 1.0f};
+            sn[j] = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
+            if (qpos[m] < a.S && nt < a.NT && hh < a.H + a.Hkv) {
+                c[j] = *(const f32x4_t*)(a.cosT + (size_t)qpos[m] * 64 + 8 * t + 4 * (g4 & 1));
+                sn[j] = *(const f32x4_t*)(a.sinT + (size_t)qpos[m] * 64 + 8 * t + 4 * (g4 & 1));
+            }
+        }
+    };
+    if (EPI == EPI_QKV) qfactors(0, qc[0], qs[0]);
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         const int row = (mt0 + m) * 16 + lm;
         const bool rok = act && mt0 + m < MT && row < a.M;
+        if (EPI == EPI_QKV && m + 1 < 4) qfactors(m + 1, qc[(m + 1) & 1], qs[(m + 1) & 1]);
 #pragma unroll
         for (int j = 0; j < CW; ++j) {
             const int nt = nt0 + j;
@@ -297,8 +327,7 @@ __global__ __launch_bounds__(KG == 1 ? 256 : 512, KG == 1 ? 2 : 1) void k_gemm25
                 }
             } else if (EPI == EPI_QKV) {
                 const int hh = nt >> 3, t = nt & 7;
-                const int b = rok ? row / a.Wn : 0, jj = rok ? row % a.Wn : 0;
-                const int pos = rok ? a.n_state[b] + jj : a.S;
+                const int b = qb[m], pos = qpos[m];
                 const bool pk = ok && pos < a.S;                 // capacity guard
                 const size_t plane = (size_t)a.S * 128;
                 if (hh < a.H + a.Hkv) {
@@ -307,8 +336,7 @@ __global__ __launch_bounds__(KG == 1 ? 256 : 512, KG == 1 ? 2 : 1) void k_gemm25
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const float other = __shfl_xor(v[e], 32, 64);
-                        const float c = pk ? a.cosT[(size_t)pos * 64 + i0 + e] : 1.0f;
-                        const float s = pk ? a.sinT[(size_t)pos * 64 + i0 + e] : 0.0f;
+                        const float c = qc[m & 1][j][e], s = qs[m & 1][j][e];
                         rr[e] = g4 < 2 ? v[e] * c - other * s : v[e] * c + other * s;
                     }
                     const int el = (g4 < 2 ? 0 : 64) + i0;
