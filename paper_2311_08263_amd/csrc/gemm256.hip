@@ -132,7 +132,7 @@ __global__ __launch_bounds__(KG == 1 ? 256 : 512, KG == 1 ? 2 : 1) void k_gemm25
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             const int row = (mt0 + m) * 16 + lm;
-            const bool rok = (!KSPLIT || kg == 0) && mt0 + m < MT && row < a.M;
+            const bool rok = (!KSPLIT || kg == (m >> 1)) && mt0 + m < MT && row < a.M;
             qb[m] = rok ? row / a.Wn : 0;
             qpos[m] = rok ? a.n_state[qb[m]] + row % a.Wn : a.S;
         }
@@ -235,25 +235,25 @@ __global__ __launch_bounds__(KG == 1 ? 256 : 512, KG == 1 ? 2 : 1) void k_gemm25
 #undef STEP
 
     if (KSPLIT) {
-        // the two k-groups meet: group 1 publishes its accumulators (16 KB per wave: exactly the stage buffers,
-        // free after the loop's last barrier), group 0 adds them and runs the epilogue alone
+        // the two k-groups meet: each publishes the half of its accumulators that the other group will finish
+        // (group 0 keeps row tiles 0 and 1, group 1 row tiles 2 and 3: 8 KB per wave, the stage buffers are free
+        // after the loop's last barrier), adds what it receives and runs the epilogue for its own half
         f32x4_t* red = (f32x4_t*)&stage[0][0][0][0][0];
-        if (kg == 1) {
 #pragma unroll
-            for (int j = 0; j < CW; ++j)
+        for (int j = 0; j < CW; ++j)
 #pragma unroll
-                for (int m = 0; m < 4; ++m) red[((w * 4 + j) * 4 + m) * 64 + lane] = acc[j][m];
-        }
+            for (int mm = 0; mm < 2; ++mm) red[((w8 * 4 + j) * 2 + mm) * 64 + lane] = kg == 1 ? acc[j][mm] : acc[j][2 + mm];
         __syncthreads();
-        if (kg == 0) {
+        const int pw = kg == 0 ? w + 4 : w;             // the wave of the other group with the same n-tiles
 #pragma unroll
-            for (int j = 0; j < CW; ++j)
+        for (int j = 0; j < CW; ++j)
 #pragma unroll
-                for (int m = 0; m < 4; ++m) acc[j][m] += red[((w * 4 + j) * 4 + m) * 64 + lane];
-        }
+            for (int mm = 0; mm < 2; ++mm) {
+                const f32x4_t o = red[((pw * 4 + j) * 2 + mm) * 64 + lane];
+                if (kg == 0) acc[j][mm] += o; else acc[j][2 + mm] += o;
+            }
         __syncthreads();
     }
-    const bool act = !KSPLIT || kg == 0;                 // waves that store results
     // ---- epilogue: acc[j][m]: rows (mt0 + m) * 16 + lm, columns (nt0 + j) * 16 + 4 * g4 + r
     float best[4]; int bidx[4];
     float rscale[4];
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(KG == 1 ? 256 : 512, KG == 1 ? 2 : 1) void k_gemm25
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         const int row = (mt0 + m) * 16 + lm;
-        const bool rok = act && mt0 + m < MT && row < a.M;
+        const bool rok = (!KSPLIT || kg == (m >> 1)) && mt0 + m < MT && row < a.M;
         if (EPI == EPI_QKV && m + 1 < 4) qfactors(m + 1, qc[(m + 1) & 1], qs[(m + 1) & 1]);
 #pragma unroll
         for (int j = 0; j < CW; ++j) {
@@ -388,7 +388,7 @@ __global__ __launch_bounds__(KG == 1 ? 256 : 512, KG == 1 ? 2 : 1) void k_gemm25
                 const float ov = __shfl_xor(best[m], o, 64); const int oi = __shfl_xor(bidx[m], o, 64);
                 if (ov > best[m] || (ov == best[m] && oi < bidx[m])) { best[m] = ov; bidx[m] = oi; }
             }
-            if (g4 == 0 && act) { amv[CSPLIT ? w8 : w][m * 16 + lm] = best[m]; ami[CSPLIT ? w8 : w][m * 16 + lm] = bidx[m]; }
+            if (g4 == 0 && (!KSPLIT || kg == (m >> 1))) { amv[CSPLIT ? w8 : w][m * 16 + lm] = best[m]; ami[CSPLIT ? w8 : w][m * 16 + lm] = bidx[m]; }
         }
         __syncthreads();
         if (tid < 64) {
