@@ -183,14 +183,15 @@ enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLAN
                                       * splits, ceil(blocks / value) work on a sequence, the rest exit */
        /* K slices per column owner of the column-owner GEMM for the O / down projections (1..8; the
         * workgroup count must be a multiple of it) */
-       FASTCOT_OPT_KS_O = 32, FASTCOT_OPT_KS_DOWN = 33,
+       FASTCOT_OPT_KS_O = 32, FASTCOT_OPT_KS_DOWN = 33, FASTCOT_OPT_KS_QKV = 36, FASTCOT_OPT_KS_GU = 37,
        FASTCOT_OPT_CO_SINGLE = 27,   /* weight batches in flight per wave of the column-owner GEMM: 1 = one, 0 = two,
                                       * 2 (default) = chosen per GEMM */
-       /* 1 (default): at the first fastcot_prefill of a step shape with at most 32 rows, every column-owner
-        * GEMM is timed on the model's own matrices (a few ms) with one / two batches in flight, plain / rotated
-        * batch order and 1 / 2 / 4 K slices per owner, and the fastest combination is kept (results do not
-        * depend on the choice beyond the order of a few fp32 additions).  Setting any of the NW, KS or CO_SINGLE
-        * options turns it off: explicit choices win. */
+       /* 1 (default): at the first fastcot_prefill of a step shape with at most 32 rows, the column-owner GEMMs that
+        * walk K in plain order (QKV, O) are timed on the model's own matrices with one / two weight batches in flight
+        * or the whole K slice requested up front, and the fastest is kept.  The choice moves loads, not additions:
+        * logits are the same bits whichever wins, in every process.  Everything that fixes the order of the fp32
+        * additions (K slices per owner, batch order) is chosen from the model shape alone.  Setting any of the NW,
+        * KS or CO_SINGLE options turns the measurement off: explicit choices win. */
        FASTCOT_OPT_AUTOTUNE = 34,
        /* 1 (default): whenever fastcot_generate finds finished sequences at one of its checks, they trade slots
         * (state and K/V cache) with unfinished ones so that the following steps run only the unfinished
@@ -235,11 +236,29 @@ int fastcot_attn_window(const float* d_q, const void* d_k_cache, const void* d_v
                         int32_t H, int32_t Hkv, int32_t Dh, int32_t max_seq, int32_t dtype, float* d_out,
                         void* d_scratch, void* hip_stream);
 
-/* Measurement aid: one plain streaming read of `bytes` (multiple of 16) device bytes at d_src (16-byte
- * aligned); d_sink16 is a 16-byte device scratch the kernel may write.  Timed by the caller, it gives the
- * read bandwidth the device delivers to the simplest kernel: a second denominator beside the published
- * HBM peak. */
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): fastcot_attn_window with the kernel's scratch (split-key partial results and arrival
+ * counters) in an array built into the library instead of a caller buffer.  Arguments and results as for
+ * fastcot_attn_window.  Limits: H <= 64 query heads and W <= 16 window rows (FASTCOT_ECAPACITY beyond, with a
+ * text in fastcot_last_error(NULL)); the array is about 8.5 MiB per GPU the library runs on, held until the
+ * process ends.  The call allocates nothing and frees nothing.  All calls on one GPU share that GPU's array:
+ * calls that overlap in time on one GPU (different streams or threads) race and give undefined results. */
+int fastcot_attn_window_noalloc(const float* d_q, const void* d_k_cache, const void* d_vt_cache, int32_t n, int32_t W,
+                                int32_t H, int32_t Hkv, int32_t Dh, int32_t max_seq, int32_t dtype, float* d_out,
+                                void* hip_stream);
+
+/* Measurement aids.  fastcot_stream_read: one plain streaming read of `bytes` (multiple of 16) device bytes at
+ * d_src (16-byte aligned), shaped like the weight stream of the step's GEMMs (one workgroup per compute unit,
+ * contiguous kilobytes per wave, 16 loads in flight); d_sink16 is a 16-byte device scratch the kernel may
+ * write.  Timed by the caller, it gives the read bandwidth the device delivers to the simplest kernel: a
+ * second denominator beside the published HBM peak.  fastcot_stream_read_chain: n_launches such launches back
+ * to back, launch i reading launch_bytes[i] (host array; rounded down to whole kilobytes, each at most
+ * src_bytes) from consecutive parts of the src_bytes at d_src (wrapping around): with the byte counts of a
+ * step's kernels this is what the step would cost if every kernel only read its weights -- the floor of a
+ * step made of separate launches. */
 int fastcot_stream_read(const void* d_src, size_t bytes, void* d_sink16, void* hip_stream);
+int fastcot_stream_read_chain(const void* d_src, size_t src_bytes, const uint64_t* launch_bytes, int32_t n_launches,
+                              void* d_sink16, void* hip_stream);
 
 /* LM head fused with argmax (Eq. 1/2, lowest id on ties): act device fp32 [M][d] (already
  * normalised), packed W_lm as written by fastcot_lmhead_pack from canonical bf16 [d][V];

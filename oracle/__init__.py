@@ -55,6 +55,9 @@ def lib(real: str = "f64"):
         L.oracle_session_len.argtypes = [vp]
         L.oracle_session_set_len.argtypes = [vp, i32]
         L.oracle_forward.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, vp, vp, vp]
+        L.oracle_embed.argtypes = [vp, vp, ctypes.c_int, vp]
+        L.oracle_layers.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
+        L.oracle_head.argtypes = [vp, vp, ctypes.c_int, vp, vp]
         L.oracle_verify.argtypes = [vp, vp, i32]
         L.oracle_verify.restype = i32
         L.oracle_greedy_ar.argtypes = [vp, vp, i32, i32, i32, vp]
@@ -166,6 +169,62 @@ class Session:
                                    hidden.ctypes.data if want_hidden else None)
         assert rc == 0, rc
         return logits, amax, hidden
+
+
+def forward_streamed(shape_fields: dict, wdtype: int, global_weights: dict, layer_weights, sequences, max_seq: int,
+                     real: str = "f64", progress=None):
+    """The forward of Session.forward for models whose weights do not fit the host: one layer's weights at a time.
+
+    global_weights: dict with 'emb', 'wlm' (and optionally 'gf').  layer_weights(l) -> dict name -> array for
+    'wq','wk','wv','wo','wg','wu','wd' (optionally 'g1','g2') of layer l; it is called once per layer and the
+    arrays are dropped afterwards.  sequences: list (one entry per sequence) of lists of passes
+    (tokens, pos0, want_logits); the passes of a sequence run in order on one K/V cache, exactly as successive
+    Session.forward calls would (a layer's K/V depends on no other layer's, so running all passes of a sequence
+    through layer l before layer l+1 computes the same values).  Returns, per sequence and pass,
+    (logits [R, V] float64 or None, argmax [R] or None).  Built from oracle_embed / oracle_layers /
+    oracle_head, the bodies oracle_forward itself is made of."""
+    L = lib(real)
+    f0 = dict(shape_fields, n_layers=0)
+    g = {k: v for k, v in global_weights.items() if k in ("emb", "wlm", "gf")}
+    m0 = Model(f0, g, wdtype=wdtype, real=real)
+    d, V = shape_fields["d_model"], shape_fields["vocab"]
+    xs = []
+    for passes in sequences:
+        row = []
+        for tok, pos0, _ in passes:
+            tok = _i32(tok)
+            x = np.empty((len(tok), d), dtype=np.float64)
+            assert L.oracle_embed(m0.h, tok.ctypes.data, len(tok), x.ctypes.data) == 0
+            row.append(x)
+        xs.append(row)
+    f1 = dict(shape_fields, n_layers=1)
+    for l in range(shape_fields["n_layers"]):
+        w = layer_weights(l)
+        m1 = Model(f1, {k: [v] for k, v in w.items()}, wdtype=wdtype, real=real)
+        for si, passes in enumerate(sequences):
+            ss = m1.session(max_seq)
+            for pi, (tok, pos0, _) in enumerate(passes):
+                x = xs[si][pi]
+                assert L.oracle_layers(ss.h, 0, 1, x.shape[0], int(pos0), x.ctypes.data) == 0
+            del ss
+        del m1, w
+        if progress:
+            progress(l)
+    out = []
+    for si, passes in enumerate(sequences):
+        row = []
+        for pi, (tok, pos0, want) in enumerate(passes):
+            if not want:
+                row.append((None, None))
+                continue
+            x = xs[si][pi]
+            R = x.shape[0]
+            logits = np.empty((R, V), dtype=np.float64)
+            amax = np.empty(R, dtype=np.int32)
+            assert L.oracle_head(m0.h, x.ctypes.data, R, logits.ctypes.data, amax.ctypes.data) == 0
+            row.append((logits, amax))
+        out.append(row)
+    return out
 
 
 def verify(w, o, real: str = "f64") -> int:

@@ -239,20 +239,21 @@ void oracle_lmhead_argmax(const double* act, const void* W, int wdtype, int M, i
  * positions 0 .. pos0 + r (its own K/V included), i.e. the committed prefix plus the window
  * slots before it -- the causal-mask formulation of Eq. (2)/(4).  K/V of all R rows are
  * written at their positions; whether they become final is the caller's decision (n).
- * Outputs (nullable): logits [R][vocab] as double, amax [R], hidden [R][d] (residual stream
- * after the last layer, before the final norm) as double.  Returns 0, or -1 on bad arguments.
+ * oracle_forward is made of three bodies -- embedding rows, decoder layers, final norm + LM head --
+ * which oracle_embed / oracle_layers / oracle_head below expose one by one.
  */
-int oracle_forward(oracle_session* ss, const int32_t* tok, int R, int pos0, double* logits,
-                   int32_t* amax, double* hidden) {
+static void embed_rows(const oracle_model* m, const int32_t* tok, int R, real* x) {
+    const int d = m->s.d_model;
+    for (int r = 0; r < R; ++r)
+        for (int i = 0; i < d; ++i) x[(size_t)r * d + i] = wval(m->emb, m->s.wdtype, (size_t)tok[r] * d + i);
+}
+
+/* decoder layers l0 .. l1-1 applied in place to the residual stream x [R][d] of rows at positions pos0.. */
+static void apply_layers(oracle_session* ss, int l0, int l1, int R, int pos0, real* x) {
     const oracle_model* m = ss->m;
     const oracle_shape* s = &m->s;
-    const int d = s->d_model, H = s->n_heads, Hkv = s->n_kv_heads, Dh = s->head_dim, F = s->d_ffn,
-              V = s->vocab, L = s->n_layers;
+    const int d = s->d_model, H = s->n_heads, Hkv = s->n_kv_heads, Dh = s->head_dim, F = s->d_ffn;
     const int qd = H * Dh, kvd = Hkv * Dh, group = H / Hkv;
-    if (R <= 0 || pos0 < 0 || pos0 + R > ss->max_seq || Dh > 512) return -1;
-    for (int r = 0; r < R; ++r) if (tok[r] < 0 || tok[r] >= V) return -1;
-
-    real* x = (real*)malloc((size_t)R * d * sizeof(real));
     real* nx = (real*)malloc((size_t)R * d * sizeof(real));
     real* q = (real*)malloc((size_t)R * qd * sizeof(real));
     real* kx = (real*)malloc((size_t)R * kvd * sizeof(real));
@@ -262,10 +263,7 @@ int oracle_forward(oracle_session* ss, const int32_t* tok, int R, int pos0, doub
     real* gate = (real*)malloc((size_t)R * F * sizeof(real));
     real* up = (real*)malloc((size_t)R * F * sizeof(real));
 
-    for (int r = 0; r < R; ++r)
-        for (int i = 0; i < d; ++i) x[(size_t)r * d + i] = wval(m->emb, s->wdtype, (size_t)tok[r] * d + i);
-
-    for (int l = 0; l < L; ++l) {
+    for (int l = l0; l < l1; ++l) {
         real* kcl = ss->kc + (size_t)l * ss->max_seq * kvd;
         real* vcl = ss->vc + (size_t)l * ss->max_seq * kvd;
         /* attention block */
@@ -301,19 +299,77 @@ int oracle_forward(oracle_session* ss, const int32_t* tok, int R, int pos0, doub
         matmul_rows(m->w[T_WD][l], s->wdtype, F, d, gate, R, proj);
         for (size_t i = 0; i < (size_t)R * d; ++i) x[i] += proj[i];
     }
-    if (hidden) for (size_t i = 0; i < (size_t)R * d; ++i) hidden[i] = (double)x[i];
+    free(nx); free(q); free(kx); free(vx); free(att); free(proj); free(gate); free(up);
+}
 
-    if (logits || amax) {
-        real* lg = (real*)malloc((size_t)R * V * sizeof(real));
-        for (int r = 0; r < R; ++r) oracle_rmsnorm(x + (size_t)r * d, m->gf, d, s->rms_eps, nx + (size_t)r * d);
-        matmul_rows(m->wlm, s->wdtype, d, V, nx, R, lg);
-        for (int r = 0; r < R; ++r) {
-            if (amax) amax[r] = oracle_argmax(lg + (size_t)r * V, V);
-            if (logits) for (int n = 0; n < V; ++n) logits[(size_t)r * V + n] = (double)lg[(size_t)r * V + n];
-        }
-        free(lg);
+/* final norm, LM head, argmax of the residual stream x [R][d]; logits [R][vocab] as double and amax [R] nullable */
+static void head_rows(const oracle_model* m, const real* x, int R, double* logits, int32_t* amax) {
+    const int d = m->s.d_model, V = m->s.vocab;
+    real* nx = (real*)malloc((size_t)R * d * sizeof(real));
+    real* lg = (real*)malloc((size_t)R * V * sizeof(real));
+    for (int r = 0; r < R; ++r) oracle_rmsnorm(x + (size_t)r * d, m->gf, d, m->s.rms_eps, nx + (size_t)r * d);
+    matmul_rows(m->wlm, m->s.wdtype, d, V, nx, R, lg);
+    for (int r = 0; r < R; ++r) {
+        if (amax) amax[r] = oracle_argmax(lg + (size_t)r * V, V);
+        if (logits) for (int n = 0; n < V; ++n) logits[(size_t)r * V + n] = (double)lg[(size_t)r * V + n];
     }
-    free(x); free(nx); free(q); free(kx); free(vx); free(att); free(proj); free(gate); free(up);
+    free(nx); free(lg);
+}
+
+static int rows_ok(const oracle_session* ss, const int32_t* tok, int R, int pos0) {
+    if (R <= 0 || pos0 < 0 || pos0 + R > ss->max_seq || ss->m->s.head_dim > 512) return 0;
+    if (tok) for (int r = 0; r < R; ++r) if (tok[r] < 0 || tok[r] >= ss->m->s.vocab) return 0;
+    return 1;
+}
+
+/* Outputs (nullable): logits [R][vocab] as double, amax [R], hidden [R][d] (residual stream
+ * after the last layer, before the final norm) as double.  Returns 0, or -1 on bad arguments. */
+int oracle_forward(oracle_session* ss, const int32_t* tok, int R, int pos0, double* logits,
+                   int32_t* amax, double* hidden) {
+    const oracle_model* m = ss->m;
+    const int d = m->s.d_model;
+    if (!rows_ok(ss, tok, R, pos0)) return -1;
+    real* x = (real*)malloc((size_t)R * d * sizeof(real));
+    embed_rows(m, tok, R, x);
+    apply_layers(ss, 0, m->s.n_layers, R, pos0, x);
+    if (hidden) for (size_t i = 0; i < (size_t)R * d; ++i) hidden[i] = (double)x[i];
+    if (logits || amax) head_rows(m, x, R, logits, amax);
+    free(x);
+    return 0;
+}
+
+/* The same forward in three calls, so that a caller can hold the weights of one layer at a time (models whose
+ * weights do not fit the host): oracle_embed gives the residual stream x [R][d] of the rows (as double: exact
+ * for either build of `real`), oracle_layers applies layers l0 .. l1-1 to it in place (writing their K/V at
+ * positions pos0.. of the session, as oracle_forward does), oracle_head gives logits and argmax.  The three are
+ * the bodies oracle_forward itself is made of.  Return 0, or -1 on bad arguments. */
+int oracle_embed(const oracle_model* m, const int32_t* tok, int R, double* x) {
+    const int d = m->s.d_model;
+    if (R <= 0) return -1;
+    for (int r = 0; r < R; ++r) if (tok[r] < 0 || tok[r] >= m->s.vocab) return -1;
+    real* xr = (real*)malloc((size_t)R * d * sizeof(real));
+    embed_rows(m, tok, R, xr);
+    for (size_t i = 0; i < (size_t)R * d; ++i) x[i] = (double)xr[i];
+    free(xr);
+    return 0;
+}
+int oracle_layers(oracle_session* ss, int l0, int l1, int R, int pos0, double* x) {
+    const int d = ss->m->s.d_model;
+    if (!rows_ok(ss, NULL, R, pos0) || l0 < 0 || l1 > ss->m->s.n_layers || l0 > l1) return -1;
+    real* xr = (real*)malloc((size_t)R * d * sizeof(real));
+    for (size_t i = 0; i < (size_t)R * d; ++i) xr[i] = (real)x[i];
+    apply_layers(ss, l0, l1, R, pos0, xr);
+    for (size_t i = 0; i < (size_t)R * d; ++i) x[i] = (double)xr[i];
+    free(xr);
+    return 0;
+}
+int oracle_head(const oracle_model* m, const double* x, int R, double* logits, int32_t* amax) {
+    const int d = m->s.d_model;
+    if (R <= 0) return -1;
+    real* xr = (real*)malloc((size_t)R * d * sizeof(real));
+    for (size_t i = 0; i < (size_t)R * d; ++i) xr[i] = (real)x[i];
+    head_rows(m, xr, R, logits, amax);
+    free(xr);
     return 0;
 }
 

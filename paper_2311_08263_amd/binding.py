@@ -67,8 +67,10 @@ SYMBOLS = {
     "fastcot_set_windows": (ctypes.c_int, [vp, vp]),
     "fastcot_answer": (ctypes.c_int, [vp, vp, i32, i32, i32, vp, vp]),
     "fastcot_stream_read": (ctypes.c_int, [vp, ctypes.c_size_t, vp, vp]),
+    "fastcot_stream_read_chain": (ctypes.c_int, [vp, ctypes.c_size_t, vp, i32, vp, vp]),
     "fastcot_kv_scatter": (ctypes.c_int, [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]),
     "fastcot_attn_window": (ctypes.c_int, [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]),
+    "fastcot_attn_window_noalloc": (ctypes.c_int, [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]),
     "fastcot_lmhead_packed_bytes": (sz, [i32, i32]),
     "fastcot_lmhead_scratch_bytes": (sz, [i32, i32, i32]),
     "fastcot_lmhead_pack": (ctypes.c_int, [vp, i32, i32, vp, vp]),
@@ -324,6 +326,20 @@ def attn_window(q, kc, vc, n: int, scratch=None):
     return out
 
 
+def attn_window_noalloc(q, kc, vc, n: int, out=None):
+    """attn_window through the entry point that allocates nothing (scratch built into the library); `out` may be
+    a preallocated fp32 [W, H*Dh] device tensor."""
+    torch = _torch()
+    W, H, Dh = q.shape
+    Hkv, max_seq = kc.shape[0], kc.shape[1] * 32
+    dt = 0 if kc.dtype == torch.float32 else 1
+    if out is None:
+        out = torch.empty(W, H * Dh, dtype=torch.float32, device="cuda")
+    _check(lib().fastcot_attn_window_noalloc(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), n, W, H, Hkv, Dh, max_seq, dt,
+                                             out.data_ptr(), _stream_ptr()))
+    return out
+
+
 def stream_read(buf, sink=None):
     """One plain streaming read over the device tensor `buf` on torch's current stream."""
     torch = _torch()
@@ -332,6 +348,17 @@ def stream_read(buf, sink=None):
     nbytes = (buf.numel() * buf.element_size()) // 16 * 16
     _check(lib().fastcot_stream_read(buf.data_ptr(), nbytes, sink.data_ptr(), _stream_ptr()))
     return nbytes
+
+
+def stream_read_chain(buf, launch_bytes, sink=None):
+    """Back-to-back plain streaming reads of launch_bytes[i] bytes each over `buf` on torch's current stream."""
+    torch = _torch()
+    if sink is None:
+        sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    lb = np.ascontiguousarray(launch_bytes, dtype=np.uint64)
+    _check(lib().fastcot_stream_read_chain(buf.data_ptr(), buf.numel() * buf.element_size(), lb.ctypes.data, int(lb.size),
+                                           sink.data_ptr(), _stream_ptr()))
+    return int((lb // 1024 * 1024).sum())
 
 
 def lmhead_pack(w_bf16):

@@ -51,6 +51,7 @@ static int fail(fastcot_ctx* c, int code, const char* fmt, const char* a = "", l
     if (c) snprintf(g_err, 512, "%s", dst);
     return code;
 }
+void fc_set_error(const char* msg) { snprintf(g_err, 512, "%s", msg); }
 #define HIPCHK(c, call)                                                                          \
     do {                                                                                         \
         hipError_t e_ = (call);                                                                  \
@@ -285,11 +286,13 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
         if (value > 0 && (value % ks || value / ks > NT || (NT + value / ks - 1) / (value / ks) > 8))
             return fail(c, FASTCOT_EINVAL, "workgroups of the column-owner GEMM do not fit its K slices per owner%s");
         c->plan.nw[gi] = value; c->opt_tune = 0;
-    } else if (option == FASTCOT_OPT_KS_O || option == FASTCOT_OPT_KS_DOWN) {
-        const int gi = option == FASTCOT_OPT_KS_O ? 1 : 3, NT = c->kd.d / 16, nw = c->plan.nw[gi];
-        const int K = gi == 1 ? c->kd.H * c->kd.Dh : c->kd.F;
+    } else if (option == FASTCOT_OPT_KS_O || option == FASTCOT_OPT_KS_DOWN || option == FASTCOT_OPT_KS_QKV || option == FASTCOT_OPT_KS_GU) {
+        const int gi = option == FASTCOT_OPT_KS_QKV ? 0 : (option == FASTCOT_OPT_KS_O ? 1 : (option == FASTCOT_OPT_KS_GU ? 2 : 3));
+        const int nts[4] = {c->kd.qkvN / 16, c->kd.d / 16, 2 * c->kd.F / 16, c->kd.d / 16};
+        const int Ks[4] = {c->kd.d, c->kd.H * c->kd.Dh, c->kd.d, c->kd.F};
+        const int NT = nts[gi], nw = c->plan.nw[gi], K = Ks[gi];
         if (value < 1 || value > 8 || K / 256 < value) return fail(c, FASTCOT_EINVAL, "K slices per owner out of range%s");
-        if (nw > 0 && (nw % value || nw / value > NT || nw / value < 1 || (NT + nw / value - 1) / (nw / value) > 8))
+        if (nw > 0 && (nw % value || nw / value > NT || nw / value < 1 || (NT + nw / value - 1) / (nw / value) > 12))
             return fail(c, FASTCOT_EINVAL, "K slices per owner do not fit the workgroup count of that GEMM%s");
         c->plan.ks[gi] = value; c->opt_tune = 0;
     } else if (option == FASTCOT_OPT_CO_SINGLE) {

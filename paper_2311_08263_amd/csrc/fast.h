@@ -46,8 +46,8 @@ void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t
 void fc_fast_plan(const KernelDims& kd, FastPlan* plan);
 hipError_t fc_fast_forward(const FastArgs& a);
 // Times every column-owner GEMM of the pass shape a.kd (at most 32 rows) with one and with two weight batches in
-// flight per wave or the wave's whole K slice at once, plain and rotated batch order and, for the residual GEMMs, 1, 2 or 4 K slices per owner, and
-// records the fastest combination in the plan.  Overwrites activations and layer 0's first cache rows:
+// flight per wave or the wave's whole K slice at once and records the fastest in the plan.  Only that choice is
+// measured: it moves loads, not additions, so the results are the same bits whichever wins.  Overwrites activations and layer 0's first cache rows:
 // call it before a prefill.  Synchronises the stream.
 hipError_t fc_fast_tune(FastArgs a, FastPlan* plan);
 

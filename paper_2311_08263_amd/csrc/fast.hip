@@ -168,7 +168,7 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         const int ksl = a.tune_gi >= 0 ? a.tune_ks : (M <= 16 ? a.plan->ks[gi] : a.plan->ks2[gi]);
         if (nw > 0) {
             co.W = (const bf16_t*)W; co.K = K; co.NT = N / 16; co.X = X; co.ldx = ldx; co.gain = gain; co.out = out; co.ldo = ldo;
-            co.layer = g.layer; co.ks = epi == EPI_RESID ? ksl : 1;
+            co.layer = g.layer; co.ks = epi != EPI_LMHEAD ? ksl : 1;
             // one or two weight batches in flight per wave: which is faster depends on the GEMM and on the shape
             // (7B: two for down and LM head; 13B: two for QKV and gate/up, one for down), so it is a plan entry
             co.single_buffer = a.tune_gi >= 0 ? a.tune_sb : (a.plan->co_single == 2 ? a.plan->co_sb[M > 16][gi] : a.plan->co_single);
@@ -296,32 +296,33 @@ hipError_t fc_fast_tune(FastArgs a, FastPlan* plan) {
         if (r == hipSuccess) r = hipEventElapsedTime(ms, e0, e1);
         return r;
     };
+    // Only the number of weight batches in flight is measured, and only for the GEMMs that walk their batches in
+    // plain order: there it changes when loads are issued, never the order in which a wave adds its k-tiles, so
+    // every choice gives the same bits.  The K slices per owner and the batch order do change the order of the
+    // fp32 additions, and so does the batch size of a GEMM that walks its batches in rotated order: all of those
+    // stay as fc_fast_plan fixed them from the shape.  Two processes therefore compute identical logits whatever
+    // their timings were.
     for (int gi = 0; gi < 5 && e == hipSuccess; ++gi) {
         const int nw = cls ? plan->nw2[gi] : plan->nw[gi];
         if (nw <= 0) continue;                      // not a column-owner launch
-        const bool resid = gi == 1 || gi == 3;
         float best = 1e30f;
-        int best_sb = plan->co_sb[cls][gi], best_rot = plan->co_rot[cls][gi], best_ks = cls ? plan->ks2[gi] : plan->ks[gi];
-        a.tune_gi = gi;
-        for (int ks = 1; ks <= (resid ? 4 : 1) && e == hipSuccess; ks *= 2)
-            for (int rot = 0; rot < 2 && e == hipSuccess; ++rot)
-                for (int sb = 0; sb < 3 && e == hipSuccess; ++sb) {      // two batches, one batch, the whole slice at once
-                    if (sb == 2 && rot) continue;                          // (which has no batch order)
-                    a.tune_ks = ks; a.tune_rot = rot; a.tune_sb = sb;
-                    float t = 1e30f;
-                    for (int rep = 0; rep < 3 && e == hipSuccess; ++rep) {
-                        float ms = 0.f;
-                        const hipError_t r = measure(&ms);
-                        if (r == hipErrorInvalidValue) { t = 1e30f; break; }
-                        e = r;
-                        if (e == hipSuccess && ms < t) t = ms;
-                    }
-                    if (e == hipSuccess && t < best) { best = t; best_sb = sb; best_rot = rot; best_ks = ks; }
-                }
-        if (e == hipSuccess && best < 1e29f) {
-            plan->co_sb[cls][gi] = best_sb; plan->co_rot[cls][gi] = best_rot;
-            if (cls) plan->ks2[gi] = best_ks; else plan->ks[gi] = best_ks;
+        int best_sb = plan->co_sb[cls][gi];
+        const int rot = plan->co_rot[cls][gi], ks = cls ? plan->ks2[gi] : plan->ks[gi];
+        if (rot) continue;
+        a.tune_gi = gi; a.tune_ks = ks; a.tune_rot = rot;
+        for (int sb = 0; sb < 3 && e == hipSuccess; ++sb) {      // two batches, one batch, the whole slice at once
+            a.tune_sb = sb;
+            float t = 1e30f;
+            for (int rep = 0; rep < 3 && e == hipSuccess; ++rep) {
+                float ms = 0.f;
+                const hipError_t r = measure(&ms);
+                if (r == hipErrorInvalidValue) { t = 1e30f; break; }
+                e = r;
+                if (e == hipSuccess && ms < t) t = ms;
+            }
+            if (e == hipSuccess && t < best) { best = t; best_sb = sb; }
         }
+        if (e == hipSuccess) plan->co_sb[cls][gi] = best_sb;
     }
     (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
     return e;

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int lm = lane & 15, g4 = lane >> 4;
     // workgroup i owns n-tiles [i*NT/G, (i+1)*NT/G): at most NW of them
-    const int ks = (EPI == EPI_RESID && a.ks > 1) ? a.ks : 1;
+    const int ks = (EPI != EPI_LMHEAD && a.ks > 1) ? a.ks : 1;
     const int G = gridDim.x / ks, owner = blockIdx.x / ks, slice = blockIdx.x % ks;
     const int nt0 = (int)(((unsigned)owner * (unsigned)a.NT) / (unsigned)G);
     const int nt1 = (int)(((unsigned)(owner + 1) * (unsigned)a.NT) / (unsigned)G);
@@ -284,12 +284,11 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     int ntf[NF];
     bool fin[NF];
     f32x4_t v[NF];
-    float rs = 1.0f;
+    float rs = 1.0f, ssrow = 0.f;
     if (a.gain) {
-        float s = 0.f;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) s += lds_ss[(q * MT + tm) * 16 + lm];
-        rs = 1.0f / sqrtf(s / (float)a.K + a.eps);
+        for (int q = 0; q < 8; ++q) ssrow += lds_ss[(q * MT + tm) * 16 + lm];
+        rs = 1.0f / sqrtf(ssrow / (float)a.K + a.eps);
     }
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
@@ -300,25 +299,37 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         if (fin[f]) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) v[f] += lds_part[(q * TW + ti) * 64 + lane];
-            v[f] *= rs;
+            if (ks == 1) v[f] *= rs;
         }
     }
-    if (EPI == EPI_RESID && ks > 1) {
-        // partial tiles of the ks slices meet through memory; the last workgroup to arrive adds them
+    if (EPI != EPI_LMHEAD && ks > 1) {
+        // partial tiles of the ks slices (and, with a norm in front, each slice's share of the row sums of
+        // squares) meet through memory; the last workgroup to arrive adds them in slice order
 #pragma unroll
         for (int f = 0; f < NF; ++f) {
             float* mine = a.xpart + ((size_t)blockIdx.x * (8 * NF) + w + 8 * f) * 256 + lane * 4;
             if (fin[f]) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) st_agent_f32(mine + r, v[f][r]);
+                st_agent_f32x2(mine, v[f][0], v[f][1]);
+                st_agent_f32x2(mine + 2, v[f][2], v[f][3]);
             }
         }
+        float* sspart = a.xpart + (size_t)gridDim.x * (8 * NF) * 256;       // [workgroup][MT * 16]
+        if (a.gain && w < MT && g4 == 0) st_agent_f32(sspart + (size_t)blockIdx.x * (MT * 16) + tm * 16 + lm, ssrow);
         wait_vmem_done();
         __syncthreads();
         int* flag = (int*)lds_ss;
         if (tid == 0) *flag = arrive_agent(a.xcnt + owner);
         __syncthreads();
         if (*flag != ks - 1) return;
+        if (a.gain) {
+            float s = 0.f;
+#pragma unroll
+            for (int s2 = 0; s2 < 8; ++s2) {
+                const float p = ld_agent_f32(sspart + (size_t)(owner * ks + (s2 < ks ? s2 : 0)) * (MT * 16) + tm * 16 + lm);
+                if (s2 < ks) s += p;
+            }
+            rs = 1.0f / sqrtf(s / (float)a.K + a.eps);
+        }
 #pragma unroll
         for (int f = 0; f < NF; ++f) {
             if (!fin[f]) continue;
@@ -326,12 +337,15 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
 #pragma unroll
             for (int s2 = 0; s2 < 8; ++s2) {
                 const float* src = a.xpart + ((size_t)(owner * ks + (s2 < ks ? s2 : 0)) * (8 * NF) + w + 8 * f) * 256 + lane * 4;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) part[s2][r] = ld_agent_f32(src + r);
+                float p0, p1, p2, p3;
+                ld_agent_f32x2(src, p0, p1);
+                ld_agent_f32x2(src + 2, p2, p3);
+                part[s2] = (f32x4_t){p0, p1, p2, p3};
             }
             v[f] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s2 = 0; s2 < 8; ++s2) if (s2 < ks) v[f] += part[s2];
+            v[f] *= rs;
         }
         if (tid == 0) st_agent_i32(a.xcnt + owner, 0);
     }
@@ -504,6 +518,7 @@ static hipError_t launch_epi(const GemmCoArgs& a, int G, hipStream_t st) {
     const int owners = G / (a.ks > 1 ? a.ks : 1);
     const int nw = (a.NT + owners - 1) / owners;  // most n-tiles any workgroup owns
     if (a.single_buffer == 2) return launch_deep<EPI>(a, G, nw, st);
+    if (a.M > 16 && nw > 8) return hipErrorInvalidValue;
     if (a.M > 16 && !a.single_buffer) {           // two row tiles, two batches in flight
         switch (nw) {
             case 1: return launch_k<EPI, 1, 2, true, 2>(a, G, st);
@@ -525,6 +540,10 @@ static hipError_t launch_epi(const GemmCoArgs& a, int G, hipStream_t st) {
             case 7: case 8: return launch_k<EPI, 8, 2, false, 2>(a, G, st);
         }
         return hipErrorInvalidValue;
+    }
+    if (nw > 8) {                                 // 9..12 n-tiles per workgroup (K slices per owner make them short)
+        if (nw > 12) return hipErrorInvalidValue;
+        return a.single_buffer ? launch_k<EPI, 12, 1, false, 1>(a, G, st) : launch_k<EPI, 12, 1, true, 1>(a, G, st);
     }
     if (a.single_buffer) {
         switch (nw) {
@@ -549,11 +568,11 @@ static hipError_t launch_epi(const GemmCoArgs& a, int G, hipStream_t st) {
 }
 
 hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st) {
-    const int ks = a.ks > 1 ? a.ks : 1, most = 8;
+    const int ks = a.ks > 1 ? a.ks : 1, most = a.M <= 16 ? 12 : 8;
     if (a.M < 1 || a.M > 32 || a.K % 256 || a.NT < 1 || G < 1 || ks > 8 || G % ks || G / ks > a.NT ||
         (a.NT + G / ks - 1) / (G / ks) > most || a.K / 256 < ks)
         return hipErrorInvalidValue;
-    if (ks > 1 && (epi != EPI_RESID || !a.xpart || !a.xcnt || G / ks > FC_MAX_COUNTERS)) return hipErrorInvalidValue;
+    if (ks > 1 && (epi == EPI_LMHEAD || !a.xpart || !a.xcnt || G / ks > FC_MAX_COUNTERS)) return hipErrorInvalidValue;
     switch (epi) {
         case EPI_RESID: return launch_epi<EPI_RESID>(a, G, st);
         case EPI_SWIGLU: return launch_epi<EPI_SWIGLU>(a, G, st);

@@ -2,6 +2,9 @@
 #pragma once
 #include "common.h"
 
+// text of the last failure of a context-less call (what fastcot_last_error(NULL) returns)
+void fc_set_error(const char* msg);
+
 // ---- plain kernels (one thread per output; used for fp32 models and as the on-device cross-check)
 hipError_t fc_embed(const void* emb, int dt, const int32_t* win, float* x, int M, int d, int V, hipStream_t st);
 hipError_t fc_rmsnorm_plain(const float* x, const float* g, float* out, int M, int d, float eps, hipStream_t st);

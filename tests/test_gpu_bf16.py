@@ -218,6 +218,40 @@ def test_deterministic_replay(fc):
         assert (r["ids"] == res[0]["ids"]).all() and (r["steps"] == res[0]["steps"]).all()
 
 
+@pytest.mark.parametrize("shape,B,W", [(synthgen.small_variant(synthgen.SHAPES["7b"], n_layers=3), 1, 16),
+                                       (synthgen.small_variant(synthgen.SHAPES["13b"], n_layers=2), 1, 32)])
+def test_fresh_contexts_give_identical_bits(fc, shape, B, W):
+    """Same inputs, same logits bits, same verified counts and lengths in any context: three contexts, each
+    measuring its own launch plan at its first prefill (the measurement may come out differently each time; it
+    only moves loads)."""
+    import torch
+    P, N = 70, 32
+    S = ((P + N + 2 * W + 31) // 32) * 32
+    cfg = fc.Config.from_shape(shape, B, S, W)
+    packed = fc.load_synth_weights(cfg, shape)
+    prompts = synthgen.prompts(B, P, shape.vocab, seed=71)
+    buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=72)
+    runs = []
+    for variant in range(3):
+        say(f"fresh context {variant}: d={shape.d_model} W={W}")
+        ctx = fc.Context(cfg, packed)
+        ctx.prefill(prompts, [P] * B, buf)
+        dbg = ctx.debug_logits(True)
+        steps = []
+        for s in range(3):
+            nacc, acc, win = ctx.step()
+            st = ctx.state()
+            steps.append((dbg.clone(), nacc.copy(), st["o"].copy(), st["K"].copy(), st["n"].copy()))
+        torch.cuda.synchronize()
+        runs.append(steps)
+        ctx.close()
+    for variant in (1, 2):
+        for a, b in zip(runs[0], runs[variant]):
+            assert torch.equal(a[0], b[0]), "logits differ between two fresh contexts"
+            for x, y in zip(a[1:], b[1:]):
+                assert (x == y).all()
+
+
 @pytest.mark.parametrize("n,W,H,Hkv", [(2048, 16, 32, 32), (0, 16, 4, 4), (37, 5, 8, 2), (1000, 32, 8, 1), (2031, 16, 4, 4)])
 def test_attention_isolation(fc, n, W, H, Hkv):
     """Kernel-isolation shape: K/V ~ N(0,1) in bf16, queries ~ N(0,1), causal inside the window."""

@@ -1,8 +1,13 @@
 """Full-size checks of the two larger benchmark configurations, in the launch configuration the benchmark
 times: Llama-2-13B-shaped bf16, batch 8 x prompt 1024 x window 32 (256 rows per step, the many-row kernels), and
-Llama-2-70B-shaped bf16 (64 query heads on 8 K/V heads), batch 1 x prompt 512 x window 16.  One oracle step at
-these sizes is minutes to hours of host time, so the oracle's part is done at these layer shapes with two layers
-(test_gpu_shapes.py) and here the full-depth models are held to properties that hold at any size:
+Llama-2-70B-shaped bf16 (64 query heads on 8 K/V heads), batch 1 x prompt 512 x window 16.  The oracle follows
+both at full depth (40 and 80 layers), one layer's weights on the host at a time: in the 13B batch one sequence
+has a short prompt (96 tokens) and the oracle follows it for three steps -- 95 prompt rows plus 3 x 32 window rows
+through every layer -- while the other seven sequences keep prompts of about 1000 tokens, so the step is the
+256-row many-row launch the benchmark times; the 70B run has a 24-token prompt followed for two steps (23 + 2 x 16
+rows).  Bar: |dlogit| <= 2e-2, the GPU's argmax equal to the oracle's wherever the oracle's margin exceeds 0.05,
+the integer path of every sequence exact.  Beyond that the full-depth models are held to properties that hold at
+any size:
 
 * a sequence computes the same thing alone as inside a batch (Eq. 2 couples no two sequences) -- alone it runs
   through the column-owner kernels, in the batch of 8 through the many-row kernels, so this is also a
@@ -19,7 +24,7 @@ import numpy as np
 import pytest
 
 import synthgen
-from gpu_util import margins, say
+from gpu_util import follow_streamed, margins, say
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
@@ -136,3 +141,48 @@ def test_70b_full_size():
             break
     ctx.debug_logits(False)
     print(f"70b full size: window 1 and window 16 agree on the first {upto} of {N} tokens")
+
+
+@pytest.mark.timeout(900)
+def test_13b_batch8_full_depth_against_the_oracle():
+    """40 layers, batch 8 x window 32 = 256 rows per step (the many-row kernels): sequence 3 has a 96-token prompt and
+    is followed by the oracle for three steps; the others have prompts of about 1000 tokens."""
+    import paper_2311_08263_amd as fc
+    shape = synthgen.SHAPES["13b"]
+    B, P, W, N = 8, 1024, 32, 64
+    S = P + N + 2 * W + 32
+    say("13b full depth: weights")
+    cfg = fc.Config.from_shape(shape, B, S, W)
+    packed = fc.load_synth_weights(cfg, shape)
+    prompts = synthgen.prompts(B, P, shape.vocab, seed=61)
+    buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=62)
+    lens = [P - 37 * b for b in range(B)]
+    lens[3] = 96
+    ctx = fc.Context(cfg, packed)
+    ctx.prefill(prompts, lens, buf)
+    r = follow_streamed(ctx, shape, prompts, lens, [3], 3, TOL, label="13b")
+    print(f"13b full depth: max |dlogit| {r['max_err']:.3e} over {r['rows']} rows ({r['low_margin_rows']} low-margin), "
+          f"K={r['K']}, oracle {r['oracle_s']:.0f}s")
+    assert r["rows"] == 3 * W
+    ctx.close()
+
+
+@pytest.mark.timeout(900)
+def test_70b_full_depth_against_the_oracle():
+    """80 layers, 64 query heads on 8 K/V heads, batch 1 x window 16: a 24-token prompt followed for two steps."""
+    import paper_2311_08263_amd as fc
+    shape = synthgen.SHAPES["70b"]
+    P, W, N = 24, 16, 32
+    S = 128
+    say("70b full depth: weights")
+    cfg = fc.Config.from_shape(shape, 1, S, W)
+    packed = fc.load_synth_weights(cfg, shape)
+    prompts = synthgen.prompts(1, P, shape.vocab, seed=63)
+    buf = synthgen.buffer_init(1, N + 2 * W, shape.vocab, seed=64)
+    ctx = fc.Context(cfg, packed)
+    ctx.prefill(prompts, [P], buf)
+    r = follow_streamed(ctx, shape, prompts, [P], [0], 2, TOL, label="70b")
+    print(f"70b full depth: max |dlogit| {r['max_err']:.3e} over {r['rows']} rows ({r['low_margin_rows']} low-margin), "
+          f"K={r['K']}, oracle {r['oracle_s']:.0f}s")
+    assert r["rows"] == 2 * W
+    ctx.close()

@@ -304,3 +304,89 @@ def test_stored_tiny_trajectory_is_reproduced():
     W, N = stored["config"]["window"], stored["config"]["new_tokens"]
     assert all(0 <= k <= W - 1 for k in stored["K"]) and len(stored["K"]) == stored["steps"]
     assert sum(k + 1 for k in stored["K"]) >= N > sum(k + 1 for k in stored["K"][:-1])
+
+
+@pytest.mark.parametrize("real", ["f64", "f32"])
+def test_layer_streamed_forward_is_the_forward_bit_for_bit(real):
+    """oracle.forward_streamed (one layer's weights at a time: oracle_embed / oracle_layers / oracle_head over
+    one-layer models) against Session.forward of the whole model, which the library pin above fixes: a prefill,
+    then two windowed passes of which the second rewinds over positions the first wrote (the K/V a Jacobi step
+    leaves past its accepted prefix), grouped K/V heads, random gains.  Equal to the last bit."""
+    shape = synthgen.ModelShape(3, 128, 4, 2, 32, 352, 512, dtype="f32")
+    model, weights = rand_gain_model(shape, seed=11, real=real)
+    toks = synthgen.tokens(40, 9, 0x77, shape.vocab)
+    passes = [(toks[:17], 0, False), (toks[17:25], 17, True), (toks[25:33], 20, True)]
+    ss = model.session(48)
+    want = []
+    for t, p0, wl in passes:
+        lg, am, _ = ss.forward(t, p0, want_logits=wl)
+        want.append((lg, am))
+    fields = dict(model.fields)
+    got = oracle.forward_streamed(fields, 0, {k: weights[k] for k in ("emb", "wlm", "gf")},
+                                  lambda l: {k: weights[k][l] for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2")},
+                                  [passes, passes[:2]], 48, real=real)
+    for seq in got:
+        assert seq[0] == (None, None)
+        for (lg, am), (wlg, wam) in zip(seq[1:], want[1:]):
+            assert (lg == wlg).all() and (am == wam).all()
+
+
+def test_oracle_and_generators_under_address_and_ub_sanitizers(tmp_path):
+    """Builds oracle/fastcot_oracle.c and synthgen/gen.c with -fsanitize=address,undefined into one host program
+    that generates a tiny model and runs a short Jacobi trajectory and the layer-range calls; any out-of-bounds
+    access, leak-free or not, or undefined operation aborts it."""
+    import os
+    import subprocess
+    here = os.path.dirname(os.path.abspath(__file__))
+    root = os.path.dirname(here)
+    main = tmp_path / "san_main.c"
+    main.write_text(r'''
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+typedef struct { int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab; float rms_eps, rope_base; int32_t wdtype; } oracle_shape;
+void* oracle_model_new(const oracle_shape*); void oracle_model_free(void*); int oracle_model_set(void*, int, int, const void*);
+void* oracle_session_new(const void*, int32_t); void oracle_session_free(void*);
+int oracle_forward(void*, const int32_t*, int, int, double*, int32_t*, double*);
+int oracle_embed(const void*, const int32_t*, int, double*); int oracle_layers(void*, int, int, int, int, double*);
+int oracle_head(const void*, const double*, int, double*, int32_t*);
+int oracle_jacobi_generate(const void*, const int32_t*, int32_t, int32_t*, int32_t, int32_t, int32_t, int32_t, int32_t, int32_t*, int32_t*, int32_t*, int32_t*, int32_t, int32_t*);
+int32_t oracle_greedy_ar(const void*, const int32_t*, int32_t, int32_t, int32_t, int32_t*);
+double synth_sigma_sum(void);
+void synth_tokens(int32_t*, size_t, uint64_t, uint64_t, int32_t);
+void synth_normal_bf16(uint16_t*, size_t, uint64_t, uint64_t, float);
+int main(void) {
+    oracle_shape s = {2, 64, 4, 2, 16, 96, 128, 1e-5f, 1e4f, 1};
+    const int d = 64, qd = 64, kvd = 32, F = 96, V = 128, L = 2;
+    void* m = oracle_model_new(&s);
+    float sc = (float)(0.05 / synth_sigma_sum());
+    size_t sizes[10] = {(size_t)V * d, (size_t)d * V, 0, (size_t)d * qd, (size_t)d * kvd, (size_t)d * kvd, (size_t)qd * d, (size_t)d * F, (size_t)d * F, (size_t)F * d};
+    uint16_t* keep[2 + 7 * 2]; int nk = 0;
+    for (int t = 0; t < 2; ++t) { uint16_t* w = malloc(sizes[t] * 2); synth_normal_bf16(w, sizes[t], 5, 100 + t, sc); oracle_model_set(m, t, -1, w); keep[nk++] = w; }
+    for (int l = 0; l < L; ++l) for (int t = 3; t < 10; ++t) { uint16_t* w = malloc(sizes[t] * 2); synth_normal_bf16(w, sizes[t], 5, l * 16 + t, sc); oracle_model_set(m, t, l, w); keep[nk++] = w; }
+    int32_t prompt[9], buf[40], out[16], Ks[16], tail[4], greedy[16], olen = 0, osteps = 0;
+    synth_tokens(prompt, 9, 1, 2, V); synth_tokens(buf, 40, 1, 3, V);
+    if (oracle_jacobi_generate(m, prompt, 9, buf, 40, 5, 16, 0, -1, out, &olen, &osteps, Ks, 16, tail)) return 2;
+    if (oracle_greedy_ar(m, prompt, 9, 16, -1, greedy) != 16 || olen != 16 || memcmp(out, greedy, 64)) return 3;
+    /* layer-range calls against the whole forward */
+    void* a = oracle_session_new(m, 16); void* b = oracle_session_new(m, 16);
+    double la[9 * 128], lb[9 * 128], x[9 * 64]; int32_t am[9];
+    if (oracle_forward(a, prompt, 9, 0, la, am, NULL)) return 4;
+    if (oracle_embed(m, prompt, 9, x) || oracle_layers(b, 0, 1, 9, 0, x) || oracle_layers(b, 1, 2, 9, 0, x) || oracle_head(m, x, 9, lb, am)) return 5;
+    if (memcmp(la, lb, sizeof(la))) return 6;
+    oracle_session_free(a); oracle_session_free(b);
+    for (int i = 0; i < nk; ++i) free(keep[i]);
+    oracle_model_free(m);
+    printf("sanitized run ok: %d tokens in %d steps\n", olen, osteps);
+    return 0;
+}
+''')
+    exe = tmp_path / "san_oracle"
+    subprocess.check_call(["gcc", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan", "-fopenmp",
+                           "-o", str(exe), str(main), os.path.join(root, "oracle", "fastcot_oracle.c"),
+                           os.path.join(root, "synthgen", "gen.c"), "-lm"])
+    env = dict(os.environ, OMP_NUM_THREADS="2", ASAN_OPTIONS="detect_leaks=1")
+    r = subprocess.run([str(exe)], env=env, capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "sanitized run ok" in r.stdout
