@@ -34,11 +34,11 @@ def test_attn_window_noalloc_matches_attn_window():
     out_small = torch.empty(7, 8 * 128, dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
     say("no-alloc attention: 2048 keys x 32 heads x 16 rows, then 300 keys x 8 heads (2 K/V heads) x 7 rows")
-    mem0 = torch.cuda.memory_allocated()
+    allocs0 = torch.cuda.memory_stats()["allocation.all.allocated"]       # allocations made so far (never decreases)
     fc.attn_window_noalloc(big[3], big[4], big[5], 2048, out=out_big)
     fc.attn_window_noalloc(small[3], small[4], small[5], 300, out=out_small)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == mem0
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == allocs0
     ref_big = fc.attn_window(big[3], big[4], big[5], 2048)
     ref_small = fc.attn_window(small[3], small[4], small[5], 300)
     torch.cuda.synchronize()
