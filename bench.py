@@ -141,7 +141,7 @@ def extras(torch, fc, synthgen, packed, log_fn):
 
 
 def window_sweep(args):
-    """Step time against window size and prompt length (the measurement of the paper's Fig. 2, Sec. 3.2:
+    """Step time against window size and prompt length (the measurement of the paper's Fig. 2, Sec. 3.1:
     how large may the window grow before the step stops being free), batch 1, 7B and 13B shapes."""
     import torch
     import synthgen
@@ -303,9 +303,6 @@ def main():
     log(f"event pair around an empty kernel: {empty_ms * 1e3:.2f} us (the floor of these event intervals; a profiler's begin-to-end "
         "durations of the long kernels are 2-3 us shorter than the figures above)")
     cands = [t for t in table if t[3]]
-    if not cands:      # persistent kernel: the whole step is one launch
-        ms, cnt = prof["persistent_step"]
-        cands = [("persistent_step", ms, cnt, int(alg))]
     dom = max(cands, key=lambda t: t[1] * t[2])
     achieved = dom[3] / (dom[1] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom[0], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -331,7 +328,7 @@ def main():
     # to more than the graph-replayed step takes; the excess, spread over the launches, is the pairs' share.
     # `achieved` and `frac` stay on the raw intervals; the net figures are what a profiler's durations show.
     launches = sum(t[2] for t in table)
-    if launches and "persistent_step" not in prof:
+    if launches:
         over_ms = (sum(t[1] * t[2] for t in table) - ms_per_step) / launches
         net_ms = dom[1] - over_ms
         if over_ms > 0 and net_ms > 0:

@@ -77,6 +77,17 @@ size_t fastcot_workspace_bytes(const fastcot_config* cfg);
 int fastcot_pack_tensor(const fastcot_config* cfg, int32_t tensor, int32_t layer, const void* d_canonical,
                         void* d_packed, void* hip_stream);
 
+/* The whole model in one call: d_canonical is one device buffer of fastcot_canonical_bytes() bytes holding every
+ * tensor in the canonical layout above, tensor (t, layer) at byte offset fastcot_canonical_offset(cfg, t, layer)
+ * (tensors follow each other in the order EMB, WLM, GF, then per layer WQ, WK, WV, WO, WG, WU, WD, G1, G2, each
+ * start rounded up to 256 bytes; gains are fp32 and must be present: write ones for "no gain").  Equivalent to
+ * fastcot_pack_tensor for every tensor; models too large to hold twice on the device are packed tensor by tensor
+ * through a staging buffer instead.  (The library holds no weight generator: synthetic weights are inputs like
+ * any others and come from the caller.)  fastcot_canonical_offset returns (size_t)-1 on bad arguments. */
+size_t fastcot_canonical_bytes(const fastcot_config* cfg);
+size_t fastcot_canonical_offset(const fastcot_config* cfg, int32_t tensor, int32_t layer);
+int fastcot_pack_weights(const fastcot_config* cfg, const void* d_canonical, void* d_packed, void* hip_stream);
+
 /* Creates a context over packed weights and a zero-initialised-or-not workspace (the library
  * initialises what it needs, synchronously).  Both device buffers must stay alive and untouched
  * by the caller until fastcot_free. */
@@ -117,8 +128,6 @@ int fastcot_generate(fastcot_ctx* ctx, int32_t max_new_tokens, int32_t max_steps
 int fastcot_get_state(fastcot_ctx* ctx, int32_t* n, int32_t* generated, int32_t* done, int32_t* window,
                       int32_t* last_o, int32_t* last_K);
 
-/* Debug: if d_logits (device, fp32 [max_batch*W][vocab]) is non-NULL every following step also
- * stores the full logits there (row b*W + j); NULL switches it off. */
 /* Changes the window size between two fastcot_jacobi_step calls (not during fastcot_generate): the next
  * step runs `window` rows per sequence, slot 0 the newest exact token, the rest from the buffer.  1 <= window
  * <= the rows a pass may have (the configured window, or 256 where the matrix-core path covers the model);
@@ -126,7 +135,7 @@ int fastcot_get_state(fastcot_ctx* ctx, int32_t* n, int32_t* generated, int32_t*
  * (Sec. 4.1); the step count does.  This is the hook an adaptive-window controller needs (Limitations). */
 int fastcot_set_window(fastcot_ctx* ctx, int32_t window);
 
-/* Per-sequence window sizes (ragged batches, Sec. 5.3; the window enters Eq. 4 and Eq. 5 per sequence):
+/* Per-sequence window sizes (ragged batches, Sec. 5.4 Time Composition; the window enters Eq. 4 and Eq. 5 per sequence):
  * windows: host, one entry per sequence of the last fastcot_prefill, 1 <= windows[b] <= the current batch
  * window W.  From the next step on sequence b verifies (Eq. 5), accepts and writes back to its buffer only the
  * first windows[b] rows of its W; its accepted stream, step count and approximate tokens are those of a run with
@@ -136,14 +145,13 @@ int fastcot_set_window(fastcot_ctx* ctx, int32_t window);
  * sequence b.  FASTCOT_ESTATE otherwise. */
 int fastcot_set_windows(fastcot_ctx* ctx, const int32_t* windows);
 
-/* Ragged batches (Sec. 5.3, Table 2: a padded batch otherwise runs until its longest member ends): between
+/* Ragged batches (Sec. 5.4 Time Composition, Table 2: a padded batch otherwise runs until its longest member ends): between
  * two fastcot_jacobi_step calls (not with fastcot_generate) a new sequence takes over slot `slot`, 0 <= slot <
  * the batch of the last fastcot_prefill.  prompt: host, len >= 1 token ids; buffer_init: host, buf_len ids
  * (the buf_len of that prefill).  The slot's former sequence is dropped; every other sequence keeps its state
  * and, Eq. 2 coupling no two sequences, its stream.  The newcomer's prompt is run through the model as a batch
  * of one (the sequence in slot 0 trades places with it meanwhile: two cache-to-cache copies of one sequence's
- * K/V).  Synchronises the stream.  FASTCOT_ESTATE before a prefill, after fastcot_generate or with the
- * persistent step kernel; FASTCOT_EINVAL / FASTCOT_ECAPACITY as for fastcot_prefill. */
+ * K/V).  Synchronises the stream.  FASTCOT_ESTATE before a prefill or after fastcot_generate; FASTCOT_EINVAL / FASTCOT_ECAPACITY as for fastcot_prefill. */
 int fastcot_join(fastcot_ctx* ctx, int32_t slot, const int32_t* prompt, int32_t len, const int32_t* buffer_init);
 
 /* Answer phase (Sec. 4.4 "Trigger Answer"), after fastcot_generate has returned: every sequence continues
@@ -155,51 +163,48 @@ int fastcot_join(fastcot_ctx* ctx, int32_t slot, const int32_t* prompt, int32_t 
 int fastcot_answer(fastcot_ctx* ctx, const int32_t* trigger_ids, int32_t n_trigger, int32_t max_new_tokens,
                    int32_t eos_id, int32_t* out_ids, int32_t* out_len);
 
+/* Debug: if d_logits (device, fp32 [max_batch*W][vocab]) is non-NULL every following step also
+ * stores the full logits there (row b*W + j); NULL switches it off. */
 int fastcot_debug_logits(fastcot_ctx* ctx, float* d_logits);
 
-/* Options.  FASTCOT_OPT_PLAIN_KERNELS = 1 routes every step through the plain one-thread-per-
- * output kernels (always used for fp32 models); 0 (default) uses the MFMA kernels for bf16.
- * FASTCOT_OPT_GRAPH = 1 (default) replays a captured HIP graph per step; 0 launches kernels
- * one by one.  A context on the default (NULL) stream always launches one by one, since that
- * stream cannot be captured.
- * FASTCOT_OPT_KV_PLANES (bf16 models): 2 (default) keeps every cached K/V value as a bf16 hi +
- * bf16 lo pair (4 bytes, ~16 mantissa bits); 1 keeps the hi plane only (2 bytes, plain bf16).
- * Changing it invalidates the sequences: call fastcot_prefill again.
- * FASTCOT_OPT_PERSISTENT = 1 runs a step of a bf16 model with at most 16 rows as one persistent
- * kernel (one workgroup per compute unit, grid barriers between stages, weight tiles prefetched
- * across stages); 0 (default) launches one kernel per stage.  The persistent kernel is correct but
- * currently slower than the per-stage kernels. */
-enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLANES = 3, FASTCOT_OPT_PERSISTENT = 4,
-       /* launch-shape tuning of the MFMA path (defaults are chosen from the model shape): K slices
-        * per column group of the QKV / O / gate-up / down / LM-head GEMMs, key-range splits of
-        * the attention kernel */
-       FASTCOT_OPT_SK_QKV = 16, FASTCOT_OPT_SK_O = 17, FASTCOT_OPT_SK_GU = 18, FASTCOT_OPT_SK_DOWN = 19,
-       FASTCOT_OPT_SK_LM = 20, FASTCOT_OPT_ATTN_SPLITS = 21,
-       /* workgroups of the column-owner GEMM for QKV / O / gate-up / down / LM head (each owns
-        * at most 8 tiles of 16 columns); 0 selects the split-K kernel for that GEMM */
-       FASTCOT_OPT_NW_QKV = 22, FASTCOT_OPT_NW_O = 23, FASTCOT_OPT_NW_GU = 24, FASTCOT_OPT_NW_DOWN = 25,
-       FASTCOT_OPT_NW_LM = 26,
-       FASTCOT_OPT_ATTN_BLOCKS = 28, /* key blocks of 32 positions per attention workgroup: of the launched
-                                      * splits, ceil(blocks / value) work on a sequence, the rest exit */
-       /* K slices per column owner of the column-owner GEMM for the O / down projections (1..8; the
-        * workgroup count must be a multiple of it) */
-       FASTCOT_OPT_KS_O = 32, FASTCOT_OPT_KS_DOWN = 33, FASTCOT_OPT_KS_QKV = 36, FASTCOT_OPT_KS_GU = 37,
-       FASTCOT_OPT_CO_SINGLE = 27,   /* weight batches in flight per wave of the column-owner GEMM: 1 = one, 0 = two,
-                                      * 2 (default) = chosen per GEMM */
-       /* 1 (default): at the first fastcot_prefill of a step shape with at most 32 rows, the column-owner GEMMs that
-        * walk K in plain order (QKV, O) are timed on the model's own matrices with one / two weight batches in flight
-        * or the whole K slice requested up front, and the fastest is kept.  The choice moves loads, not additions:
-        * logits are the same bits whichever wins, in every process.  Everything that fixes the order of the fp32
-        * additions (K slices per owner, batch order) is chosen from the model shape alone.  Setting any of the NW,
-        * KS or CO_SINGLE options turns the measurement off: explicit choices win. */
-       FASTCOT_OPT_AUTOTUNE = 34,
-       /* 1 (default): whenever fastcot_generate finds finished sequences at one of its checks, they trade slots
-        * (state and K/V cache) with unfinished ones so that the following steps run only the unfinished
-        * sequences' rows; the order is restored before it returns.  0: finished sequences keep their rows. */
-       FASTCOT_OPT_COMPACT = 35,
-       /* debug: run only the first `value` stages of a forward (per layer: QKV, attention, O,
-        * gate/up, down); negative = all */
-       FASTCOT_OPT_DEBUG_STAGES = 30 };
+/* Options of a context.
+ * FASTCOT_OPT_PLAIN_KERNELS = 1 routes every step through the plain one-thread-per-output kernels (always used
+ * for fp32 models, and for bf16 models whose shape the matrix-core kernels do not cover: head_dim other than 128,
+ * or d_model / d_ffn / n_heads*head_dim not multiples of 256 -- fastcot_last_error() says so after fastcot_init);
+ * 0 (default) uses the matrix-core kernels for bf16.
+ * FASTCOT_OPT_GRAPH = 1 (default) replays a captured HIP graph per step; 0 launches kernels one by one.  A
+ * context on the default (NULL) stream always launches one by one, since that stream cannot be captured.
+ * FASTCOT_OPT_KV_PLANES (bf16 models): 2 (default) keeps every cached K/V value as a bf16 hi + bf16 lo pair
+ * (4 bytes, ~16 mantissa bits); 1 keeps the hi plane only (2 bytes, plain bf16).  Changing it invalidates the
+ * sequences: call fastcot_prefill again.
+ * FASTCOT_OPT_COMPACT = 1 (default): whenever fastcot_generate finds finished sequences at one of its checks,
+ * they trade slots (state and K/V cache) with unfinished ones so that the following steps run only the
+ * unfinished sequences' rows; the order is restored before it returns.  0: finished sequences keep their rows.
+ * FASTCOT_OPT_AUTOTUNE = 1 (default): at the first fastcot_prefill of a step shape with at most 32 rows, the
+ * column-owner GEMMs that walk K in plain order (QKV, O) are timed on the model's own matrices with one / two
+ * weight batches in flight or the whole K slice requested up front, and the fastest is kept.  The choice moves
+ * loads, not additions: logits are the same bits whichever wins, in every process.  Everything that fixes the
+ * order of the fp32 additions (K slices per owner, batch order) is chosen from the model shape alone.  Setting
+ * any FASTCOT_PLAN_* value turns the measurement off: explicit choices win.
+ * FASTCOT_OPT_DEBUG_STAGES: run only the first `value` stages of a forward (per layer: QKV, attention, O,
+ * gate/up, down); negative (default) = all. */
+enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLANES = 3, FASTCOT_OPT_COMPACT = 4,
+       FASTCOT_OPT_AUTOTUNE = 5, FASTCOT_OPT_DEBUG_STAGES = 6 };
+
+/* Launch-plan values, also set through fastcot_set_option.  They are measurement aids: defaults are chosen from
+ * the model shape, and which values exist may change with the kernels.  The five GEMMs are numbered QKV, O,
+ * gate/up, down, LM head.
+ * FASTCOT_PLAN_NW + g: workgroups of GEMM g (each owns at most 8 tiles of 16 columns over all of K).
+ * FASTCOT_PLAN_KS + g (g < 4): workgroups per column owner, each taking 1/value of K (1..8); their partial tiles
+ * meet through memory and the last to arrive adds them in slice order.  The workgroup count must be a multiple.
+ * FASTCOT_PLAN_SB + g: weight batches in flight per wave: 0 two, 1 one, 2 the wave's whole K slice up front.
+ * FASTCOT_PLAN_ROT + g: 1 = every wave walks its K batches in an order rotated by workgroup and wave.
+ * FASTCOT_PLAN_CO_SINGLE: 0 / 1 = two / one batch in flight for every GEMM, 2 (default) = per GEMM (PLAN_SB).
+ * FASTCOT_PLAN_ATTN_SPLITS: key-range splits the attention launch provides (1..16).
+ * FASTCOT_PLAN_ATTN_BLOCKS: key blocks of 32 positions per attention workgroup: of the launched splits,
+ * ceil(blocks / value) work on a sequence, the rest exit. */
+enum { FASTCOT_PLAN_NW = 100, FASTCOT_PLAN_KS = 105, FASTCOT_PLAN_SB = 110, FASTCOT_PLAN_ROT = 115,
+       FASTCOT_PLAN_CO_SINGLE = 120, FASTCOT_PLAN_ATTN_SPLITS = 121, FASTCOT_PLAN_ATTN_BLOCKS = 122 };
 int fastcot_set_option(fastcot_ctx* ctx, int32_t option, int32_t value);
 
 /* Debug: copies `count` floats of an activation buffer of the last forward to the host after
@@ -262,13 +267,15 @@ int fastcot_stream_read_chain(const void* d_src, size_t src_bytes, const uint64_
 
 /* LM head fused with argmax (Eq. 1/2, lowest id on ties): act device fp32 [M][d] (already
  * normalised), packed W_lm as written by fastcot_lmhead_pack from canonical bf16 [d][V];
- * ids device int32 [M], top device fp32 [M] (the winning logit); d_logits nullable fp32 [M][V].
+ * ids device int32 [M], top device fp32 [M] (the winning logit); d_top2 nullable fp32 [M], the largest logit
+ * among all other ids (top - top2 is the margin of the decision; asking for it makes the call write the
+ * logits, to d_logits or to the scratch); d_logits nullable fp32 [M][V].
  * scratch: device, fastcot_lmhead_scratch_bytes() bytes, zeroed once by the caller. */
 size_t fastcot_lmhead_packed_bytes(int32_t d, int32_t V);
 size_t fastcot_lmhead_scratch_bytes(int32_t M, int32_t d, int32_t V);
 int fastcot_lmhead_pack(const void* d_canonical_bf16, int32_t d, int32_t V, void* d_packed, void* hip_stream);
 int fastcot_lmhead_argmax(const float* d_act, const void* d_packed, int32_t M, int32_t d, int32_t V,
-                          int32_t* d_ids, float* d_top, float* d_logits, void* d_scratch, void* hip_stream);
+                          int32_t* d_ids, float* d_top, float* d_top2, float* d_logits, void* d_scratch, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -19,7 +19,8 @@ vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_siz
 N_KINDS = 16
 
 T = {"emb": 0, "wlm": 1, "gf": 2, "wq": 3, "wk": 4, "wv": 5, "wo": 6, "wg": 7, "wu": 8, "wd": 9, "g1": 10, "g2": 11}
-OPT_PLAIN_KERNELS, OPT_GRAPH = 1, 2
+OPT_PLAIN_KERNELS, OPT_GRAPH, OPT_KV_PLANES, OPT_COMPACT, OPT_AUTOTUNE, OPT_DEBUG_STAGES = 1, 2, 3, 4, 5, 6
+PLAN_NW, PLAN_KS, PLAN_SB, PLAN_ROT, PLAN_CO_SINGLE, PLAN_ATTN_SPLITS, PLAN_ATTN_BLOCKS = 100, 105, 110, 115, 120, 121, 122
 _STATUS = {0: "OK", -1: "EINVAL", -2: "ESTATE", -3: "ECAPACITY", -4: "EHIP", -5: "ENOMEM"}
 
 
@@ -74,7 +75,10 @@ SYMBOLS = {
     "fastcot_lmhead_packed_bytes": (sz, [i32, i32]),
     "fastcot_lmhead_scratch_bytes": (sz, [i32, i32, i32]),
     "fastcot_lmhead_pack": (ctypes.c_int, [vp, i32, i32, vp, vp]),
-    "fastcot_lmhead_argmax": (ctypes.c_int, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]),
+    "fastcot_lmhead_argmax": (ctypes.c_int, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]),
+    "fastcot_canonical_bytes": (sz, [ctypes.POINTER(Config)]),
+    "fastcot_canonical_offset": (sz, [ctypes.POINTER(Config), i32, i32]),
+    "fastcot_pack_weights": (ctypes.c_int, [ctypes.POINTER(Config), vp, vp, vp]),
 }
 
 
@@ -370,8 +374,39 @@ def lmhead_pack(w_bf16):
     return packed
 
 
-def lmhead_argmax(act, packed, V: int, want_logits: bool = False, scratch=None):
-    """act: device fp32 [M,d]; returns (ids int32 [M], top fp32 [M], logits or None)."""
+def pack_weights_whole(cfg: Config, tensors, gains=None):
+    """pack_weights through the one-call entry point: every tensor is first laid out in one canonical device
+    buffer (so the model is on the device twice meanwhile), then fastcot_pack_weights rearranges them all."""
+    torch = _torch()
+    L = lib()
+    nbytes, cbytes = L.fastcot_weight_bytes(ctypes.byref(cfg)), L.fastcot_canonical_bytes(ctypes.byref(cfg))
+    if nbytes == 0 or cbytes == 0:
+        raise FastcotError(-1, "invalid configuration")
+    canon = torch.zeros(cbytes, dtype=torch.uint8, device="cuda")
+    packed = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+
+    def put(name, layer, arr):
+        off = L.fastcot_canonical_offset(ctypes.byref(cfg), T[name], max(layer, 0))
+        raw = torch.from_numpy(np.ascontiguousarray(arr).view(np.uint8).reshape(-1))
+        canon[off:off + raw.numel()] = raw.to("cuda")
+    for name, layer, arr in tensors:
+        put(name, layer, arr)
+    gains = gains or {}
+    ones = np.ones(cfg.d_model, dtype=np.float32)
+    for name in ("gf", "g1", "g2"):
+        for l in ([-1] if name == "gf" else range(cfg.n_layers)):
+            g = gains.get(name)
+            if g is not None and name != "gf":
+                g = g[l]
+            put(name, l, np.asarray(ones if g is None else g, dtype=np.float32))
+    _check(L.fastcot_pack_weights(ctypes.byref(cfg), canon.data_ptr(), packed.data_ptr(), _stream_ptr()))
+    torch.cuda.current_stream().synchronize()
+    return packed
+
+
+def lmhead_argmax(act, packed, V: int, want_logits: bool = False, scratch=None, want_top2: bool = False):
+    """act: device fp32 [M,d]; returns (ids int32 [M], top fp32 [M], logits or None) and, with want_top2, the
+    runner-up logit of every row as a fourth entry."""
     torch = _torch()
     M, d = act.shape
     if scratch is None:
@@ -379,6 +414,8 @@ def lmhead_argmax(act, packed, V: int, want_logits: bool = False, scratch=None):
     ids = torch.empty(M, dtype=torch.int32, device="cuda")
     top = torch.empty(M, dtype=torch.float32, device="cuda")
     logits = torch.empty(M, V, dtype=torch.float32, device="cuda") if want_logits else None
+    top2 = torch.empty(M, dtype=torch.float32, device="cuda") if want_top2 else None
     _check(lib().fastcot_lmhead_argmax(act.data_ptr(), packed.data_ptr(), M, d, V, ids.data_ptr(), top.data_ptr(),
+                                       top2.data_ptr() if want_top2 else None,
                                        logits.data_ptr() if want_logits else None, scratch.data_ptr(), _stream_ptr()))
-    return ids, top, logits
+    return (ids, top, logits, top2) if want_top2 else (ids, top, logits)

@@ -8,7 +8,6 @@
 #include <vector>
 #include "kernels.h"
 #include "fast.h"
-#include "persist.h"
 
 static thread_local char g_err[512] = "";
 
@@ -27,7 +26,7 @@ struct fastcot_ctx {
     int tuned_rows[2];   // rows per step the plan's per-GEMM choices were last measured for (up to 16 / 17..32 rows)
     int last_eos;        // eos_id of the last fastcot_generate (-1 = none)
     int buf_len;
-    int opt_plain, opt_graph, opt_persist, dbg_stop;
+    int opt_plain, opt_graph, dbg_stop;
     float* dbg_logits;
     hipGraphExec_t graph_exec;
     hipGraph_t graph;
@@ -60,7 +59,7 @@ void fc_set_error(const char* msg) { snprintf(g_err, 512, "%s", msg); }
 
 static const char* kKernelNames[FASTCOT_N_KERNEL_KINDS] = {
     "embed", "rmsnorm", "gemm_qkv", "rope_cache", "attention", "gemm_o", "gemm_gate_up", "swiglu",
-    "gemm_down", "lm_head", "argmax", "accept_commit", "attn_combine", "persistent_step", "empty_kernel", "reserved15"};
+    "gemm_down", "lm_head", "argmax", "accept_commit", "attn_combine", "reserved13", "empty_kernel", "reserved15"};
 enum { KK_EMBED = 0, KK_RMSNORM, KK_QKV, KK_ROPE, KK_ATTN, KK_O, KK_GU, KK_SWIGLU, KK_DOWN, KK_LM, KK_ARGMAX, KK_ACCEPT, KK_EMPTY = 14 };
 __global__ void k_empty() {}
 
@@ -70,18 +69,21 @@ extern "C" const char* fastcot_kernel_name(int32_t kind) {
 extern "C" const char* fastcot_last_error(const fastcot_ctx* ctx) { return ctx ? ctx->err : g_err; }
 
 // ------------------------------------------------------------------ layout maps
-static int valid_cfg(const fastcot_config* c) {
-    if (!c) return 0;
+// NULL if the configuration is usable, else what is wrong with it
+static const char* cfg_problem(const fastcot_config* c) {
+    if (!c) return "configuration is NULL";
     if (c->n_layers < 0 || c->d_model <= 0 || c->n_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 ||
-        c->d_ffn <= 0 || c->vocab <= 0 || c->max_batch <= 0 || c->max_seq <= 0 || c->window <= 0) return 0;
-    if (c->dtype != FASTCOT_F32 && c->dtype != FASTCOT_BF16) return 0;
-    if (c->n_heads % c->n_kv_heads) return 0;
-    if (c->head_dim % 32 || c->d_model % 16 || c->d_ffn % 16 || c->vocab % 16) return 0;
-    if (c->dtype == FASTCOT_BF16 && (c->d_model % 32 || c->d_ffn % 32 || (c->n_heads * c->head_dim) % 32)) return 0;
-    if (c->max_seq > 16000 || c->max_seq < 2 * c->window) return 0;
-    if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return 0;
-    return 1;
+        c->d_ffn <= 0 || c->vocab <= 0 || c->max_batch <= 0 || c->max_seq <= 0 || c->window <= 0) return "a dimension or capacity is not positive";
+    if (c->dtype != FASTCOT_F32 && c->dtype != FASTCOT_BF16) return "dtype is neither FASTCOT_F32 nor FASTCOT_BF16";
+    if (c->n_heads % c->n_kv_heads) return "n_heads is not a multiple of n_kv_heads";
+    if (c->head_dim % 32 || c->d_model % 16 || c->d_ffn % 16 || c->vocab % 16) return "head_dim must be a multiple of 32; d_model, d_ffn and vocab multiples of 16";
+    if (c->dtype == FASTCOT_BF16 && (c->d_model % 32 || c->d_ffn % 32 || (c->n_heads * c->head_dim) % 32)) return "bf16 models need d_model, d_ffn and n_heads*head_dim to be multiples of 32";
+    if (c->max_seq > 16000) return "max_seq above 16000 positions is not supported";
+    if (c->max_seq < 2 * c->window) return "max_seq must be at least 2*window";
+    if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return "rms_eps must be >= 0 and rope_base > 0";
+    return nullptr;
 }
+static int valid_cfg(const fastcot_config* c) { return cfg_problem(c) == nullptr; }
 
 int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, KernelDims* kd) {
     if (!valid_cfg(c)) return FASTCOT_EINVAL;
@@ -169,7 +171,7 @@ extern "C" size_t fastcot_workspace_bytes(const fastcot_config* cfg) {
 extern "C" int fastcot_pack_tensor(const fastcot_config* cfg, int32_t tensor, int32_t layer, const void* src,
                                    void* d_packed, void* hip_stream) {
     ModelMap mm; KernelDims kd;
-    if (fc_build_maps(cfg, &mm, nullptr, &kd) != 0) return fail(nullptr, FASTCOT_EINVAL, "invalid configuration%s");
+    if (fc_build_maps(cfg, &mm, nullptr, &kd) != 0) return fail(nullptr, FASTCOT_EINVAL, "invalid configuration: %s", cfg_problem(cfg));
     if (!d_packed) return fail(nullptr, FASTCOT_EINVAL, "d_packed is NULL%s");
     hipStream_t st = (hipStream_t)hip_stream;
     const int dt = cfg->dtype, d = kd.d, qd = kd.H * kd.Dh, kvd = kd.Hkv * kd.Dh;
@@ -202,6 +204,57 @@ extern "C" int fastcot_pack_tensor(const fastcot_config* cfg, int32_t tensor, in
     return 0;
 }
 
+// canonical layout of a whole model: element count and element size of a tensor
+static size_t canon_elems(const KernelDims& kd, int t) {
+    const size_t d = kd.d, qd = (size_t)kd.H * kd.Dh, kvd = (size_t)kd.Hkv * kd.Dh, F = kd.F, V = kd.V;
+    switch (t) {
+        case FASTCOT_T_EMB: case FASTCOT_T_WLM: return V * d;
+        case FASTCOT_T_GF: case FASTCOT_T_G1: case FASTCOT_T_G2: return d;
+        case FASTCOT_T_WQ: case FASTCOT_T_WO: return d * qd;
+        case FASTCOT_T_WK: case FASTCOT_T_WV: return d * kvd;
+        case FASTCOT_T_WG: case FASTCOT_T_WU: case FASTCOT_T_WD: return d * F;
+    }
+    return 0;
+}
+static size_t canon_bytes(const KernelDims& kd, int t) {
+    const bool gain = t == FASTCOT_T_GF || t == FASTCOT_T_G1 || t == FASTCOT_T_G2;
+    return FC_ALIGN(canon_elems(kd, t) * (gain ? 4 : (size_t)kd.esz));
+}
+extern "C" size_t fastcot_canonical_offset(const fastcot_config* cfg, int32_t tensor, int32_t layer) {
+    KernelDims kd;
+    if (fc_build_maps(cfg, nullptr, nullptr, &kd) != 0 || tensor < FASTCOT_T_EMB || tensor > FASTCOT_T_G2) return (size_t)-1;
+    size_t global = 0, per_layer = 0, off_in_layer = 0;
+    for (int t = FASTCOT_T_EMB; t <= FASTCOT_T_GF; ++t) { if (t == tensor) return global; global += canon_bytes(kd, t); }
+    if (layer < 0 || layer >= kd.L) return (size_t)-1;
+    for (int t = FASTCOT_T_WQ; t <= FASTCOT_T_G2; ++t) { if (t == tensor) off_in_layer = per_layer; per_layer += canon_bytes(kd, t); }
+    return global + (size_t)layer * per_layer + off_in_layer;
+}
+extern "C" size_t fastcot_canonical_bytes(const fastcot_config* cfg) {
+    KernelDims kd;
+    if (fc_build_maps(cfg, nullptr, nullptr, &kd) != 0) return 0;
+    size_t total = 0;
+    for (int t = FASTCOT_T_EMB; t <= FASTCOT_T_GF; ++t) total += canon_bytes(kd, t);
+    size_t per_layer = 0;
+    for (int t = FASTCOT_T_WQ; t <= FASTCOT_T_G2; ++t) per_layer += canon_bytes(kd, t);
+    return total + (size_t)kd.L * per_layer;
+}
+extern "C" int fastcot_pack_weights(const fastcot_config* cfg, const void* d_canonical, void* d_packed, void* hip_stream) {
+    KernelDims kd;
+    if (fc_build_maps(cfg, nullptr, nullptr, &kd) != 0) return fail(nullptr, FASTCOT_EINVAL, "invalid configuration: %s", cfg_problem(cfg));
+    if (!d_canonical || !d_packed) return fail(nullptr, FASTCOT_EINVAL, "NULL device buffer%s");
+    const char* src = (const char*)d_canonical;
+    for (int t = FASTCOT_T_EMB; t <= FASTCOT_T_GF; ++t) {
+        const int rc = fastcot_pack_tensor(cfg, t, 0, src + fastcot_canonical_offset(cfg, t, 0), d_packed, hip_stream);
+        if (rc) return rc;
+    }
+    for (int l = 0; l < kd.L; ++l)
+        for (int t = FASTCOT_T_WQ; t <= FASTCOT_T_G2; ++t) {
+            const int rc = fastcot_pack_tensor(cfg, t, l, src + fastcot_canonical_offset(cfg, t, l), d_packed, hip_stream);
+            if (rc) return rc;
+        }
+    return 0;
+}
+
 // ------------------------------------------------------------------ context
 static int32_t* state_ptr(fastcot_ctx* c) { return (int32_t*)(c->ws + c->wm.state); }
 
@@ -212,11 +265,11 @@ extern "C" int fastcot_init(const fastcot_config* cfg, const void* d_packed, voi
     if (!d_packed || !d_workspace) return fail(nullptr, FASTCOT_EINVAL, "NULL device buffer%s");
     fastcot_ctx* c = new (std::nothrow) fastcot_ctx();
     if (!c) return fail(nullptr, FASTCOT_ENOMEM, "out of host memory%s");
-    if (fc_build_maps(cfg, &c->mm, &c->wm, &c->kd) != 0) { delete c; return fail(nullptr, FASTCOT_EINVAL, "invalid configuration%s"); }
+    if (fc_build_maps(cfg, &c->mm, &c->wm, &c->kd) != 0) { delete c; return fail(nullptr, FASTCOT_EINVAL, "invalid configuration: %s", cfg_problem(cfg)); }
     if (workspace_bytes < c->wm.total) { delete c; return fail(nullptr, FASTCOT_ECAPACITY, "workspace too small%s"); }
     c->cfg = *cfg; c->weights = (const char*)d_packed; c->ws = (char*)d_workspace; c->st = (hipStream_t)hip_stream;
     c->Bact = 0; c->prefilled = 0; c->generated = 0; c->buf_len = 0; c->opt_tune = 1; c->opt_compact = 1;
-    c->opt_plain = (cfg->dtype == FASTCOT_F32); c->opt_graph = 1; c->opt_persist = 0; c->dbg_stop = -1; c->dbg_logits = nullptr;
+    c->opt_plain = (cfg->dtype == FASTCOT_F32); c->opt_graph = 1; c->dbg_stop = -1; c->dbg_logits = nullptr;
     c->graph_exec = nullptr; c->graph = nullptr; c->graph_valid = 0; c->prof_on = 0; c->prof_used = 0;
     c->pinned = nullptr; c->err[0] = 0;
     fc_fast_plan(c->kd, &c->plan);
@@ -238,6 +291,12 @@ extern "C" int fastcot_init(const fastcot_config* cfg, const void* d_packed, voi
     INITCHK(hipMemsetAsync(c->ws + c->wm.kc, 0, c->wm.rope_cos - c->wm.kc, c->st));   // whole KV cache
     INITCHK(hipStreamSynchronize(c->st));
 #undef INITCHK
+    // a bf16 model the matrix-core kernels do not cover runs through the plain kernels: say so (not an error)
+    if (cfg->dtype == FASTCOT_BF16 && !fc_fast_supported(c->kd, c->kd.B * c->kd.W)) {
+        c->opt_plain = 1;
+        snprintf(c->err, sizeof(c->err), "note: this bf16 model runs on the plain one-thread-per-output kernels: the matrix-core kernels need "
+                 "head_dim 128 and d_model, d_ffn, n_heads*head_dim multiples of 256");
+    }
     *out = c;
     return 0;
 }
@@ -260,53 +319,43 @@ extern "C" void fastcot_free(fastcot_ctx* c) {
 
 extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value) {
     if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
+    const int nts[5] = {c->kd.qkvN / 16, c->kd.d / 16, 2 * c->kd.F / 16, c->kd.d / 16, c->kd.V / 16};
+    const int Ks[5] = {c->kd.d, c->kd.H * c->kd.Dh, c->kd.d, c->kd.F, c->kd.d};
     if (option == FASTCOT_OPT_PLAIN_KERNELS) {
         if (!value && c->cfg.dtype == FASTCOT_F32) return fail(c, FASTCOT_EINVAL, "fp32 models only have the plain kernels%s");
         c->opt_plain = value != 0;
     } else if (option == FASTCOT_OPT_GRAPH) c->opt_graph = value != 0;
-    else if (option == FASTCOT_OPT_PERSISTENT) c->opt_persist = value != 0;
     else if (option == FASTCOT_OPT_DEBUG_STAGES) c->dbg_stop = value;
     else if (option == FASTCOT_OPT_KV_PLANES) {
         if (c->cfg.dtype != FASTCOT_BF16 || (value != 1 && value != 2)) return fail(c, FASTCOT_EINVAL, "KV planes: 1 or 2, bf16 models only%s");
         c->kd.kvp = value; c->prefilled = 0;      // the cache layout changes: a new prefill is required
-    }
-    else if (option >= FASTCOT_OPT_SK_QKV && option <= FASTCOT_OPT_SK_LM) {
-        GemmPlan* gp[5] = {&c->plan.qkv, &c->plan.o, &c->plan.gu, &c->plan.down, &c->plan.lm};
-        const int Ks[5] = {c->kd.d, c->kd.H * c->kd.Dh, c->kd.d, c->kd.F, c->kd.d};
-        const int NU = Ks[option - FASTCOT_OPT_SK_QKV] / 256;
-        if (value < 1 || value > FC_MAX_SK || value > NU || (NU + value - 1) / value > 4)
-            return fail(c, FASTCOT_EINVAL, "split-K out of range: slices must hold 1..4 units of 256 inputs%s");
-        gp[option - FASTCOT_OPT_SK_QKV]->sk = value;
-    } else if (option >= FASTCOT_OPT_NW_QKV && option <= FASTCOT_OPT_NW_LM) {
-        const int nts[5] = {c->kd.qkvN / 16, c->kd.d / 16, 2 * c->kd.F / 16, c->kd.d / 16, c->kd.V / 16};
-        const int NT = nts[option - FASTCOT_OPT_NW_QKV];
-        if (value < 0 || value > NT || (value > 0 && (NT + value - 1) / value > 8))
-            return fail(c, FASTCOT_EINVAL, "workgroups of the column-owner GEMM: 0 (split-K kernel) or NT/8 .. NT%s");
-        const int gi = option - FASTCOT_OPT_NW_QKV, ks = c->plan.ks[gi] > 1 ? c->plan.ks[gi] : 1;
-        if (value > 0 && (value % ks || value / ks > NT || (NT + value / ks - 1) / (value / ks) > 8))
+    } else if (option == FASTCOT_OPT_COMPACT) c->opt_compact = value != 0;
+    else if (option == FASTCOT_OPT_AUTOTUNE) { c->opt_tune = value != 0; c->tuned_rows[0] = c->tuned_rows[1] = 0; }
+    else if (option >= FASTCOT_PLAN_NW && option < FASTCOT_PLAN_NW + 5) {
+        const int gi = option - FASTCOT_PLAN_NW, NT = nts[gi], ks = c->plan.ks[gi] > 1 ? c->plan.ks[gi] : 1;
+        if (value < 1 || value > NT || (NT + value - 1) / value > 8)
+            return fail(c, FASTCOT_EINVAL, "workgroups of the column-owner GEMM: NT/8 .. NT%s");
+        if (value % ks || value / ks > NT || (NT + value / ks - 1) / (value / ks) > 12)
             return fail(c, FASTCOT_EINVAL, "workgroups of the column-owner GEMM do not fit its K slices per owner%s");
         c->plan.nw[gi] = value; c->opt_tune = 0;
-    } else if (option == FASTCOT_OPT_KS_O || option == FASTCOT_OPT_KS_DOWN || option == FASTCOT_OPT_KS_QKV || option == FASTCOT_OPT_KS_GU) {
-        const int gi = option == FASTCOT_OPT_KS_QKV ? 0 : (option == FASTCOT_OPT_KS_O ? 1 : (option == FASTCOT_OPT_KS_GU ? 2 : 3));
-        const int nts[4] = {c->kd.qkvN / 16, c->kd.d / 16, 2 * c->kd.F / 16, c->kd.d / 16};
-        const int Ks[4] = {c->kd.d, c->kd.H * c->kd.Dh, c->kd.d, c->kd.F};
-        const int NT = nts[gi], nw = c->plan.nw[gi], K = Ks[gi];
+    } else if (option >= FASTCOT_PLAN_KS && option < FASTCOT_PLAN_KS + 4) {
+        const int gi = option - FASTCOT_PLAN_KS, NT = nts[gi], nw = c->plan.nw[gi], K = Ks[gi];
         if (value < 1 || value > 8 || K / 256 < value) return fail(c, FASTCOT_EINVAL, "K slices per owner out of range%s");
-        if (nw > 0 && (nw % value || nw / value > NT || nw / value < 1 || (NT + nw / value - 1) / (nw / value) > 12))
+        if (nw % value || nw / value > NT || nw / value < 1 || (NT + nw / value - 1) / (nw / value) > 12)
             return fail(c, FASTCOT_EINVAL, "K slices per owner do not fit the workgroup count of that GEMM%s");
         c->plan.ks[gi] = value; c->opt_tune = 0;
-    } else if (option == FASTCOT_OPT_CO_SINGLE) {
+    } else if (option >= FASTCOT_PLAN_SB && option < FASTCOT_PLAN_SB + 5) {
+        if (value < 0 || value > 2) return fail(c, FASTCOT_EINVAL, "weight batches in flight: 0 (two), 1 (one) or 2 (whole slice up front)%s");
+        c->plan.co_sb[0][option - FASTCOT_PLAN_SB] = c->plan.co_sb[1][option - FASTCOT_PLAN_SB] = value; c->opt_tune = 0;
+    } else if (option >= FASTCOT_PLAN_ROT && option < FASTCOT_PLAN_ROT + 5) {
+        c->plan.co_rot[0][option - FASTCOT_PLAN_ROT] = c->plan.co_rot[1][option - FASTCOT_PLAN_ROT] = value != 0; c->opt_tune = 0;
+    } else if (option == FASTCOT_PLAN_CO_SINGLE) {
         if (value < 0 || value > 2) return fail(c, FASTCOT_EINVAL, "buffering of the column-owner GEMM: 0, 1 or 2%s");
         c->plan.co_single = value; c->opt_tune = 0;
-    } else if (option == FASTCOT_OPT_COMPACT) {
-        c->opt_compact = value != 0;
-    } else if (option == FASTCOT_OPT_AUTOTUNE) {
-        c->opt_tune = value != 0; c->tuned_rows[0] = c->tuned_rows[1] = 0;
-    }
-    else if (option == FASTCOT_OPT_ATTN_SPLITS) {
+    } else if (option == FASTCOT_PLAN_ATTN_SPLITS) {
         if (value < 1 || value > FC_MAX_ATTN_SPLITS) return fail(c, FASTCOT_EINVAL, "attention splits out of range%s");
         c->plan.attn_splits = value;
-    } else if (option == FASTCOT_OPT_ATTN_BLOCKS) {
+    } else if (option == FASTCOT_PLAN_ATTN_BLOCKS) {
         if (value < 1 || value > 4096) return fail(c, FASTCOT_EINVAL, "attention blocks per workgroup out of range%s");
         c->plan.attn_bpw = value;
     }
@@ -371,14 +420,8 @@ static int forward_plain(fastcot_ctx* c, int lmhead, int R) {
     return 0;
 }
 
-static bool use_persist(const fastcot_ctx* c, int R = 0) {
-    KernelDims kd = c->kd;
-    if (R > 0) kd.W = R;
-    return !c->opt_plain && c->opt_persist && fc_persist_supported(kd, c->Bact * kd.W);
-}
-
 // one forward pass over R rows per sequence (R = 0: the window)
-static int forward(fastcot_ctx* c, int lmhead, int do_accept = 0, int R = 0) {
+static int forward(fastcot_ctx* c, int lmhead, int R = 0) {
     if (R <= 0) R = c->kd.W;
     if (R > c->kd.Wcap) return fail(c, FASTCOT_ECAPACITY, "pass of %s%ld rows per sequence exceeds the workspace (%ld)", "", (long)R, (long)c->kd.Wcap);
     if (c->opt_plain || !fc_fast_supported(c->kd, c->Bact * R)) return forward_plain(c, lmhead, R);
@@ -389,23 +432,12 @@ static int forward(fastcot_ctx* c, int lmhead, int do_accept = 0, int R = 0) {
     a.dbg_stop = c->dbg_stop;
     a.prof = c->prof_on ? c : nullptr;
     a.prof_mark = c->prof_on ? [](void* p, int kind) { return prof_mark((fastcot_ctx*)p, kind); } : nullptr;
-    hipError_t e = use_persist(c, R) ? fc_persist_step(a, do_accept, a.prof, a.prof_mark) : fc_fast_forward(a);
+    hipError_t e = fc_fast_forward(a);
     if (e != hipSuccess) return fail(c, FASTCOT_EHIP, "forward launch failed: %s", hipGetErrorString(e));
     return 0;
 }
 
-// the persistent kernel's grid barrier gave up (the grid was not co-resident): report it
-static int check_abort(fastcot_ctx* c) {
-    if (!use_persist(c)) return 0;
-    int32_t flag = 0;
-    hipError_t e = hipMemcpy(&flag, (int32_t*)(c->ws + c->wm.gemm_cnt) + FC_MAX_COUNTERS - 7, 4, hipMemcpyDeviceToHost);
-    if (e != hipSuccess) return fail(c, FASTCOT_EHIP, "HIP error '%s' reading the barrier state", hipGetErrorString(e));
-    if (flag) return fail(c, FASTCOT_EHIP, "grid barrier of the persistent step kernel timed out%s");
-    return 0;
-}
-
 static int step_body(fastcot_ctx* c) {
-    if (use_persist(c)) return forward(c, 1, 1);      // accept/commit is the kernel's last stage
     int rc = forward(c, 1);
     if (rc) return rc;
     LAUNCH(c, KK_ACCEPT, fc_accept_commit(state_ptr(c), c->wm.st, c->Bact, c->kd.W, c->kd.S, c->st));
@@ -445,7 +477,7 @@ static int prefill_passes(fastcot_ctx* c, int B, int maxlen) {
         if (R < 1) R = rows_cap < 16 ? rows_cap : 16;          // 1-token prompts: no forward, only the window set-up
         const bool last = p0 + R >= maxlen - 1;
         HIPCHK(c, fc_prefill_window(stp, sm, B, R, kd.S, p0, c->st));
-        if (left > 0) { int rc = forward(c, 0, 0, R); if (rc) return rc; }
+        if (left > 0) { int rc = forward(c, 0, R); if (rc) return rc; }
         HIPCHK(c, fc_prefill_advance(stp, sm, B, kd.W, kd.S, p0 + R, last, c->st));
         p0 += R;
     } while (p0 < maxlen - 1);
@@ -501,7 +533,7 @@ extern "C" int fastcot_prefill(fastcot_ctx* c, int32_t B, const int32_t* prompts
     // hold nothing yet that the passes below do not overwrite)
     {
         const int rows = B * kd.W, cls = rows > 16;
-        if (c->opt_tune && !c->opt_plain && !c->opt_persist && c->plan.co_single == 2 && rows <= 32 && c->tuned_rows[cls] != rows &&
+        if (c->opt_tune && !c->opt_plain && c->plan.co_single == 2 && rows <= 32 && c->tuned_rows[cls] != rows &&
             fc_fast_supported(kd, rows)) {
             FastArgs a;
             a.kd = kd; a.kd.M = rows; a.Bact = B; a.mm = &c->mm; a.wm = &c->wm; a.weights = c->weights; a.ws = c->ws;
@@ -513,7 +545,6 @@ extern "C" int fastcot_prefill(fastcot_ctx* c, int32_t B, const int32_t* prompts
     }
     { int rc = prefill_passes(c, B, maxlen); if (rc) return rc; }
     HIPCHK(c, hipStreamSynchronize(c->st));
-    { int rc = check_abort(c); if (rc) return rc; }
     c->prefilled = 1;
     return 0;
 }
@@ -536,7 +567,6 @@ extern "C" int fastcot_jacobi_step(fastcot_ctx* c, int32_t* n_accepted, int32_t*
         if (accepted) for (int j = 0; j < W; ++j) accepted[(size_t)b * W + j] = (j <= K[b]) ? o[(size_t)b * W + j] : -1;
     }
     if (window_next) HIPCHK(c, hipMemcpy(window_next, stp + sm.win, (size_t)B * W * 4, hipMemcpyDeviceToHost));
-    { int rc2 = check_abort(c); if (rc2) return rc2; }
     int32_t flags[2];
     HIPCHK(c, hipMemcpy(flags, stp + sm.flags, 8, hipMemcpyDeviceToHost));
     if (flags[FLAG_ERROR]) return fail(c, FASTCOT_ECAPACITY, "a sequence ran out of cache or buffer capacity%s");
@@ -567,7 +597,7 @@ extern "C" int fastcot_set_window(fastcot_ctx* c, int32_t window) {
     return 0;
 }
 
-// Per-sequence window sizes (ragged batches, Sec. 5.3): sequence b verifies, accepts and writes back only the
+// Per-sequence window sizes (ragged batches, Sec. 5.4 Time Composition): sequence b verifies, accepts and writes back only the
 // first windows[b] rows of its share of the step.  The step still computes the batch's window for every
 // sequence (rows sit at b * W + j), so this changes what a sequence does per step, not what the step costs.
 extern "C" int fastcot_set_windows(fastcot_ctx* c, const int32_t* windows) {
@@ -584,7 +614,7 @@ extern "C" int fastcot_set_windows(fastcot_ctx* c, const int32_t* windows) {
 }
 
 // ------------------------------------------------------------------ a sequence joins the running batch
-// Ragged batches (Sec. 5.3: a batch otherwise runs, padded, until its longest member ends): between two
+// Ragged batches (Sec. 5.4 Time Composition, Table 2: a batch otherwise runs, padded, until its longest member ends): between two
 // fastcot_jacobi_step calls a new prompt takes over slot `slot`; the other sequences keep their state, and
 // since no term of Eq. 2 couples sequences, their streams are what they would have been.  The kernels work
 // on the first slots of the batch, so the newcomer is prefilled in slot 0 as a batch of one: the sequence
@@ -593,7 +623,6 @@ extern "C" int fastcot_join(fastcot_ctx* c, int32_t slot, const int32_t* prompt,
     if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
     if (!c->prefilled) return fail(c, FASTCOT_ESTATE, "fastcot_join before fastcot_prefill%s");
     if (c->generated) return fail(c, FASTCOT_ESTATE, "fastcot_join after fastcot_generate%s");
-    if (use_persist(c)) return fail(c, FASTCOT_ESTATE, "fastcot_join is not available with the persistent step kernel%s");
     if (!prompt || !buffer_init) return fail(c, FASTCOT_EINVAL, "NULL prompt or buffer%s");
     const KernelDims& kd = c->kd; const StateMap& sm = c->wm.st; const int B = c->Bact;
     if (slot < 0 || slot >= B) return fail(c, FASTCOT_EINVAL, "slot %s%ld outside the batch of %ld", "", (long)slot, (long)B);
@@ -631,7 +660,7 @@ extern "C" int fastcot_join(fastcot_ctx* c, int32_t slot, const int32_t* prompt,
     bool any_done = false;
     for (int b = 0; b < B; ++b) any_done = any_done || c->pinned[b] != 0;
     if (!any_done) { int32_t zeros[2] = {0, 0}; HIPCHK(c, hipMemcpy(stp + sm.flags, zeros, 8, hipMemcpyHostToDevice)); }
-    return check_abort(c);
+    return 0;
 }
 
 // ------------------------------------------------------------------ generate
@@ -698,7 +727,6 @@ extern "C" int fastcot_generate(fastcot_ctx* c, int32_t max_new, int32_t max_ste
         HIPCHK(c, hipMemcpyAsync(c->pinned + B, stp + sm.done, (size_t)B * 4, hipMemcpyDeviceToHost, c->st));
         HIPCHK(c, hipMemcpyAsync(c->pinned + 2 * B, stp + sm.flags, 8, hipMemcpyDeviceToHost, c->st));
         HIPCHK(c, hipStreamSynchronize(c->st));
-        { int rc = check_abort(c); if (rc) return rc; }
         all_done = c->pinned[2 * B + FLAG_ALL_DONE] != 0;
         for (int b = 0; b < B; ++b) { hg[b] = c->pinned[b]; hdone[b] = c->pinned[B + b]; }
         if (c->pinned[2 * B + FLAG_ERROR]) {
@@ -706,7 +734,7 @@ extern "C" int fastcot_generate(fastcot_ctx* c, int32_t max_new, int32_t max_ste
             c->Bact = B; drop_graph(c);
             return fail(c, FASTCOT_ECAPACITY, "a sequence ran out of cache or buffer capacity%s");
         }
-        if (!all_done && c->opt_compact && !use_persist(c) && !(max_steps > 0 && total_steps >= max_steps)) {
+        if (!all_done && c->opt_compact && !(max_steps > 0 && total_steps >= max_steps)) {
             int lo = 0, hi = Bcur - 1, moved = 0;
             for (;;) {
                 while (lo < hi && !hdone[lo]) ++lo;          // first finished slot
@@ -804,7 +832,7 @@ extern "C" int fastcot_answer(fastcot_ctx* c, const int32_t* trigger_ids, int32_
         for (int b = 0; b < B; ++b)
             for (int j = 0; j < Rp && p0 + j + 1 < (int)ctxrows[b].size(); ++j) rows[(size_t)b * Rp + j] = ctxrows[b][p0 + j];
         HIPCHK(c, hipMemcpy(stp + sm.win, rows.data(), rows.size() * 4, hipMemcpyHostToDevice));
-        int rc = forward(c, 0, 0, Rp);
+        int rc = forward(c, 0, Rp);
         if (rc) return rc;
         HIPCHK(c, hipStreamSynchronize(c->st));
         for (int b = 0; b < B; ++b) {
@@ -835,7 +863,7 @@ extern "C" int fastcot_answer(fastcot_ctx* c, const int32_t* trigger_ids, int32_
         int need = 1;
         for (int b = 0; b < B; ++b) if (!d2[b] && max_new - g2[b] > need) need = max_new - g2[b];
         for (int s = 0; s < need; ++s) {
-            int rc = forward(c, 1, 0, 1);
+            int rc = forward(c, 1, 1);
             if (rc) return rc;
             HIPCHK(c, fc_accept_commit(stp, sm, B, 1, S, c->st));
         }
@@ -843,7 +871,6 @@ extern "C" int fastcot_answer(fastcot_ctx* c, const int32_t* trigger_ids, int32_
         HIPCHK(c, hipMemcpyAsync(c->pinned + B, stp + sm.done, (size_t)B * 4, hipMemcpyDeviceToHost, c->st));
         HIPCHK(c, hipMemcpyAsync(c->pinned + 2 * B, stp + sm.flags, 8, hipMemcpyDeviceToHost, c->st));
         HIPCHK(c, hipStreamSynchronize(c->st));
-        { int rc = check_abort(c); if (rc) return rc; }
         all_done = c->pinned[2 * B + FLAG_ALL_DONE] != 0;
         for (int b = 0; b < B; ++b) { g2[b] = c->pinned[b]; d2[b] = c->pinned[B + b]; }
         if (c->pinned[2 * B + FLAG_ERROR]) return fail(c, FASTCOT_ECAPACITY, "a sequence ran out of cache capacity%s");

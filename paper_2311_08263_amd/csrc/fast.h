@@ -3,15 +3,9 @@
 #include "common.h"
 
 #define FC_MAX_COUNTERS 8192
-#define FC_MAX_SK 64          // largest cross-workgroup split of K
 #define FC_MAX_ATTN_SPLITS 16 // largest split of the key range across workgroups
 
-struct GemmPlan {      // how one weight-streaming GEMM is cut into workgroups
-    int32_t ncg;       // column groups of 8 n-tiles (128 columns)
-    int32_t sk;        // K slices per column group (cross-workgroup split-K with ordered fix-up)
-};
 struct FastPlan {
-    GemmPlan qkv, o, gu, down, lm;
     int32_t attn_splits;
     int32_t attn_bpw;  // key blocks of 32 per attention workgroup (decides at run time how many of the splits work)
     int32_t co_single; // column-owner GEMM: 1 = one weight batch in flight per wave, 0 = two, 2 = chosen per GEMM
@@ -20,7 +14,7 @@ struct FastPlan {
     int32_t co_rot[2][5];  // per-GEMM: walk the K batches in a per-wave rotated order (same defaults / measurement)
     int32_t ks[5];     // column-owner GEMM: K slices per owner (residual GEMMs only; 1 elsewhere)
     int32_t nw2[5], ks2[5];   // the same for passes of 17..32 rows (two row tiles per workgroup)
-    int32_t nw[5];     // column-owner GEMM: workgroups for QKV, O, gate/up, down, LM head; 0 = use the split-K kernel
+    int32_t nw[5];     // column-owner GEMM: workgroups for QKV, O, gate/up, down, LM head
 };
 struct FastArgs {
     KernelDims kd;     // kd.M = rows of this pass
@@ -56,5 +50,5 @@ size_t fc_attn_iso_scratch_bytes(int W, int H, int Dh);
 hipError_t fc_attn_iso(const float* q, const void* kc, const void* vc, int n, int W, int H, int Hkv, int Dh, int S,
                        int dt, float* out, void* scratch, hipStream_t st);
 size_t fc_lmhead_iso_scratch_bytes(int M, int d, int V);
-hipError_t fc_lmhead_iso(const float* act, const void* packed, int M, int d, int V, int32_t* ids, float* top,
+hipError_t fc_lmhead_iso(const float* act, const void* packed, int M, int d, int V, int32_t* ids, float* top, float* top2,
                          float* logits, void* scratch, hipStream_t st);

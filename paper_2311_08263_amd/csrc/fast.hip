@@ -2,9 +2,7 @@
 // O-proj+residual, gate/up+SwiGLU, down+residual), then the LM head with fused argmax.
 #include <string.h>
 #include "kernels.h"
-#include "gemm16.h"
 #include "attn16.h"
-#include "persist.h"
 #include "gemmco.h"
 #include "gemm256.h"
 
@@ -15,29 +13,8 @@ bool fc_fast_supported(const KernelDims& kd, int rows) {
            (kd.H * kd.Dh) % 256 == 0 && kd.S % 32 == 0 && kd.V % 16 == 0;
 }
 
-// K slices per column group: about 500 workgroups in all (two per CU, one round), slices of 2..4
-// units of 256 inputs where the shape allows (measured on the 7B shape: fewer, fatter slices beat
-// many thin ones because every slice pays the fixed cost of the cross-workgroup fix-up).
-static int choose_sk(int K, int ncg) {
-    const int NU = K / 256;
-    int lo = (NU + 3) / 4, hi = NU / 2;
-    if (lo < 1) lo = 1;
-    if (hi < lo) hi = lo;
-    if (hi > FC_MAX_SK) hi = FC_MAX_SK;
-    int sk = (500 + ncg / 2) / ncg;
-    if (sk < lo) sk = lo;
-    if (sk > hi) sk = hi;
-    return sk;
-}
-
 void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     memset(p, 0, sizeof(*p));
-    auto mk = [&](int K, int N) { GemmPlan g; g.ncg = (N / 16 + 7) / 8; g.sk = K % 256 == 0 ? choose_sk(K, g.ncg) : 1; return g; };
-    p->qkv = mk(kd.d, kd.qkvN);
-    p->o = mk(kd.H * kd.Dh, kd.d);
-    p->gu = mk(kd.d, 2 * kd.F);
-    p->down = mk(kd.F, kd.d);
-    p->lm = mk(kd.d, kd.V);
     // at most 8 key splits: the last workgroup to arrive folds up to 8 partial results in one round of loads
     // (measured at 2050 positions, 32 heads: 8 splits 24 us, 12 splits 32 us; at 350 positions 6 splits of 2
     // key blocks 12.7 us, 3 splits of 4 blocks 14.9 us)
@@ -51,14 +28,12 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     p->attn_bpw = 2;
     // column-owner kernel: workgroups per GEMM (one per CU where the matrix allows)
     const int nts[5] = {kd.qkvN / 16, kd.d / 16, 2 * kd.F / 16, kd.d / 16, kd.V / 16};
-    // measured on the 7B shape: one workgroup per CU, one weight batch in flight per wave; the O
-    // projection (few columns, short K) is faster through the split-K kernel
+    // measured on the 7B shape: one workgroup per CU
     for (int i = 0; i < 5; ++i) { p->nw[i] = fc_gemmco_grid(nts[i]); p->ks[i] = 1; }
     if (nts[1] < 512) {                  // O projection with fewer than two n-tiles per CU
-        // measured at the 7B shape: two K slices per owner (16.6 us) beat the split-K kernel (17.6 us)
+        // measured at the 7B shape: two K slices per owner (16.6 us against 17.6 us for one)
         const int G = p->nw[1], K = kd.H * kd.Dh;
         if (G % 2 == 0 && G / 2 <= nts[1] && (nts[1] + G / 2 - 1) / (G / 2) <= 8 && K >= 2048) p->ks[1] = 2;
-        else p->nw[1] = 0;
     }
     // down projection: K is long and the columns few, so every workgroup would read far more activation
     // bytes than weight bytes; K slices per owner cut that (measured at the 7B shape)
@@ -96,13 +71,12 @@ static ManyRowScratch many_row_scratch(const KernelDims& kd) {
 }
 
 void fc_fast_scratch_sizes(const KernelDims& kd, size_t* gemm_part_bytes, size_t* attn_part_bytes) {
-    // partial tiles: (column groups x slices) x 8 waves x 2 row tiles x 1 KB, sized for the widest matrix
+    // column-owner kernel with K slices per owner: per workgroup up to 16 partial tiles of 1 KB and 32 partial row
+    // sums; at most as many workgroups as the widest matrix has n-tiles
     int nmax = 2 * kd.F;
     if (kd.qkvN > nmax) nmax = kd.qkvN;
     if (kd.V > nmax) nmax = kd.V;
-    const size_t ncg = (size_t)(nmax / 16 + 7) / 8;
-    *gemm_part_bytes = ncg * FC_MAX_SK * (8 * 2 * 1024 + 2 * 16 * 4) + 4096;
-    if (*gemm_part_bytes < fc_persist_part_bytes(kd)) *gemm_part_bytes = fc_persist_part_bytes(kd);
+    *gemm_part_bytes = (size_t)(nmax / 16 + 1) * (16 * 1024 + 32 * 4) + 4096;
     // many-row path: activation fragments, row statistics and split-K partial tiles live in the same scratch
     const size_t big = many_row_scratch(kd).end + 4096;
     if (*gemm_part_bytes < big) *gemm_part_bytes = big;
@@ -125,13 +99,10 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     int32_t* stp = (int32_t*)(ws + wm.state);
     float* x = (float*)(ws + wm.x); float* q = (float*)(ws + wm.qkv); float* att = (float*)(ws + wm.att);
     float* h = (float*)(ws + wm.h);
-    Gemm16Args g; memset(&g, 0, sizeof(g));
-    g.M = M; g.eps = kd.eps; g.part = (float*)(ws + wm.gemm_part);
-    g.cnt = (int32_t*)(ws + wm.gemm_cnt);
+    struct { const int32_t* n_state; const float* cosT; const float* sinT; bf16_t* kc; bf16_t* vc; float* amax_val; int layer; } g;
     g.n_state = stp + wm.st.n; g.cosT = (const float*)(ws + wm.rope_cos); g.sinT = (const float*)(ws + wm.rope_sin);
     g.kc = (bf16_t*)(ws + wm.kc); g.vc = (bf16_t*)(ws + wm.vc);
-    g.H = kd.H; g.Hkv = kd.Hkv; g.B = kd.B; g.S = kd.S; g.Wn = kd.W; g.kvp = kd.kvp;
-    g.amax_val = (float*)(ws + wm.amax_part);
+    g.amax_val = (float*)(ws + wm.amax_part); g.layer = 0;
     AttnArgs at; memset(&at, 0, sizeof(at));
     at.q = q; at.ldq = qd; at.kc = g.kc; at.vc = g.vc; at.B = kd.B; at.H = kd.H; at.Hkv = kd.Hkv; at.S = kd.S; at.W = kd.W; at.kvp = kd.kvp;
     at.n_state = g.n_state; at.out = att; at.ldo = qd; at.part = (float*)(ws + wm.attn_part); at.cnt = (int32_t*)(ws + wm.attn_cnt); at.bpw = a.plan->attn_bpw;
@@ -161,9 +132,9 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     const int lm_ncb = (kd.V / 16 + lm_cols - 1) / lm_cols;
     big.amax_val = g.amax_val; big.amax_idx = (int32_t*)(g.amax_val + (size_t)lm_ncb * big.amax_stride);
     int gi = 0;        // which GEMM of the plan
-    auto gemm = [&](int epi, const GemmPlan& pl, const void* W, int K, int N, const float* X, int ldx, const float* gain,
+    auto gemm = [&](int epi, const void* W, int K, int N, const float* X, int ldx, const float* gain,
                     float* out, int ldo) {
-        // workgroups of the column-owner kernel (0 = split-K kernel) and its K slices per owner
+        // workgroups of the column-owner kernel and its K slices per owner
         const int nw = M <= 16 ? a.plan->nw[gi] : (M <= 32 ? a.plan->nw2[gi] : 0);
         const int ksl = a.tune_gi >= 0 ? a.tune_ks : (M <= 16 ? a.plan->ks[gi] : a.plan->ks2[gi]);
         if (nw > 0) {
@@ -200,23 +171,18 @@ hipError_t fc_fast_forward(const FastArgs& a) {
             }
             return fc_gemm256(epi, big, a.st);
         }
-        // split-K kernel, at most 32 rows
-        g.W = (const bf16_t*)W; g.K = K; g.NT = N / 16; g.sk = pl.sk; g.ldx = ldx; g.gain = gain; g.ldo = ldo;
-        g.M = M; g.m0 = 0; g.X = X; g.out = out;
-        // partial row sums live right after the partial tiles of this launch
-        g.sspart = g.part + (size_t)pl.ncg * pl.sk * 8 * (M > 16 ? 2 : 1) * 256;
-        return fc_gemm16(epi, g, pl.ncg, a.st);
+        return hipErrorInvalidValue;       // every plan gives the column-owner kernel a grid
     };
 
     if (a.tune_gi >= 0) {            // timing run of one GEMM (layer 0 weights, whatever the buffers hold)
         const char* lb = wt + mm.layers_off;
         g.layer = 0; gi = a.tune_gi;
         switch (gi) {
-            case 0: return gemm(EPI_QKV, a.plan->qkv, lb + mm.qkv.off, d, kd.qkvN, x, d, (const float*)(lb + mm.g1_off), q, qd);
-            case 1: return gemm(EPI_RESID, a.plan->o, lb + mm.o.off, qd, d, att, qd, nullptr, x, d);
-            case 2: return gemm(EPI_SWIGLU, a.plan->gu, lb + mm.gu.off, d, 2 * kd.F, x, d, (const float*)(lb + mm.g2_off), h, kd.F);
-            case 3: return gemm(EPI_RESID, a.plan->down, lb + mm.down.off, kd.F, d, h, kd.F, nullptr, x, d);
-            case 4: return gemm(EPI_LMHEAD, a.plan->lm, wt + mm.lm.off, d, kd.V, x, d, (const float*)(wt + mm.gf_off), nullptr, kd.V);
+            case 0: return gemm(EPI_QKV, lb + mm.qkv.off, d, kd.qkvN, x, d, (const float*)(lb + mm.g1_off), q, qd);
+            case 1: return gemm(EPI_RESID, lb + mm.o.off, qd, d, att, qd, nullptr, x, d);
+            case 2: return gemm(EPI_SWIGLU, lb + mm.gu.off, d, 2 * kd.F, x, d, (const float*)(lb + mm.g2_off), h, kd.F);
+            case 3: return gemm(EPI_RESID, lb + mm.down.off, kd.F, d, h, kd.F, nullptr, x, d);
+            case 4: return gemm(EPI_LMHEAD, wt + mm.lm.off, d, kd.V, x, d, (const float*)(wt + mm.gf_off), nullptr, kd.V);
         }
         return hipErrorInvalidValue;
     }
@@ -228,7 +194,7 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         g.layer = l; at.layer = l;
         DBG_STOP();
         gi = 0;
-        FLAUNCH(KK_QKV, gemm(EPI_QKV, a.plan->qkv, lb + mm.qkv.off, d, kd.qkvN, x, d, (const float*)(lb + mm.g1_off), q, qd));
+        FLAUNCH(KK_QKV, gemm(EPI_QKV, lb + mm.qkv.off, d, kd.qkvN, x, d, (const float*)(lb + mm.g1_off), q, qd));
         DBG_STOP();
         if (M > 32) {                  // the many-row O projection reads fragments: attention writes them itself
             at.ofrag = af_att; att_frag = true;
@@ -247,25 +213,24 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         DBG_STOP();
         gi = 1;
         next_gain = (const float*)(lb + mm.g2_off);
-        FLAUNCH(KK_O, gemm(EPI_RESID, a.plan->o, lb + mm.o.off, qd, d, att, qd, nullptr, x, d));
+        FLAUNCH(KK_O, gemm(EPI_RESID, lb + mm.o.off, qd, d, att, qd, nullptr, x, d));
         DBG_STOP();
         gi = 2;
-        FLAUNCH(KK_GU, gemm(EPI_SWIGLU, a.plan->gu, lb + mm.gu.off, d, 2 * kd.F, x, d, (const float*)(lb + mm.g2_off), h, kd.F));
+        FLAUNCH(KK_GU, gemm(EPI_SWIGLU, lb + mm.gu.off, d, 2 * kd.F, x, d, (const float*)(lb + mm.g2_off), h, kd.F));
         DBG_STOP();
         gi = 3;
         next_gain = l + 1 < kd.L ? (const float*)(wt + mm.layers_off + (size_t)(l + 1) * mm.layer_stride + mm.g1_off) : (const float*)(wt + mm.gf_off);
-        FLAUNCH(KK_DOWN, gemm(EPI_RESID, a.plan->down, lb + mm.down.off, kd.F, d, h, kd.F, nullptr, x, d));
+        FLAUNCH(KK_DOWN, gemm(EPI_RESID, lb + mm.down.off, kd.F, d, h, kd.F, nullptr, x, d));
     }
     if (a.dbg_stop >= 0 && nstage >= a.dbg_stop) return hipSuccess;
     if (a.lmhead) {
         const int stride = M > 16 ? 32 : 16;
         const int nwlm = M <= 16 ? a.plan->nw[4] : (M <= 32 ? a.plan->nw2[4] : 0);
-        const int nwin = nwlm > 0 ? nwlm : a.plan->lm.ncg;    // partial winners to reduce
-        g.amax_idx = (int32_t*)(g.amax_val + (size_t)nwin * stride);
+        const int nwin = nwlm;                                // partial winners to reduce
         gi = 4;
-        FLAUNCH(KK_LM, gemm(EPI_LMHEAD, a.plan->lm, wt + mm.lm.off, d, kd.V, x, d, (const float*)(wt + mm.gf_off), a.dbg_logits, kd.V));
+        FLAUNCH(KK_LM, gemm(EPI_LMHEAD, wt + mm.lm.off, d, kd.V, x, d, (const float*)(wt + mm.gf_off), a.dbg_logits, kd.V));
         if (M <= 32)
-            FLAUNCH(KK_ARGMAX, fc_argmax_final(g.amax_val, g.amax_idx, nwin, stride, M, stp + wm.st.o,
+            FLAUNCH(KK_ARGMAX, fc_argmax_final(g.amax_val, (const int32_t*)(g.amax_val + (size_t)nwin * stride), nwin, stride, M, stp + wm.st.o,
                                                (float*)(ws + wm.topv), a.st));
         else
             FLAUNCH(KK_ARGMAX, fc_argmax_final(big.amax_val, big.amax_idx, lm_ncb, big.amax_stride, M,
@@ -355,41 +320,47 @@ hipError_t fc_attn_iso(const float* q, const void* kc, const void* vc, int n, in
     return fc_attn16(at, 1, iso_attn_splits(n + W), st);
 }
 
-// scratch: counters [ncg], winners [ncg][32] value + index, partial tiles
+// scratch: winners per workgroup [workgroups][32] value + index, then room for logits (plain path only)
+static int lm_iso_grid(int M, int d, int V) { return fc_gemmco_grid(V / 16, M > 16 ? fc_gemmco_most(32, d, false) : 8); }
 size_t fc_lmhead_iso_scratch_bytes(int M, int d, int V) {
-    const size_t ncg = (size_t)(V / 16 + 7) / 8;
-    return ((ncg * 4 + 255) & ~(size_t)255) + ncg * 32 * 8 + 256 + ncg * FC_MAX_SK * (8 * 2 * 1024 + 128) + (size_t)M * V * 4;
+    const size_t G = (size_t)(V / 16 + 1);
+    return G * 32 * 8 + 256 + (size_t)M * V * 4;
 }
-hipError_t fc_lmhead_iso(const float* act, const void* packed, int M, int d, int V, int32_t* ids, float* top,
+// largest logit of every row among the ids other than the row's winner
+__global__ void k_top2(const float* logits, int V, const int32_t* ids, float* top2) {
+    __shared__ float sv[4];
+    const int m = blockIdx.x, win = ids[m];
+    float best = -3.0e38f;
+    for (int n = threadIdx.x; n < V; n += blockDim.x) { const float v = logits[(size_t)m * V + n]; if (n != win && v > best) best = v; }
+    for (int o = 32; o > 0; o >>= 1) best = fmaxf(best, __shfl_xor(best, o, 64));
+    if ((threadIdx.x & 63) == 0) sv[threadIdx.x >> 6] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) top2[m] = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+}
+hipError_t fc_lmhead_iso(const float* act, const void* packed, int M, int d, int V, int32_t* ids, float* top, float* top2,
                          float* logits, void* scratch, hipStream_t st) {
-    const int ncg = (V / 16 + 7) / 8;
     char* sc = (char*)scratch;
-    const size_t cnt_bytes = ((size_t)ncg * 4 + 255) & ~(size_t)255;
+    float* lg_scratch = (float*)(sc + (size_t)(V / 16 + 1) * 32 * 8 + 256);
+    if (top2 && !logits) logits = lg_scratch;              // the runner-up is read off the logits
     if (M > 32 || d % 256) {
-        float* lg = logits ? logits : (float*)(sc + cnt_bytes + (size_t)ncg * 32 * 8 + 256 + (size_t)ncg * FC_MAX_SK * (8 * 2 * 1024 + 128));
+        float* lg = logits ? logits : lg_scratch;
         hipError_t e = fc_gemm_plain(packed, FASTCOT_BF16, d, V, V, act, d, lg, V, M, 0, st);
         if (e != hipSuccess) return e;
-        return fc_argmax_plain(lg, M, V, ids, top, st);
+        e = fc_argmax_plain(lg, M, V, ids, top, st);
+        if (e != hipSuccess || !top2) return e;
+        k_top2<<<M, 256, 0, st>>>(lg, V, ids, top2);
+        return hipGetLastError();
     }
-    if (M <= 16) {
-        GemmCoArgs co; memset(&co, 0, sizeof(co));
-        const int nwg = fc_gemmco_grid(V / 16), nw = nwg;
-        co.W = (const bf16_t*)packed; co.K = d; co.NT = V / 16; co.X = act; co.ldx = d; co.M = M; co.out = logits; co.ldo = V;
-        co.amax_val = (float*)(sc + cnt_bytes + (size_t)ncg * 32 * 8 + 256);      // the partial-tile area is free here
-        co.amax_idx = (int32_t*)(co.amax_val + (size_t)nwg * 16);
-        hipError_t e = fc_gemmco(EPI_LMHEAD, co, nw, st);
-        if (e != hipSuccess) return e;
-        return fc_argmax_final(co.amax_val, co.amax_idx, nwg, 16, M, ids, top, st);
-    }
-    Gemm16Args g; memset(&g, 0, sizeof(g));
-    const int stride = M > 16 ? 32 : 16, sk = choose_sk(d, ncg);
-    g.W = (const bf16_t*)packed; g.K = d; g.NT = V / 16; g.sk = sk; g.X = act; g.ldx = d; g.M = M; g.gain = nullptr;
-    g.cnt = (int32_t*)sc;
-    g.amax_val = (float*)(sc + cnt_bytes); g.amax_idx = (int32_t*)(g.amax_val + (size_t)ncg * stride);
-    g.part = (float*)(sc + cnt_bytes + (size_t)ncg * 32 * 8 + 256);
-    g.sspart = g.part + (size_t)ncg * sk * 8 * (M > 16 ? 2 : 1) * 256;
-    g.out = logits; g.ldo = V;
-    hipError_t e = fc_gemm16(EPI_LMHEAD, g, ncg, st);
+    GemmCoArgs co; memset(&co, 0, sizeof(co));
+    const int nwg = lm_iso_grid(M, d, V), stride = M > 16 ? 32 : 16;
+    co.W = (const bf16_t*)packed; co.K = d; co.NT = V / 16; co.X = act; co.ldx = d; co.M = M; co.out = logits; co.ldo = V;
+    co.single_buffer = 1;
+    co.amax_val = (float*)sc;
+    co.amax_idx = (int32_t*)(co.amax_val + (size_t)nwg * stride);
+    hipError_t e = fc_gemmco(EPI_LMHEAD, co, nwg, st);
     if (e != hipSuccess) return e;
-    return fc_argmax_final(g.amax_val, g.amax_idx, ncg, stride, M, ids, top, st);
+    e = fc_argmax_final(co.amax_val, co.amax_idx, nwg, stride, M, ids, top, st);
+    if (e != hipSuccess || !top2) return e;
+    k_top2<<<M, 256, 0, st>>>(logits, V, ids, top2);
+    return hipGetLastError();
 }

@@ -1,6 +1,6 @@
 // Argument block and launchers of the many-row bf16 GEMM (see gemm256.hip).
 #pragma once
-#include "gemm16.h"
+#include "gemmco.h"
 
 struct Gemm256Args {
     const bf16_t* W;       // fused matrix in fragment order

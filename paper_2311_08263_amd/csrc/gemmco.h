@@ -1,6 +1,8 @@
 // Argument block and launcher of the column-owner weight-streaming GEMM (see gemmco.hip).
 #pragma once
-#include "gemm16.h"
+#include "fast.h"
+
+enum { EPI_RESID = 0, EPI_SWIGLU = 1, EPI_QKV = 2, EPI_LMHEAD = 3 };
 
 struct GemmCoArgs {
     const bf16_t* W;       // fused matrix in fragment order
@@ -33,3 +35,6 @@ int fc_gemmco_grid(int NT, int most = 8);
 int fc_gemmco_most(int M, int K, bool gain);
 int fc_num_cus();      // compute units of the current device
 hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st);
+// reduction of the LM head's per-workgroup winners [nparts][stride] to one id and value per row (lowest id on ties)
+hipError_t fc_argmax_final(const float* val, const int32_t* idx, int nparts, int stride, int M, int32_t* ids, float* top,
+                           hipStream_t st);

@@ -27,6 +27,19 @@ __device__ inline uint32_t rne16(float f) {
 }
 __device__ inline float up16(uint32_t b) { return __uint_as_float(b << 16); }
 
+#ifdef FC_TRACE
+// timing build only: per wave, wall-clock stamps (10 ns units) at a few points of the kernel selected by FC_TRACE_EPI
+__device__ unsigned long long g_trace[512 * 8 * 8];
+#define STAMP(i) do { if (EPI == FC_TRACE_EPI && lane == 0 && blockIdx.x < 512 && (FC_TRACE_K == 0 || a.K == FC_TRACE_K)) { unsigned long long* t_ = g_trace + ((size_t)blockIdx.x * 8 + w) * 8; if ((i) == 0) { for (int z_ = 1; z_ < 8; ++z_) t_[z_] = 0; } t_[i] = wall_clock64(); } } while (0)
+extern "C" int fastcot_trace_read(void* host, size_t bytes) {
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), bytes < sizeof(g_trace) ? bytes : sizeof(g_trace)) == hipSuccess ? 0 : -4;
+}
+#define STAMP_FIRST_DATA(ib) do { if (EPI == FC_TRACE_EPI && (ib) == 0 && (FC_TRACE_K == 0 || a.K == FC_TRACE_K)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); STAMP(1); } } while (0)
+#else
+#define STAMP(i) do { } while (0)
+#define STAMP_FIRST_DATA(ib) do { } while (0)
+#endif
+
 // One batch = KB k-tiles: the wave's weight tiles for its n-tiles and its activation octets.
 template <int NW, int KB, int MT> struct Batch {
     u32x4_t wt[KB][NW];
@@ -48,6 +61,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     float* lds_gain = (float*)(lds_ami + 8 * 16);       // [K] (only with a norm in front)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int lm = lane & 15, g4 = lane >> 4;
+    STAMP(0);
     // workgroup i owns n-tiles [i*NT/G, (i+1)*NT/G): at most NW of them
     const int ks = (EPI != EPI_LMHEAD && a.ks > 1) ? a.ks : 1;
     const int G = gridDim.x / ks, owner = blockIdx.x / ks, slice = blockIdx.x % ks;
@@ -228,6 +242,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
             __syncthreads();
         }
         for (int ib = 0; ib < nb; ib += 2) {
+            STAMP_FIRST_DATA(ib);
             compute(A, ib);
             load(A, ib + 2);
             __builtin_amdgcn_sched_barrier(0);          // the loads stay here, ahead of the other batch's arithmetic
@@ -241,12 +256,14 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
             __syncthreads();
         }
         for (int ib = 0; ib < nb; ++ib) {
+            STAMP_FIRST_DATA(ib);
             compute(A, ib);
             load(A, ib + 1);
         }
     }
     }
 
+    STAMP(2);
     // the eight K slices meet in LDS, in two rounds so that four partial sets (4 x TW KB) are enough: waves
     // 4..7 publish, waves 0..3 add those to their own and publish the sums
 #pragma unroll
@@ -277,6 +294,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     }
     __syncthreads();
 
+    STAMP(3);
     // wave w finishes tiles w and (with more than 8 tiles) w + 8: lane holds row tm*16 + lm, columns
     // nt*16 + 4*g4 + r.  MT divides 8, so both tiles of a wave belong to the same row tile tm.
     const int tm = w % MT;
@@ -417,6 +435,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
             for (int r = 0; r < 4; ++r) if (vv[r] > best || (vv[r] == best && n0 + r < bi)) { best = vv[r]; bi = n0 + r; }
         }
     }
+    STAMP(4);
     if (EPI == EPI_LMHEAD) {
 #pragma unroll
         for (int o = 16; o <= 32; o <<= 1) {
@@ -580,4 +599,32 @@ hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st) {
         case EPI_LMHEAD: return launch_epi<EPI_LMHEAD>(a, G, st);
     }
     return hipErrorInvalidValue;
+}
+
+// reduction of the LM head's per-workgroup winners: lowest id on ties
+__global__ void k_argmax_final(const float* val, const int32_t* idx, int nparts, int stride, int32_t* ids, float* top) {
+    __shared__ float bv[4];
+    __shared__ int bi[4];
+    const int m = blockIdx.x;
+    float best = -3.0e38f; int b = 0x7fffffff;
+    for (int c = threadIdx.x; c < nparts; c += blockDim.x) {
+        float v = val[(size_t)c * stride + m]; int i = idx[(size_t)c * stride + m];
+        if (v > best || (v == best && i < b)) { best = v; b = i; }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        float ov = __shfl_xor(best, o, 64); int oi = __shfl_xor(b, o, 64);
+        if (ov > best || (ov == best && oi < b)) { best = ov; b = oi; }
+    }
+    if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = b; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int q = 1; q < (int)(blockDim.x >> 6); ++q)
+            if (bv[q] > best || (bv[q] == best && bi[q] < b)) { best = bv[q]; b = bi[q]; }
+        ids[m] = b; top[m] = best;
+    }
+}
+hipError_t fc_argmax_final(const float* val, const int32_t* idx, int nparts, int stride, int M, int32_t* ids, float* top,
+                           hipStream_t st) {
+    k_argmax_final<<<M, 256, 0, st>>>(val, idx, nparts, stride, ids, top);
+    return hipGetLastError();
 }

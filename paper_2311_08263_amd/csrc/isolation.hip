@@ -140,9 +140,9 @@ extern "C" int fastcot_lmhead_pack(const void* src, int32_t d, int32_t V, void* 
     return e == hipSuccess ? 0 : FASTCOT_EHIP;
 }
 extern "C" int fastcot_lmhead_argmax(const float* d_act, const void* d_packed, int32_t M, int32_t d, int32_t V,
-                                     int32_t* d_ids, float* d_top, float* d_logits, void* d_scratch, void* hip_stream) {
+                                     int32_t* d_ids, float* d_top, float* d_top2, float* d_logits, void* d_scratch, void* hip_stream) {
     if (!d_act || !d_packed || !d_ids || !d_top || !d_scratch) return FASTCOT_EINVAL;
     if (M <= 0 || d <= 0 || V <= 0 || d % 32 || V % 16) return FASTCOT_EINVAL;
-    hipError_t e = fc_lmhead_iso(d_act, d_packed, M, d, V, d_ids, d_top, d_logits, d_scratch, (hipStream_t)hip_stream);
+    hipError_t e = fc_lmhead_iso(d_act, d_packed, M, d, V, d_ids, d_top, d_top2, d_logits, d_scratch, (hipStream_t)hip_stream);
     return e == hipSuccess ? 0 : FASTCOT_EHIP;
 }

@@ -53,5 +53,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert L.fastcot_init(ctypes.byref(cfg), None, None, 0, None, ctypes.byref(out)) == -1
     assert L.fastcot_pack_tensor(ctypes.byref(cfg), 99, 0, None, None, None) == -1
     assert L.fastcot_attn_window(None, None, None, 0, 1, 1, 1, 16, 16, 0, None, None, None) == -1
-    assert L.fastcot_lmhead_argmax(None, None, 1, 32, 16, None, None, None, None, None) == -1
+    assert L.fastcot_lmhead_argmax(None, None, 1, 32, 16, None, None, None, None, None, None) == -1
+    assert L.fastcot_pack_weights(ctypes.byref(cfg), None, None, None) == -1
+    assert L.fastcot_canonical_offset(ctypes.byref(cfg), 3, 99) == ctypes.c_size_t(-1).value
     assert L.fastcot_kernel_name(4) == b"attention"

@@ -33,18 +33,14 @@ def setup(fc, shape, B, S, W):
     return fc.Context(cfg, packed), oracle.model_from_synth(shape)
 
 
-@pytest.mark.parametrize("persistent", [0, 1])
 @pytest.mark.parametrize("shape,B,W,P", [(SMALL, 1, 16, 45), (SMALL, 2, 16, 33), (SMALL_MHA, 1, 8, 20),
                                          (SMALL, 1, 32, 70), (SMALL_MHA, 3, 5, 12), (SMALL, 4, 32, 40),
                                          (SMALL_MHA, 3, 16, 30), (SMALL, 1, 64, 75), (SMALL_MHA, 2, 40, 300)])
-def test_follow_mode_small_models(fc, shape, B, W, P, persistent):
-    if persistent and B * W > 16:
-        pytest.skip("the persistent kernel covers at most 16 rows per step")
-    say(f"bf16 follow shape d={shape.d_model} B={B} W={W} P={P} persistent={persistent}")
+def test_follow_mode_small_models(fc, shape, B, W, P):
+    say(f"bf16 follow shape d={shape.d_model} B={B} W={W} P={P}")
     N = 48
     S = ((P + N + 2 * W + 31) // 32) * 32
     ctx, om = setup(fc, shape, B, S, W)
-    ctx.set_option(4, persistent)
     lens = [P - 3 * b for b in range(B)]
     prompts = synthgen.prompts(B, P, shape.vocab, seed=21)
     buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=22)
@@ -56,12 +52,12 @@ def test_follow_mode_small_models(fc, shape, B, W, P, persistent):
 
 @pytest.mark.parametrize("W", [16, 24])
 def test_without_autotune(fc, W):
-    """The plan's defaults (no timing runs at prefill: option 34 = 0) pass the same bar as the measured plan."""
+    """The plan's defaults (no timing runs at prefill) pass the same bar as the measured plan."""
     shape, B, P, N = SMALL, 2, 37, 48
     say(f"bf16 follow without autotune W={W}")
     S = ((P + N + 2 * W + 31) // 32) * 32
     ctx, om = setup(fc, shape, B, S, W)
-    ctx.set_option(34, 0)
+    ctx.set_option(fc.binding.OPT_AUTOTUNE, 0)
     lens = [P, P - 4]
     prompts = synthgen.prompts(B, P, shape.vocab, seed=61)
     buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=62)
@@ -181,20 +177,18 @@ def test_join_bf16(fc):
     print(f"join follow: max |dlogit| {r['max_err']:.2e} over {r['rows']} rows, {r['low_margin_rows']} low-margin")
 
 
-@pytest.mark.parametrize("persistent", [0, 1])
-def test_per_sequence_windows_bf16(fc, persistent):
+def test_per_sequence_windows_bf16(fc):
     """bf16 model, follow mode with per-sequence window sizes (per-stage kernels and the one-launch step): the
     verified count, accepted tokens and committed length come from the first W_b rows of a sequence; one sequence
     has a perfect draft so that the cut at W_b, not a mismatch, is what ends its verification."""
     shape, W, B, P, N = SMALL, 8, 2, 30, 40
     S = ((P + N + 2 * W + 31) // 32) * 32
     ctx, om = setup(fc, shape, B, S, W)
-    ctx.set_option(4, persistent)
     prompts = synthgen.prompts(B, P, shape.vocab, seed=111)
     lens = [P, P - 5]
     buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=112)
     buf[1, :] = om.greedy_ar(prompts[1, :lens[1]], N + 2 * W)
-    say(f"bf16 per-sequence windows persistent={persistent}")
+    say(f"bf16 per-sequence windows")
     ctx.prefill(prompts, lens, buf)
     ctx.set_windows([6, 3])
     r = follow_steps(ctx, om, prompts, lens, 6, TOL, wins=[6, 3])
@@ -301,3 +295,33 @@ def test_lmhead_argmax_isolation(fc, M, d, V):
     # without the debug logits the result is the same
     ids2, _, _ = fc.lmhead_argmax(torch.from_numpy(act).cuda(), packed, V, want_logits=False)
     assert (ids2.cpu().numpy() == ids).all()
+    # the runner-up: the largest logit among the other ids (the oracle's, within the logit tolerance; the
+    # kernel's own, exactly)
+    ids3, top3, _, top2 = fc.lmhead_argmax(torch.from_numpy(act).cuda(), packed, V, want_top2=True)
+    torch.cuda.synchronize()
+    assert (ids3.cpu().numpy() == ids).all() and (top3.cpu().numpy() == lg.max(-1)).all()
+    masked = lg.copy()
+    masked[np.arange(M), ids] = -np.inf
+    assert (top2.cpu().numpy() == masked.max(-1)).all()
+    assert np.abs(top2.cpu().numpy() - np.partition(ref_logits, -2, axis=-1)[:, -2]).max() < 1e-3
+
+
+def test_pack_weights_whole_model_equals_tensor_by_tensor(fc):
+    """fastcot_pack_weights (one canonical buffer, offsets from fastcot_canonical_offset) gives the same packed
+    bytes as fastcot_pack_tensor called per tensor, gains included."""
+    import torch
+    shape = SMALL
+    cfg = fc.Config.from_shape(shape, 1, 64, 8)
+    rng = np.random.default_rng(3)
+    gains = {"gf": rng.uniform(0.5, 1.5, shape.d_model).astype(np.float32),
+             "g1": [rng.uniform(0.5, 1.5, shape.d_model).astype(np.float32) for _ in range(shape.n_layers)],
+             "g2": [None] * shape.n_layers}
+
+    def gen():
+        for spec in synthgen.weight_tensors(shape):
+            yield spec.name, spec.layer, synthgen.weight_array(shape, spec, as_bf16_bits=True)
+    say("pack_weights: whole model against tensor by tensor")
+    a = fc.pack_weights(cfg, gen(), gains)
+    b = fc.pack_weights_whole(cfg, gen(), gains)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)

@@ -48,7 +48,7 @@ def test_random_runs_fp32_bit_exact():
         if packed is None:
             packed = fc.load_synth_weights(cfg, TINY)
         ctx = fc.Context(cfg, packed)
-        ctx.set_option(35, compact)
+        ctx.set_option(4, compact)
         ctx.set_option(2, graph)
         ctx.prefill(prompts, lens, buf)
         if wins:

@@ -148,7 +148,7 @@ def test_finished_sequences_leave_the_batch(env):
     res = {}
     trigger = np.array([3, 14, 15], dtype=np.int32)
     for compact in (1, 0):
-        ctx.set_option(35, compact)
+        ctx.set_option(4, compact)
         ctx.prefill(prompts, lens, buf)
         out = ctx.generate(N)
         res[compact] = (out, ctx.state(), ctx.answer(trigger, 6))
