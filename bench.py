@@ -102,7 +102,7 @@ def time_launches(torch, fn, n):
     return 1e3 * e0.elapsed_time(e1) / n
 
 
-def extras(torch, fc, synthgen, packed, log_fn):
+def extras(torch, fc, synthgen, packed, log_fn, chain_bytes=None):
     """Secondary measurements: the device's plain streaming-read rate and the two kernels in isolation
     (window attention over a 2048-token cache; LM head + argmax), cache-cold by rotating buffer sets."""
     out = {}
@@ -111,6 +111,23 @@ def extras(torch, fc, synthgen, packed, log_fn):
     us = time_launches(torch, lambda i: fc.stream_read(packed[:nbytes], sink), 5)
     out["stream_read_ceiling"] = {"bytes": int(nbytes), "us": round(us, 1), "GB/s": round(nbytes / us / 1e3, 0)}
     log_fn(f"plain streaming read of {nbytes / 1e9:.2f} GB: {us:.0f} us -> {nbytes / us / 1e3:.0f} GB/s")
+    # the floor of a step made of separate launches: a chain of plain streaming reads with the byte counts of the
+    # step's kernels (per layer QKV, the K/V the attention reads, O, gate/up, down; then the LM head), replayed
+    # as one graph like the step itself
+    if chain_bytes:
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            fc.stream_read_chain(packed, chain_bytes, sink)          # warm (module load) outside the capture
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                total = fc.stream_read_chain(packed, chain_bytes, sink)
+        us = time_launches(torch, lambda i: g.replay(), 10)
+        out["stream_chain_floor"] = {"launches": len(chain_bytes), "bytes": int(total), "ms": round(us / 1e3, 4),
+                                     "GB/s": round(total / us / 1e3, 0), "frac_of_8TBs": round(total / us / 1e3 / HBM_PEAK_GBS, 4)}
+        log_fn(f"chain of {len(chain_bytes)} plain streaming launches with the step's byte counts ({total / 1e9:.2f} GB): "
+               f"{us / 1e3:.3f} ms -> {total / us / 1e3:.0f} GB/s ({100 * total / us / 1e3 / HBM_PEAK_GBS:.1f}% of 8 TB/s)")
+        del g
     # attention alone: 32 heads x 128, 2048 committed positions + 16 window rows, bf16 cache (one plane)
     n, W, H, Dh, S = 2048, 16, 32, 128, 2080
     sets = []
@@ -138,6 +155,53 @@ def extras(torch, fc, synthgen, packed, log_fn):
                                "GB/s": round(wb / us / 1e3, 0), "frac_of_8TBs": round(wb / us / 1e3 / HBM_PEAK_GBS, 4)}
     log_fn(f"LM head + argmax alone ({M} x {d} x {V}): {us:.1f} us, {wb / us / 1e3:.0f} GB/s")
     return out
+
+
+def step_only(torch, fc, synthgen, name, steps, warm, log_fn):
+    """ms/step, fraction of the HBM roofline and per-kernel launch times of another workload (no generate run)."""
+    shape_name, B, P, W, N = WORKLOADS[name]
+    shape = synthgen.SHAPES[shape_name]
+    max_seq = ((P + W * (steps + warm + 4) + 31) // 32) * 32
+    cfg = fc.Config.from_shape(shape, B, max_seq, W)
+    t0 = time.time()
+    packed = fc.load_synth_weights(cfg, shape)
+    ctx = fc.Context(cfg, packed)
+    log_fn(f"secondary workload {name}: model resident after {time.time() - t0:.1f}s")
+    ctx.prefill(synthgen.prompts(B, P, shape.vocab), [P] * B, synthgen.buffer_init(B, W * (steps + warm + 3), shape.vocab))
+    for _ in range(warm):
+        ctx.step(sync=False)
+    ctx.stream.synchronize()
+    n0 = ctx.state()["n"].copy()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ctx.step(sync=False)
+    ctx.stream.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / steps
+    n1 = ctx.state()["n"]
+    alg = algorithmic_bytes(shape, 2, B, W, (n0 + n1) / 2.0)
+    rec = {"workload": f"llama2-{shape_name}-shaped, batch {B}, prompt {P}, window {W}", "steps": steps, "ms_per_step": round(ms, 4),
+           "step_algorithmic_bytes": int(alg), "hbm_frac": round(alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    prof = ctx.profile_step(2)
+    prof.pop("empty_kernel", None)
+    rec["kernels_us"] = {k: round(v[0] * 1e3, 2) for k, v in prof.items()}
+    if B * W > 32:
+        # useful flops: 2 * rows * streamed parameters + attention; the GEMMs issue twice the useful MFMAs (bf16 hi + lo)
+        ctxlen = float(np.mean((n0 + n1) / 2.0)) + W / 2.0
+        flops = 2.0 * B * W * shape.n_params_streamed() + 4.0 * B * W * shape.q_dim * ctxlen * shape.n_layers
+        tf = flops / (ms * 1e-3) / 1e12
+        rec["useful_tflops"] = round(tf, 1)
+        rec["mfma_frac_useful"] = round(tf / MFMA_BF16_PEAK_TFLOPS, 4)
+        rec["mfma_frac_issued"] = round(2 * tf / MFMA_BF16_PEAK_TFLOPS, 4)
+        wb = weight_bytes_per_step(shape, 2)
+        gu_ms = prof.get("gemm_gate_up", (0.0, 0))[0]
+        if gu_ms > 0:
+            rec["gate_up_useful_tflops"] = round(2.0 * B * W * wb["gemm_gate_up"] / 2 / (gu_ms * 1e-3) / 1e12, 1)
+    log_fn(f"secondary workload {name}: {ms:.3f} ms/step, {100 * rec['hbm_frac']:.1f}% of 8 TB/s" +
+           (f", {rec['useful_tflops']:.0f} TFLOP/s useful ({100 * rec['mfma_frac_useful']:.1f}% of 2.5 PF)" if "useful_tflops" in rec else ""))
+    ctx.close()
+    del ctx, packed
+    torch.cuda.empty_cache()
+    return rec
 
 
 def window_sweep(args):
@@ -189,6 +253,8 @@ def main():
     ap.add_argument("--plain", action="store_true", help="time the plain kernels instead of the MFMA path")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary measurements (streaming-read ceiling, isolated attention and LM head, perfect draft)")
+    ap.add_argument("--no-secondary-workloads", action="store_true",
+                    help="skip the 13B batch-8 and 70B step measurements that follow the default workload")
     ap.add_argument("--window-sweep", action="store_true",
                     help="instead of the benchmark: ms/step for windows 1..128 x prompts 256..4096 on the 7B and 13B shapes")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -339,7 +405,18 @@ def main():
                 f"{net_ms * 1e3:.2f} us ({100 * roofline['frac_net']:.1f} % of peak)")
     extra = None
     if not args.no_extras and not args.plain and shape.dtype == "bf16":
-        extra = extras(torch, fc, synthgen, packed, log)
+        kv_pair = 2 * float(np.mean(n_mid)) * shape.kv_dim * 2 * 2        # K and V of the context, bf16 hi + lo planes
+        per_layer = [wb["gemm_qkv"], kv_pair, wb["gemm_o"], wb["gemm_gate_up"], wb["gemm_down"]]
+        chain = [int(b) for _ in range(shape.n_layers) for b in per_layer] + [wb["lm_head"]]
+        extra = extras(torch, fc, synthgen, packed, log, chain if B * W <= 32 else None)
+    # the other two configurations, steps only (the headline fields above stay this workload's)
+    if not args.no_extras and not args.plain and args.workload == "7b" and not args.no_secondary_workloads:
+        ctx.close()
+        del ctx, packed
+        torch.cuda.empty_cache()
+        extra = extra or {}
+        extra["step_13b_b8_w32"] = step_only(torch, fc, synthgen, "13b", 10, 3, log)
+        extra["step_70b"] = step_only(torch, fc, synthgen, "70b", 10, 3, log)
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(shape, W, log)
