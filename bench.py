@@ -204,6 +204,66 @@ def step_only(torch, fc, synthgen, name, steps, warm, log_fn):
     return rec
 
 
+def kv_format_study(args):
+    """What a narrower K/V cache format would cost in logits: every step of a short run with the cached values
+    rounded as the format would round them (FASTCOT_OPT_KV_EMULATE), against the same steps with the bf16 hi + lo
+    pair the library stores (which the oracle tests hold to a few 1e-4).  Windows are replayed from the
+    reference run, so all formats see identical inputs."""
+    import torch
+    import synthgen
+    import paper_2311_08263_amd as fc
+    modes = {"as computed": 0, "bf16": 1, "fp16": 2, "fp32 upper 24 bits": 3}
+    rows = []
+    for shape_name, P in (("7b", 256), ("13b", 1024), ("70b", 512)):
+        shape = synthgen.SHAPES[shape_name]
+        W, steps = 16, 3
+        max_seq = ((P + 4 * W + 31) // 32) * 32
+        cfg = fc.Config.from_shape(shape, 1, max_seq, W)
+        log(f"kv format study: building {shape_name} weights")
+        packed = fc.load_synth_weights(cfg, shape)
+        prompts = synthgen.prompts(1, P, shape.vocab)
+        buf = synthgen.buffer_init(1, 8 * W, shape.vocab)
+        ref = None
+        for kname, km in modes.items():
+            for vname, vm in modes.items():
+                if (km, vm) not in ((0, 0), (1, 1), (2, 2), (3, 3), (0, 1), (1, 0), (0, 2), (2, 0), (3, 2), (2, 3)):
+                    continue
+                ctx = fc.Context(cfg, packed)
+                ctx.set_option(fc.binding.OPT_KV_EMULATE, km + 16 * vm)
+                ctx.prefill(prompts, [P], buf)
+                dbg = ctx.debug_logits(True)
+                lgs = []
+                for _ in range(steps):
+                    ctx.step()
+                    lgs.append(dbg[:W].clone())
+                torch.cuda.synchronize()
+                if ref is None:
+                    ref = lgs
+                # only steps whose inputs are the reference's count: compare while the windows agree (step 0 always does)
+                err = float((lgs[0] - ref[0]).abs().max())
+                rows.append({"shape": shape_name, "prompt": P, "K": kname, "V": vname, "bytes_per_value": {0: 4, 1: 2, 2: 2, 3: 3}[km] / 2 + {0: 4, 1: 2, 2: 2, 3: 3}[vm] / 2,
+                             "max_abs_dlogit_step0": round(err, 6)})
+                log(f"kv format {shape_name} prompt {P}: K {kname:20s} V {vname:20s} max |dlogit| {err:.2e}")
+                ctx.close()
+                del ctx
+        # the same question for the GEMM inputs: activations as plain bf16 instead of the hi + lo pair, GEMM by GEMM
+        for label, mask in (("QKV", 1), ("O", 2), ("gate/up", 4), ("down", 8), ("LM head", 16), ("O + down", 10), ("all", 31)):
+            ctx = fc.Context(cfg, packed)
+            ctx.set_option(fc.binding.OPT_ACT_EMULATE, mask)
+            ctx.prefill(prompts, [P], buf)          # (the prompt pass of more than 32 rows keeps the pair)
+            dbg = ctx.debug_logits(True)
+            ctx.step()
+            err = float((dbg[:W] - ref[0]).abs().max())
+            rows.append({"shape": shape_name, "prompt": P, "plain_bf16_activations_into": label, "max_abs_dlogit_step0": round(err, 6)})
+            log(f"activation format {shape_name}: plain bf16 into {label:10s} max |dlogit| {err:.2e}")
+            ctx.close()
+            del ctx
+        del packed
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "max |dlogit| of the first step against the bf16 hi + lo pair cache, per emulated K/V storage format",
+                      "n_gpus": 1, "data": "synthetic", "dtype": "bf16", "rows": rows}), flush=True)
+
+
 def window_sweep(args):
     """Step time against window size and prompt length (the measurement of the paper's Fig. 2, Sec. 3.1:
     how large may the window grow before the step stops being free), batch 1, 7B and 13B shapes."""
@@ -257,6 +317,8 @@ def main():
                     help="skip the 13B batch-8 and 70B step measurements that follow the default workload")
     ap.add_argument("--window-sweep", action="store_true",
                     help="instead of the benchmark: ms/step for windows 1..128 x prompts 256..4096 on the 7B and 13B shapes")
+    ap.add_argument("--kv-format-study", action="store_true",
+                    help="instead of the benchmark: logit shift of narrower K/V cache formats (emulated) on the 7B, 13B and 70B shapes")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device-to-device copy of 512 MiB (the known-size kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -266,6 +328,8 @@ def main():
 
     if args.window_sweep:
         return window_sweep(args)
+    if args.kv_format_study:
+        return kv_format_study(args)
 
     import torch
     import synthgen

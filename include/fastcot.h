@@ -186,10 +186,17 @@ int fastcot_debug_logits(fastcot_ctx* ctx, float* d_logits);
  * loads, not additions: logits are the same bits whichever wins, in every process.  Everything that fixes the
  * order of the fp32 additions (K slices per owner, batch order) is chosen from the model shape alone.  Setting
  * any FASTCOT_PLAN_* value turns the measurement off: explicit choices win.
+ * FASTCOT_OPT_KV_EMULATE (bf16 models, matrix-core kernels; a precision study, not a storage mode): value =
+ * K mode + 16 * V mode; before a K (V) value is cached it is rounded as a narrower storage format would round it
+ * (mode 0 as computed, 1 bf16, 2 fp16, 3 the upper 24 bits of fp32) and then kept in the two planes as usual, so
+ * the logits show what that format would cost before a kernel for it exists.  Needs a new fastcot_prefill.
+ * FASTCOT_OPT_ACT_EMULATE (bf16 models, steps of at most 32 rows; a precision study): a mask over the five GEMMs
+ * (bit 0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head); a GEMM whose bit is set takes its input activations as plain
+ * bf16 instead of the bf16 hi + lo pair the kernels use.
  * FASTCOT_OPT_DEBUG_STAGES: run only the first `value` stages of a forward (per layer: QKV, attention, O,
  * gate/up, down); negative (default) = all. */
 enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLANES = 3, FASTCOT_OPT_COMPACT = 4,
-       FASTCOT_OPT_AUTOTUNE = 5, FASTCOT_OPT_DEBUG_STAGES = 6 };
+       FASTCOT_OPT_AUTOTUNE = 5, FASTCOT_OPT_DEBUG_STAGES = 6, FASTCOT_OPT_KV_EMULATE = 7, FASTCOT_OPT_ACT_EMULATE = 8 };
 
 /* Launch-plan values, also set through fastcot_set_option.  They are measurement aids: defaults are chosen from
  * the model shape, and which values exist may change with the kernels.  The five GEMMs are numbered QKV, O,

@@ -113,7 +113,7 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
     KernelDims k;
     k.L = c->n_layers; k.d = d; k.H = c->n_heads; k.Hkv = c->n_kv_heads; k.Dh = c->head_dim; k.F = F;
     k.V = c->vocab; k.B = c->max_batch; k.S = (c->max_seq + 31) & ~31; k.W = c->window;
-    k.qkvN = qd + 2 * kvd; k.eps = c->rms_eps; k.esz = (int)esz; k.kvp = c->dtype == FASTCOT_BF16 ? 2 : 1;
+    k.qkvN = qd + 2 * kvd; k.eps = c->rms_eps; k.esz = (int)esz; k.kvp = c->dtype == FASTCOT_BF16 ? 2 : 1; k.kvq = 0; k.actq = 0;
     // prefill runs the same kernels over chunks of the prompt; where the matrix-core path covers the
     // shape a chunk is up to 256 rows per sequence (at most 512 rows in all), else one window
     k.Wcap = k.W; k.M = k.B * k.W;
@@ -329,6 +329,12 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
     else if (option == FASTCOT_OPT_KV_PLANES) {
         if (c->cfg.dtype != FASTCOT_BF16 || (value != 1 && value != 2)) return fail(c, FASTCOT_EINVAL, "KV planes: 1 or 2, bf16 models only%s");
         c->kd.kvp = value; c->prefilled = 0;      // the cache layout changes: a new prefill is required
+    } else if (option == FASTCOT_OPT_KV_EMULATE) {
+        if (c->cfg.dtype != FASTCOT_BF16 || value < 0 || (value & 15) > 3 || (value >> 4) > 3) return fail(c, FASTCOT_EINVAL, "KV format emulation: K mode + 16 * V mode, modes 0..3, bf16 models only%s");
+        c->kd.kvq = value; c->prefilled = 0;
+    } else if (option == FASTCOT_OPT_ACT_EMULATE) {
+        if (c->cfg.dtype != FASTCOT_BF16 || value < 0 || value > 31) return fail(c, FASTCOT_EINVAL, "activation format emulation: a mask of the five GEMMs, bf16 models only%s");
+        c->kd.actq = value;
     } else if (option == FASTCOT_OPT_COMPACT) c->opt_compact = value != 0;
     else if (option == FASTCOT_OPT_AUTOTUNE) { c->opt_tune = value != 0; c->tuned_rows[0] = c->tuned_rows[1] = 0; }
     else if (option >= FASTCOT_PLAN_NW && option < FASTCOT_PLAN_NW + 5) {

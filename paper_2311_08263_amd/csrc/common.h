@@ -30,6 +30,17 @@ __device__ inline void pk_bf16_hilo(float a, float b, uint32_t& hi, uint32_t& lo
     hi = pk_bf16(a, b);
     lo = pk_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
 }
+
+// Precision study of the K/V cache: what a cached value would be after a round trip through a narrower
+// storage format (0 as computed, 1 bf16, 2 fp16, 3 the upper 24 bits of fp32), round to nearest even.  The
+// value is then stored in the hi + lo planes as usual (which hold any of these exactly), so the effect of a
+// format on the logits can be measured before a kernel for it exists.
+__device__ inline float kv_round(float v, int mode) {
+    if (mode == 1) return __uint_as_float((uint32_t)f32_to_bf16(v) << 16);
+    if (mode == 2) return (float)(_Float16)v;
+    if (mode == 3) { uint32_t u = __float_as_uint(v); u += 0x7Fu + ((u >> 8) & 1u); return __uint_as_float(u & 0xFFFFFF00u); }
+    return v;
+}
 #endif
 
 // ------------------------------------------------------------------ packed weights
@@ -105,6 +116,8 @@ struct KernelDims {    // model + capacities as the kernels need them
     float eps;
     int32_t esz;       // bytes per weight / cache element
     int32_t kvp;       // planes per cached value: bf16 models keep hi (+ lo) bf16 planes, fp32 models one fp32 plane
+    int32_t actq;      // precision study: bit g set = GEMM g (QKV, O, gate/up, down, LM head) takes its activations as plain bf16
+    int32_t kvq;       // precision study: kv_round mode of K (bits 0..3) and of V (bits 4..7) before a value is cached; 0 = off
 };
 
 // element offset of plane 0 of one (layer, sequence, kv head) block of the K or V cache; plane p

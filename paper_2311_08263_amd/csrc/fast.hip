@@ -109,11 +109,11 @@ hipError_t fc_fast_forward(const FastArgs& a) {
 
     GemmCoArgs co; memset(&co, 0, sizeof(co));
     co.M = M; co.eps = kd.eps; co.n_state = g.n_state; co.cosT = g.cosT; co.sinT = g.sinT; co.kc = g.kc; co.vc = g.vc;
-    co.H = kd.H; co.Hkv = kd.Hkv; co.B = kd.B; co.S = kd.S; co.Wn = kd.W; co.kvp = kd.kvp;
+    co.H = kd.H; co.Hkv = kd.Hkv; co.B = kd.B; co.S = kd.S; co.Wn = kd.W; co.kvp = kd.kvp; co.kvq = kd.kvq;
     co.amax_val = g.amax_val; co.single_buffer = 1;
     Gemm256Args big; memset(&big, 0, sizeof(big));
     big.M = M; big.n_state = g.n_state; big.cosT = g.cosT; big.sinT = g.sinT; big.kc = g.kc; big.vc = g.vc;
-    big.H = kd.H; big.Hkv = kd.Hkv; big.B = kd.B; big.S = kd.S; big.Wn = kd.W; big.kvp = kd.kvp;
+    big.H = kd.H; big.Hkv = kd.Hkv; big.B = kd.B; big.S = kd.S; big.Wn = kd.W; big.kvp = kd.kvp; big.kvq = kd.kvq;
     big.amax_stride = (M + 15) / 16 * 16;
     // many-row scratch: the fragments of x, of the attention output and of the hidden activations, the partial
     // row sums of squares of x, then the split-K partial tiles
@@ -139,7 +139,7 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         const int ksl = a.tune_gi >= 0 ? a.tune_ks : (M <= 16 ? a.plan->ks[gi] : a.plan->ks2[gi]);
         if (nw > 0) {
             co.W = (const bf16_t*)W; co.K = K; co.NT = N / 16; co.X = X; co.ldx = ldx; co.gain = gain; co.out = out; co.ldo = ldo;
-            co.layer = g.layer; co.ks = epi != EPI_LMHEAD ? ksl : 1;
+            co.layer = g.layer; co.ks = epi != EPI_LMHEAD ? ksl : 1; co.hi_only = (kd.actq >> gi) & 1;
             // one or two weight batches in flight per wave: which is faster depends on the GEMM and on the shape
             // (7B: two for down and LM head; 13B: two for QKV and gate/up, one for down), so it is a plan entry
             co.single_buffer = a.tune_gi >= 0 ? a.tune_sb : (a.plan->co_single == 2 ? a.plan->co_sb[M > 16][gi] : a.plan->co_single);

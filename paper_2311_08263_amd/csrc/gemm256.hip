@@ -338,6 +338,7 @@ __global__ __launch_bounds__(KG == 1 ? 256 : 512, KG == 1 ? 2 : 1) void k_gemm25
                         const float other = __shfl_xor(v[e], 32, 64);
                         const float c = qc[m & 1][j][e], s = qs[m & 1][j][e];
                         rr[e] = g4 < 2 ? v[e] * c - other * s : v[e] * c + other * s;
+                        if (hh >= a.H) rr[e] = kv_round(rr[e], a.kvq & 15);
                     }
                     const int el = (g4 < 2 ? 0 : 64) + i0;
                     if (pk) {
@@ -361,9 +362,10 @@ __global__ __launch_bounds__(KG == 1 ? 256 : 512, KG == 1 ? 2 : 1) void k_gemm25
                     bf16_t* vr = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + v_index(16 * t + 4 * g4, pos, 128);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const uint32_t h0 = rne16(v[e]);
+                        const float vq = kv_round(v[e], a.kvq >> 4);
+                        const uint32_t h0 = rne16(vq);
                         vr[e * 8] = (bf16_t)h0;
-                        if (a.kvp == 2) vr[e * 8 + plane] = (bf16_t)rne16(v[e] - up16(h0));
+                        if (a.kvp == 2) vr[e * 8 + plane] = (bf16_t)rne16(vq - up16(h0));
                     }
                 }
             } else if (EPI == EPI_LMHEAD) {

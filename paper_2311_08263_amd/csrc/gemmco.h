@@ -15,12 +15,13 @@ struct GemmCoArgs {
     int32_t ldo;
     const int32_t* n_state; const float* cosT; const float* sinT;
     bf16_t* kc; bf16_t* vc;
-    int32_t layer, H, Hkv, B, S, Wn, kvp;
+    int32_t layer, H, Hkv, B, S, Wn, kvp, kvq;
     float* amax_val; int32_t* amax_idx;   // LM head: winners per workgroup [workgroups][16 or 32 rows]
     int32_t ks;            // workgroups per column owner, each taking 1/ks of K (1..8; 1 for the LM head)
     float* xpart;          // ks > 1: partial tiles [workgroup][8 or 16 (more than 8 output tiles)][64 lanes][4], then each
                            // workgroup's share of the row sums of squares [workgroup][16 or 32]
     int32_t* xcnt;         // ks > 1: one arrival counter per owner, zero between launches
+    int32_t hi_only;       // precision study: the activations enter as plain bf16 (their lo halves dropped)
     int32_t rotate;        // walk the K batches in a per-wave rotated order (spreads the streams over the memory channels)
     int32_t single_buffer; // weights in flight per wave: 1 = one batch, 0 = two batches, 2 = the wave's whole K slice requested up front
                            // (QKV and residual GEMMs, up to 16 rows, slices of at most 16 k-tiles per wave; else rejected)

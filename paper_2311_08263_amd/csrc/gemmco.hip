@@ -138,7 +138,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) pk_bf16_hilo(v[2 * e], v[2 * e + 1], h[e], l[e]);
             hi[mt].u = (u32x4_t){h[0], h[1], h[2], h[3]};
-            lo[mt].u = (u32x4_t){l[0], l[1], l[2], l[3]};
+            lo[mt].u = a.hi_only ? (u32x4_t){0u, 0u, 0u, 0u} : (u32x4_t){l[0], l[1], l[2], l[3]};
         }
 #pragma unroll
         for (int j = 0; j < NW; ++j) {
@@ -400,6 +400,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
                     const float other = __shfl_xor(vv[e], 32, 64);
                     const float c = rcos[f][e], s = rsin[f][e];
                     r[e] = g4 < 2 ? vv[e] * c - other * s : vv[e] * c + other * s;
+                    if (hh >= a.H) r[e] = kv_round(r[e], a.kvq & 15);
                 }
                 const int el = (g4 < 2 ? 0 : 64) + i0;          // element index within the head
                 if (ok) {
@@ -423,9 +424,10 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
                 bf16_t* vr = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + v_index(16 * t + 4 * g4, pos, 128);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const uint32_t h0 = rne16(vv[e]);
+                    const float vq = kv_round(vv[e], a.kvq >> 4);
+                    const uint32_t h0 = rne16(vq);
                     vr[e * 8] = (bf16_t)h0;
-                    if (a.kvp == 2) vr[e * 8 + plane] = (bf16_t)rne16(vv[e] - up16(h0));
+                    if (a.kvp == 2) vr[e * 8 + plane] = (bf16_t)rne16(vq - up16(h0));
                 }
             }
         } else if (EPI == EPI_LMHEAD) {
