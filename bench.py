@@ -313,6 +313,8 @@ def main():
     ap.add_argument("--plain", action="store_true", help="time the plain kernels instead of the MFMA path")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary measurements (streaming-read ceiling, isolated attention and LM head, perfect draft)")
+    ap.add_argument("--plan", default="", help="launch-plan values for the timed context, as option=value pairs separated by commas "
+                    "(FASTCOT_PLAN_* numbers of include/fastcot.h, e.g. 105=2 for two K slices per owner in the QKV GEMM)")
     ap.add_argument("--no-secondary-workloads", action="store_true",
                     help="skip the 13B batch-8 and 70B step measurements that follow the default workload")
     ap.add_argument("--window-sweep", action="store_true",
@@ -349,6 +351,9 @@ def main():
     ctx = fc.Context(cfg, packed)
     if args.plain:
         ctx.set_option(1, 1)
+    for pair in filter(None, args.plan.split(",")):
+        opt, val = pair.split("=")
+        ctx.set_option(int(opt), int(val))
     log(f"model resident after {time.time() - t0:.1f}s; max_seq {max_seq}")
     prompts = synthgen.prompts(B, P, shape.vocab)
     lens = [P] * B
@@ -494,7 +499,7 @@ def main():
         "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"llama2-{shape_name}-shaped random-init, batch {B}, prompt {P}, window {W}, "
                                f"{N} new tokens, greedy", "batch": B, "prompt": P, "window": W, "new_tokens": N,
-                   "kernels": "plain" if args.plain else "mfma"},
+                   "kernels": "plain" if args.plain else "mfma", **({"plan": args.plan} if args.plan else {})},
         "generate": {"tokens": int(out["len"].sum()), "steps": gen_steps, "wall_ms": round(gen_s * 1e3, 2),
                      "median_step_ms": round(float(np.median(gen_ms)), 4),
                      "p10_step_ms": round(float(np.percentile(gen_ms, 10)), 4),

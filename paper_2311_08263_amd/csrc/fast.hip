@@ -13,6 +13,9 @@ bool fc_fast_supported(const KernelDims& kd, int rows) {
            (kd.H * kd.Dh) % 256 == 0 && kd.S % 32 == 0 && kd.V % 16 == 0;
 }
 
+// inputs (K) of GEMM i: QKV, O, gate/up, down, LM head
+static int kin0(const KernelDims& kd, int i) { return i == 1 ? kd.H * kd.Dh : (i == 3 ? kd.F : kd.d); }
+
 void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     memset(p, 0, sizeof(*p));
     // at most 8 key splits: the last workgroup to arrive folds up to 8 partial results in one round of loads
@@ -39,7 +42,25 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     // bytes than weight bytes; K slices per owner cut that (measured at the 7B shape)
     if (kd.F >= 2 * kd.d && kd.F >= 4096 && p->nw[3] % 4 == 0 && p->nw[3] / 4 <= nts[3] && (nts[3] + p->nw[3] / 4 - 1) / (p->nw[3] / 4) <= 8) p->ks[3] = 4;
     p->co_single = 2;    // measured (7B and 70B shapes): down and LM head 2-4 % faster with two batches in flight, QKV and O slower
-    for (int i = 0; i < 5; ++i) { p->co_sb[0][i] = !(i == 3 || i == 4); p->co_sb[1][i] = i < 2; p->co_rot[0][i] = p->co_rot[1][i] = i >= 2; }
+    for (int i = 0; i < 5; ++i) { p->co_sb[0][i] = !(i == 3 || i == 4); p->co_sb[1][i] = 0; p->co_rot[0][i] = i >= 2; p->co_rot[1][i] = 1; }
+    // Measured per shape (steps of up to 16 rows, every combination of K slices per owner x batch order x batches
+    // in flight timed on the shape's own matrices, the fastest recorded here): {K slices, rotated order, batches in
+    // flight} for QKV, O, gate/up, down, LM head.  Everything that fixes the order of the fp32 additions comes from
+    // this table or the rules above, never from a timing at run time, so that every process computes the same bits.
+    struct Row { int d, F, H, Hkv; int ks[5], rot[5], sb[5]; };
+    static const Row table[] = {
+        {4096, 11008, 32, 32, {1, 2, 1, 8, 1}, {0, 0, 1, 1, 1}, {2, 2, 1, 0, 0}},      // Llama-2-7B shape
+        {5120, 13824, 40, 40, {1, 4, 1, 4, 1}, {1, 0, 1, 1, 1}, {0, 1, 0, 1, 0}},      // 13B shape
+        {8192, 28672, 64, 8, {2, 4, 1, 4, 1}, {1, 1, 0, 1, 1}, {1, 1, 0, 0, 0}},       // 70B shape
+    };
+    for (const Row& r : table) {
+        if (r.d != kd.d || r.F != kd.F || r.H != kd.H || r.Hkv != kd.Hkv || kd.Dh != 128) continue;
+        for (int i = 0; i < 5; ++i) {
+            const int G = p->nw[i], ks = r.ks[i], own = G / ks;
+            if (G % ks == 0 && own >= 1 && own <= nts[i] && (nts[i] + own - 1) / own <= 12 && kin0(kd, i) / 256 >= ks) p->ks[i] = ks;
+            p->co_rot[0][i] = r.rot[i]; p->co_sb[0][i] = r.sb[i];
+        }
+    }
     // 17..32 rows (two row tiles per workgroup, up to 16 output tiles): the same grids where the partial tiles
     // fit the LDS, K slices halved until they divide the grid
     const int kin[5] = {kd.d, kd.H * kd.Dh, kd.d, kd.F, kd.d};

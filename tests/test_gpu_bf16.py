@@ -35,7 +35,9 @@ def setup(fc, shape, B, S, W):
 
 @pytest.mark.parametrize("shape,B,W,P", [(SMALL, 1, 16, 45), (SMALL, 2, 16, 33), (SMALL_MHA, 1, 8, 20),
                                          (SMALL, 1, 32, 70), (SMALL_MHA, 3, 5, 12), (SMALL, 4, 32, 40),
-                                         (SMALL_MHA, 3, 16, 30), (SMALL, 1, 64, 75), (SMALL_MHA, 2, 40, 300)])
+                                         (SMALL_MHA, 3, 16, 30), (SMALL, 1, 64, 75), (SMALL_MHA, 2, 40, 300),
+                                         # the largest window of the window sweep, and a prompt of 4k tokens
+                                         (SMALL, 1, 128, 140), (SMALL_MHA, 2, 128, 200), (SMALL_MHA, 1, 16, 4099)])
 def test_follow_mode_small_models(fc, shape, B, W, P):
     say(f"bf16 follow shape d={shape.d_model} B={B} W={W} P={P}")
     N = 48
