@@ -952,7 +952,7 @@ extern "C" int fastcot_debug_read(fastcot_ctx* c, int32_t what, float* host, siz
         case 1: off = c->wm.qkv; cap = M * c->kd.qkvN; break;
         case 2: off = c->wm.att; cap = M * c->kd.H * c->kd.Dh; break;
         case 3: off = c->wm.h; cap = M * c->kd.F; break;
-        case 4: off = c->wm.logits; cap = M * c->kd.V; break;     // plain-path logits buffer (trace data in FC_TRACE builds)
+        case 4: off = c->wm.logits; cap = M * c->kd.V; break;     // plain-path logits buffer
         default: return fail(c, FASTCOT_EINVAL, "unknown buffer%s");
     }
     if (count > cap) return fail(c, FASTCOT_ECAPACITY, "count exceeds the buffer%s");

@@ -31,16 +31,6 @@ __device__ inline void split8(const float* v, Frag& hi, Frag& lo) {
     lo.u = (u32x4_t){l[0], l[1], l[2], l[3]};
 }
 
-#ifdef FC_TRACE
-// timing build only: wall-clock stamps (10 ns units) per wave at a few points of the kernel
-__device__ unsigned long long g_atrace[512 * 4 * 8];
-#define ASTAMP(i) do { if (lane == 0) { const int wgi_ = blockIdx.y * gridDim.x + blockIdx.x; if (wgi_ < 512) { unsigned long long* t_ = g_atrace + ((size_t)wgi_ * 4 + wv) * 8; if ((i) == 7) { for (int z_ = 0; z_ < 8; ++z_) t_[z_] = 0; } else t_[i] = wall_clock64(); } } } while (0)
-extern "C" int fastcot_attn_trace_read(void* host, size_t bytes) {
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_atrace), bytes < sizeof(g_atrace) ? bytes : sizeof(g_atrace)) == hipSuccess ? 0 : -4;
-}
-#else
-#define ASTAMP(i) do { } while (0)
-#endif
 #define NEG_BIG (-1.0e30f)
 #define PART_FLOATS (8 * 64 * 4 + 128)   // per (bh, split, qt): O^T tiles, then m[64], l[64] per lane
 
@@ -49,7 +39,6 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
     extern __shared__ float lds[];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int lm = lane & 15, g = lane >> 4;
-    ASTAMP(7); ASTAMP(0);
     // a window of more rows than a workgroup takes (16 per query tile) is cut into sub-windows: sub-window `sub` of a sequence is a
     // unit of its own whose rows see the committed positions plus the window rows up to their own (the
     // K/V of all window rows are already in the cache when this kernel starts)
@@ -205,7 +194,6 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
             }
         }
     }
-    ASTAMP(1);
     // row sums over the 4 lanes of a row
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
@@ -246,7 +234,6 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
         mw[qt] = m; lw[qt] = l;
     }
 
-    ASTAMP(2);
     if (nsp > 1) {
         // ---- key splits: partial tiles go to memory with agent-scope stores; the last workgroup to
         // arrive reads all of them back -- every load of the merge is in flight at once (each wave its
@@ -266,12 +253,10 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
             }
         }
         wait_vmem_done();
-        ASTAMP(3);
         __syncthreads();                                   // all four waves' stores have completed
         int* flag = (int*)(lds + 4 * QT * PART_FLOATS);
         if (tid == 0) *flag = arrive_agent(a.cnt + bh);
         __syncthreads();
-        ASTAMP(4);
         if (*flag != nsp - 1) return;
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
@@ -310,7 +295,6 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
             lw[qt] = l;
         }
         if (tid == 0) st_agent_i32(a.cnt + bh, 0);
-        ASTAMP(5);
     }
     // out[row][h*128 + 16*dt + 4*g + r] = O / l, this wave's tiles dt = 2*wv, 2*wv + 1
 #pragma unroll
@@ -340,7 +324,6 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
             }
         }
     }
-    ASTAMP(6);
 }
 
 size_t fc_attn16_part_bytes(int BH, int nsplit, int W) {      // covers both unit sizes

@@ -27,18 +27,6 @@ __device__ inline uint32_t rne16(float f) {
 }
 __device__ inline float up16(uint32_t b) { return __uint_as_float(b << 16); }
 
-#ifdef FC_TRACE
-// timing build only: per wave, wall-clock stamps (10 ns units) at a few points of the kernel selected by FC_TRACE_EPI
-__device__ unsigned long long g_trace[512 * 8 * 8];
-#define STAMP(i) do { if (EPI == FC_TRACE_EPI && lane == 0 && blockIdx.x < 512 && (FC_TRACE_K == 0 || a.K == FC_TRACE_K)) { unsigned long long* t_ = g_trace + ((size_t)blockIdx.x * 8 + w) * 8; if ((i) == 0) { for (int z_ = 1; z_ < 8; ++z_) t_[z_] = 0; } t_[i] = wall_clock64(); } } while (0)
-extern "C" int fastcot_trace_read(void* host, size_t bytes) {
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), bytes < sizeof(g_trace) ? bytes : sizeof(g_trace)) == hipSuccess ? 0 : -4;
-}
-#define STAMP_FIRST_DATA(ib) do { if (EPI == FC_TRACE_EPI && (ib) == 0 && (FC_TRACE_K == 0 || a.K == FC_TRACE_K)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); STAMP(1); } } while (0)
-#else
-#define STAMP(i) do { } while (0)
-#define STAMP_FIRST_DATA(ib) do { } while (0)
-#endif
 
 // One batch = KB k-tiles: the wave's weight tiles for its n-tiles and its activation octets.
 template <int NW, int KB, int MT> struct Batch {
@@ -61,7 +49,6 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     float* lds_gain = (float*)(lds_ami + 8 * 16);       // [K] (only with a norm in front)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int lm = lane & 15, g4 = lane >> 4;
-    STAMP(0);
     // workgroup i owns n-tiles [i*NT/G, (i+1)*NT/G): at most NW of them
     const int ks = (EPI != EPI_LMHEAD && a.ks > 1) ? a.ks : 1;
     const int G = gridDim.x / ks, owner = blockIdx.x / ks, slice = blockIdx.x % ks;
@@ -242,7 +229,6 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
             __syncthreads();
         }
         for (int ib = 0; ib < nb; ib += 2) {
-            STAMP_FIRST_DATA(ib);
             compute(A, ib);
             load(A, ib + 2);
             __builtin_amdgcn_sched_barrier(0);          // the loads stay here, ahead of the other batch's arithmetic
@@ -256,14 +242,12 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
             __syncthreads();
         }
         for (int ib = 0; ib < nb; ++ib) {
-            STAMP_FIRST_DATA(ib);
             compute(A, ib);
             load(A, ib + 1);
         }
     }
     }
 
-    STAMP(2);
     // the eight K slices meet in LDS, in two rounds so that four partial sets (4 x TW KB) are enough: waves
     // 4..7 publish, waves 0..3 add those to their own and publish the sums
 #pragma unroll
@@ -294,7 +278,6 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     }
     __syncthreads();
 
-    STAMP(3);
     // wave w finishes tiles w and (with more than 8 tiles) w + 8: lane holds row tm*16 + lm, columns
     // nt*16 + 4*g4 + r.  MT divides 8, so both tiles of a wave belong to the same row tile tm.
     const int tm = w % MT;
@@ -437,7 +420,6 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
             for (int r = 0; r < 4; ++r) if (vv[r] > best || (vv[r] == best && n0 + r < bi)) { best = vv[r]; bi = n0 + r; }
         }
     }
-    STAMP(4);
     if (EPI == EPI_LMHEAD) {
 #pragma unroll
         for (int o = 16; o <= 32; o <<= 1) {

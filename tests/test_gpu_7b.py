@@ -42,19 +42,28 @@ def env():
 
 @pytest.mark.timeout(900)
 def test_7b_follow_mode_full_size(env):
+    """The oracle follows three full-size steps whose draft is the model's own continuation for the first 32
+    tokens (taken from a run of the GPU alone) and random ids after that: two steps that verify and accept many
+    tokens at once (Eq. 5 with K up to 15, the commit of 16 K/V rows, the shift by 16) and one that accepts a single
+    token, all with logits, argmax and the integer path checked against the oracle."""
     fc, cfg, packed, om = env
     P, W, N = 256, 16, 256
     ctx = fc.Context(cfg, packed)
     prompts = synthgen.prompts(1, P, SHAPE.vocab)
     buf = synthgen.buffer_init(1, N + 2 * W, SHAPE.vocab)
-    say("7b: prefill")
+    say("7b: the continuation (GPU alone, 32 tokens)")
     ctx.prefill(prompts, [P], buf)
+    first = ctx.generate(2 * W)["ids"][0]
+    draft = buf.copy()
+    draft[0, :2 * W] = first
+    say("7b: prefill with that draft")
+    ctx.prefill(prompts, [P], draft)
     t0 = time.time()
     r = follow_steps(ctx, om, prompts, [P], 3, 2e-2)
     print(f"7b follow: max |dlogit| {r['max_err']:.3e} over {r['rows']} rows, {r['low_margin_rows']} low-margin, "
           f"K={r['K']}, oracle time {time.time() - t0:.1f}s")
-    # continue to the end on the GPU alone: accepted stream must keep its invariants
-    say("7b: generate rest")
+    assert max(r["K"]) >= 8, "no step of the followed prefix verified a long draft"
+    assert min(r["K"]) <= 2, "no step of the followed prefix rejected its draft early"
     st = ctx.state()
     assert st["n"][0] == P - 1 + st["g"][0]
 
