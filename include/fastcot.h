@@ -175,8 +175,10 @@ int fastcot_debug_logits(fastcot_ctx* ctx, float* d_logits);
  * FASTCOT_OPT_GRAPH = 1 (default) replays a captured HIP graph per step; 0 launches kernels one by one.  A
  * context on the default (NULL) stream always launches one by one, since that stream cannot be captured.
  * FASTCOT_OPT_KV_PLANES (bf16 models): 2 (default) keeps every cached K/V value as a bf16 hi + bf16 lo pair
- * (4 bytes, ~16 mantissa bits); 1 keeps the hi plane only (2 bytes, plain bf16).  Changing it invalidates the
- * sequences: call fastcot_prefill again.
+ * (4 bytes, ~16 mantissa bits); 1 keeps the hi plane only (2 bytes, plain bf16); 3 keeps the hi plane and one
+ * byte of residual (3 bytes: the upper 24 bits of the fp32 value, which the attention kernel expands in
+ * registers; faster than the pair only for steps of at most 16 rows per sequence over long contexts without
+ * grouped-query heads).  Changing it invalidates the sequences: call fastcot_prefill again.
  * FASTCOT_OPT_COMPACT = 1 (default): whenever fastcot_generate finds finished sequences at one of its checks,
  * they trade slots (state and K/V cache) with unfinished ones so that the following steps run only the
  * unfinished sequences' rows; the order is restored before it returns.  0: finished sequences keep their rows.

@@ -129,7 +129,7 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
         size_t cur = 0;
         auto take = [&](size_t bytes) { size_t o = cur; cur = FC_ALIGN(cur + bytes); return o; };
         const size_t M = (size_t)k.M;
-        size_t cache = (size_t)k.L * k.B * k.Hkv * k.kvp * k.S * k.Dh * esz;
+        size_t cache = (size_t)k.L * k.B * k.Hkv * kv_alloc_planes(k.kvp) * k.S * k.Dh * esz;
         wm->kc = take(cache); wm->vc = take(cache);
         wm->rope_cos = take((size_t)k.S * (k.Dh / 2) * 4); wm->rope_sin = take((size_t)k.S * (k.Dh / 2) * 4);
         wm->x = take(M * d * 4); wm->nx = take(M * d * 4); wm->qkv = take(M * k.qkvN * 4); wm->qrot = take(M * qd * 4);
@@ -327,7 +327,7 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
     } else if (option == FASTCOT_OPT_GRAPH) c->opt_graph = value != 0;
     else if (option == FASTCOT_OPT_DEBUG_STAGES) c->dbg_stop = value;
     else if (option == FASTCOT_OPT_KV_PLANES) {
-        if (c->cfg.dtype != FASTCOT_BF16 || (value != 1 && value != 2)) return fail(c, FASTCOT_EINVAL, "KV planes: 1 or 2, bf16 models only%s");
+        if (c->cfg.dtype != FASTCOT_BF16 || value < 1 || value > 3) return fail(c, FASTCOT_EINVAL, "KV planes: 1, 2 or 3, bf16 models only%s");
         c->kd.kvp = value; c->prefilled = 0;      // the cache layout changes: a new prefill is required
     } else if (option == FASTCOT_OPT_KV_EMULATE) {
         if (c->cfg.dtype != FASTCOT_BF16 || value < 0 || (value & 15) > 3 || (value >> 4) > 3) return fail(c, FASTCOT_EINVAL, "KV format emulation: K mode + 16 * V mode, modes 0..3, bf16 models only%s");
@@ -493,7 +493,7 @@ static int prefill_passes(fastcot_ctx* c, int B, int maxlen) {
 // two sequences trade slots: state rows and K/V cache
 static hipError_t trade_slots(fastcot_ctx* c, int b1, int b2) {
     const KernelDims& kd = c->kd;
-    const size_t seq_bytes = (size_t)kd.Hkv * kd.kvp * kd.S * kd.Dh * kd.esz;
+    const size_t seq_bytes = (size_t)kd.Hkv * kv_alloc_planes(kd.kvp) * kd.S * kd.Dh * kd.esz;
     return fc_swap_sequences(state_ptr(c), c->wm.st, b1, b2, kd.W, kd.S, c->ws + c->wm.kc, c->ws + c->wm.vc, seq_bytes, kd.L,
                              (size_t)kd.B * seq_bytes, c->st);
 }

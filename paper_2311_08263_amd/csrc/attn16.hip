@@ -21,6 +21,7 @@
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2_t;
 union Frag { u32x4_t u; bf16x8_t v; };
 
 __device__ inline void split8(const float* v, Frag& hi, Frag& lo) {
@@ -34,6 +35,25 @@ __device__ inline void split8(const float* v, Frag& hi, Frag& lo) {
 #define NEG_BIG (-1.0e30f)
 #define PART_FLOATS (8 * 64 * 4 + 128)   // per (bh, split, qt): O^T tiles, then m[64], l[64] per lane
 
+// the bf16 lo operand of eight cached values kept as bf16 hi (h, four words) + 8-bit residual (two words of bytes):
+// value - hi = byte * 2^-15 * 2^(exponent of hi), exact in bf16
+__device__ inline void expand_lo8(const u32x4_t& h, uint32_t b0, uint32_t b1, Frag& lo) {
+    uint32_t o[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t w = h[p], bw = p < 2 ? b0 : b1;
+        // scale of the residual's unit: sign and exponent of hi, times 2^-15 (a hi of zero or below the normal
+        // range has exponent field 0: its residual is dropped, an error below 2^-126)
+        const float s0 = __uint_as_float((w << 16) & 0xFF800000u) * 3.0517578125e-05f;
+        const float s1 = __uint_as_float(w & 0xFF800000u) * 3.0517578125e-05f;
+        const float d0 = (float)((bw >> (16 * (p & 1))) & 0xFFu) * s0;
+        const float d1 = (float)((bw >> (16 * (p & 1) + 8)) & 0xFFu) * s1;
+        o[p] = pk_bf16(d0, d1);
+    }
+    lo.u = (u32x4_t){o[0], o[1], o[2], o[3]};
+}
+
+// KVP: 1 = one bf16 plane, 2 = bf16 hi + bf16 lo planes, 3 = bf16 hi plane + a plane of 8-bit residuals
 template <int QT, int KVP>
 __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
     extern __shared__ float lds[];
@@ -64,8 +84,9 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
     const int blk0 = (int)(((unsigned)sp * (unsigned)NB) / (unsigned)nsp);
     const int blk1 = (int)(((unsigned)(sp + 1) * (unsigned)NB) / (unsigned)nsp);
     const size_t plane = (size_t)a.S * 128;
-    const bf16_t* kbase = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + kvh) * KVP) * plane;
-    const bf16_t* vbase = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kvh) * KVP) * plane;
+    constexpr int NPL = KVP == 1 ? 1 : 2;                   // planes of S * 128 elements a block occupies; register sets
+    const bf16_t* kbase = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + kvh) * NPL) * plane;
+    const bf16_t* vbase = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kvh) * NPL) * plane;
 
     // Q as B operand: lane (row lm, dh 32*g + 8*s + e), hi and lo
     Frag qh[QT][4], ql[QT][4];
@@ -93,32 +114,54 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
     const float scale = 0.08838834764831845f;   // 1/sqrt(128)
 
     // one 32-key block: K tiles and V^T tiles of block `blk` into registers
-    struct KV { Frag kf[KVP][2][4], vf[KVP][8]; };
+    struct KV { Frag kf[NPL][2][4], vf[NPL][8]; };
     auto load = [&](KV& r, int blk_want) {
         const int blk = blk_want < NB ? blk_want : NB - 1;       // past the end: a valid block, never used
-        Frag (&kf)[KVP][2][4] = r.kf; Frag (&vf)[KVP][8] = r.vf;
+        Frag (&kf)[NPL][2][4] = r.kf; Frag (&vf)[NPL][8] = r.vf;
         // K tiles (A operand): tile t row r=lm <-> key 32*blk + 8*(lm/4) + 4*t + lm%4 ; dh 32*g + 8*s..
         // (the cache stores each block as these eight fragments, one contiguous kilobyte each; the loads are
         // non-temporal: K and V are read once per step, and letting them allocate in L2 cost 40% at batch 8)
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < 2; ++t) {
+            const u32x4_t* kp = (const u32x4_t*)(kbase + (size_t)blk * 4096) + lane;
 #pragma unroll
-            for (int pl = 0; pl < KVP; ++pl) {
-                const u32x4_t* kp = (const u32x4_t*)(kbase + pl * plane + (size_t)blk * 4096) + lane;
+            for (int s = 0; s < 4; ++s) kf[0][t][s].u = __builtin_nontemporal_load(kp + (t * 4 + s) * 64);
+            if (KVP == 2) {
+                const u32x4_t* kl = (const u32x4_t*)(kbase + plane + (size_t)blk * 4096) + lane;
 #pragma unroll
-                for (int s = 0; s < 4; ++s) kf[pl][t][s].u = __builtin_nontemporal_load(kp + (t * 4 + s) * 64);
+                for (int s = 0; s < 4; ++s) kf[NPL - 1][t][s].u = __builtin_nontemporal_load(kl + (t * 4 + s) * 64);
+            } else if (KVP == 3) {      // eight residual bytes per lane and fragment; expanded in compute()
+                const u32x2_t* kl = (const u32x2_t*)((const uint8_t*)(kbase + plane) + (size_t)blk * 4096) + lane;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const u32x2_t bw = __builtin_nontemporal_load(kl + (t * 4 + s) * 64);
+                    kf[NPL - 1][t][s].u = (u32x4_t){bw[0], bw[1], 0u, 0u};
+                }
             }
+        }
         // V^T tiles (A operand): row 16*dt + lm, keys kb + 8*g .. +7
         // (stored as eight fragments per block as well)
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
-#pragma unroll
-            for (int pl = 0; pl < KVP; ++pl)
-                vf[pl][dt].u = __builtin_nontemporal_load((const u32x4_t*)(vbase + pl * plane + (size_t)blk * 4096) + dt * 64 + lane);
+        for (int dt = 0; dt < 8; ++dt) {
+            vf[0][dt].u = __builtin_nontemporal_load((const u32x4_t*)(vbase + (size_t)blk * 4096) + dt * 64 + lane);
+            if (KVP == 2) vf[NPL - 1][dt].u = __builtin_nontemporal_load((const u32x4_t*)(vbase + plane + (size_t)blk * 4096) + dt * 64 + lane);
+            else if (KVP == 3) {
+                const u32x2_t bw = __builtin_nontemporal_load((const u32x2_t*)((const uint8_t*)(vbase + plane) + (size_t)blk * 4096) + dt * 64 + lane);
+                vf[NPL - 1][dt].u = (u32x4_t){bw[0], bw[1], 0u, 0u};
+            }
+        }
     };
-    auto compute = [&](const KV& r, int blk) {
+    auto compute = [&](KV& r, int blk) {
         const int kb = blk << 5;
-        const Frag (&kf)[KVP][2][4] = r.kf; const Frag (&vf)[KVP][8] = r.vf;
+        if (KVP == 3) {          // the residual bytes become bf16 lo operands
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int s = 0; s < 4; ++s) { const u32x4_t bw = r.kf[NPL - 1][t][s].u; expand_lo8(r.kf[0][t][s].u, bw[0], bw[1], r.kf[NPL - 1][t][s]); }
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) { const u32x4_t bw = r.vf[NPL - 1][dt].u; expand_lo8(r.vf[0][dt].u, bw[0], bw[1], r.vf[NPL - 1][dt]); }
+        }
+        const Frag (&kf)[NPL][2][4] = r.kf; const Frag (&vf)[NPL][8] = r.vf;
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
             f32x4_t sc[2];
@@ -129,8 +172,8 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
                 for (int s = 0; s < 4; ++s) {
                     sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][t][s].v, qh[qt][s].v, sc[t], 0, 0, 0);
                     sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][t][s].v, ql[qt][s].v, sc[t], 0, 0, 0);
-                    if (KVP == 2)   // lo x lo is below fp32 resolution and is dropped
-                        sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[KVP - 1][t][s].v, qh[qt][s].v, sc[t], 0, 0, 0);
+                    if (KVP >= 2)   // lo x lo is below fp32 resolution and is dropped
+                        sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[NPL - 1][t][s].v, qh[qt][s].v, sc[t], 0, 0, 0);
                 }
             }
             // lane: row j = qt*16 + lm, keys kb + 8*g + e  (e = 4*t + r)
@@ -166,8 +209,8 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
                 acc[qt][dt] *= alpha;
                 acc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[0][dt].v, ph.v, acc[qt][dt], 0, 0, 0);
                 acc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[0][dt].v, pl.v, acc[qt][dt], 0, 0, 0);
-                if (KVP == 2)
-                    acc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[KVP - 1][dt].v, ph.v, acc[qt][dt], 0, 0, 0);
+                if (KVP >= 2)
+                    acc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[NPL - 1][dt].v, ph.v, acc[qt][dt], 0, 0, 0);
             }
         }
     };
@@ -341,6 +384,7 @@ hipError_t fc_attn16(const AttnArgs& a, int Bact, int nsplit, hipStream_t st) {
     if (!lds_ok) {
         hipError_t e = hipFuncSetAttribute((const void*)k_attn16<2, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l2);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_attn16<2, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l2);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_attn16<2, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l2);
         if (e != hipSuccess) return e;
         lds_ok = true;
     }
@@ -350,6 +394,9 @@ hipError_t fc_attn16(const AttnArgs& a, int Bact, int nsplit, hipStream_t st) {
     } else if (a.kvp == 1) {
         if (QT == 2) k_attn16<2, 1><<<grid, 256, l2, st>>>(a);
         else k_attn16<1, 1><<<grid, 256, l1, st>>>(a);
+    } else if (a.kvp == 3) {
+        if (QT == 2) k_attn16<2, 3><<<grid, 256, l2, st>>>(a);
+        else k_attn16<1, 3><<<grid, 256, l1, st>>>(a);
     } else return hipErrorInvalidValue;
     return hipGetLastError();
 }

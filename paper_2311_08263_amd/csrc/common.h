@@ -31,6 +31,19 @@ __device__ inline void pk_bf16_hilo(float a, float b, uint32_t& hi, uint32_t& lo
     lo = pk_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
 }
 
+// The 3-byte cache format (kvp == 3): a value is rounded to the upper 24 bits of its fp32 pattern (to nearest
+// even); the upper 16 bits go to the hi plane (a bf16, truncated, not rounded), the next 8 to a plane of bytes.
+// hi and value - hi are both exact bf16 numbers, so the attention kernel feeds them to the matrix cores as it
+// feeds the hi + lo pair.
+__host__ __device__ inline void kv24_split(float v, uint32_t& hi16, uint32_t& lo8) {
+    union { uint32_t u; float f; } x; x.f = v;
+    const uint32_t u = x.u + 0x7Fu + ((x.u >> 8) & 1u);
+    hi16 = u >> 16; lo8 = (u >> 8) & 0xFFu;
+}
+__host__ __device__ inline float kv24_join(uint32_t hi16, uint32_t lo8) {
+    union { uint32_t u; float f; } x; x.u = (hi16 << 16) | (lo8 << 8); return x.f;
+}
+
 // Precision study of the K/V cache: what a cached value would be after a round trip through a narrower
 // storage format (0 as computed, 1 bf16, 2 fp16, 3 the upper 24 bits of fp32), round to nearest even.  The
 // value is then stored in the hi + lo planes as usual (which hold any of these exactly), so the effect of a
@@ -115,7 +128,8 @@ struct KernelDims {    // model + capacities as the kernels need them
     int32_t qkvN;      // (H + 2 Hkv) * Dh
     float eps;
     int32_t esz;       // bytes per weight / cache element
-    int32_t kvp;       // planes per cached value: bf16 models keep hi (+ lo) bf16 planes, fp32 models one fp32 plane
+    int32_t kvp;       // cached value: 1 = one plane (fp32 models: fp32; bf16 models: plain bf16), 2 = bf16 hi + bf16 lo planes,
+                       // 3 = bf16 hi plane + a plane of 8-bit residuals (kv24_split), kept in the space of two planes
     int32_t actq;      // precision study: bit g set = GEMM g (QKV, O, gate/up, down, LM head) takes its activations as plain bf16
     int32_t kvq;       // precision study: kv_round mode of K (bits 0..3) and of V (bits 4..7) before a value is cached; 0 = off
 };
@@ -130,8 +144,9 @@ struct KernelDims {    // model + capacities as the kernels need them
 //  V (transposed): Dh/16 fragments of 16 head elements; lane = dh % 16 + 16 * (position / 8), element
 //     position % 8.
 // S is a multiple of 32 and Dh a multiple of 32.
+__host__ __device__ inline int kv_alloc_planes(int kvp) { return kvp == 3 ? 2 : kvp; }   // planes of S * Dh elements a block occupies
 __host__ __device__ inline size_t kv_block(const KernelDims& kd, int layer, int b, int kh) {
-    return ((((size_t)layer * kd.B + b) * kd.Hkv + kh) * (size_t)kd.kvp) * (size_t)kd.S * kd.Dh;
+    return ((((size_t)layer * kd.B + b) * kd.Hkv + kh) * (size_t)kv_alloc_planes(kd.kvp)) * (size_t)kd.S * kd.Dh;
 }
 __host__ __device__ inline size_t k_index(int pos, int dh, int Dh) {
     const int kk = pos & 31, t = (kk >> 2) & 1, r = 4 * (kk >> 3) + (kk & 3);

@@ -389,28 +389,46 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
                 if (ok) {
                     if (hh < a.H) *(f32x4_t*)(a.out + (size_t)m * a.ldo + hh * 128 + el) = r;
                     else {
-                        bf16_t* kr = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + (hh - a.H)) * a.kvp) * plane + k_index(pos, el, 128);
+                        bf16_t* kb = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + (hh - a.H)) * kv_alloc_planes(a.kvp)) * plane;
+                        const size_t ki = k_index(pos, el, 128);
+                        bf16_t* kr = kb + ki;
                         uint32_t h[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) h[e] = rne16(r[e]);
-                        *(uint2*)kr = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-                        if (a.kvp == 2) {
+                        if (a.kvp == 3) {
                             uint32_t l[4];
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) l[e] = rne16(r[e] - up16(h[e]));
-                            *(uint2*)(kr + plane) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+                            for (int e = 0; e < 4; ++e) kv24_split(r[e], h[e], l[e]);
+                            *(uint2*)kr = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                            *(uint32_t*)((uint8_t*)(kb + plane) + ki) = l[0] | (l[1] << 8) | (l[2] << 16) | (l[3] << 24);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) h[e] = rne16(r[e]);
+                            *(uint2*)kr = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                            if (a.kvp == 2) {
+                                uint32_t l[4];
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) l[e] = rne16(r[e] - up16(h[e]));
+                                *(uint2*)(kr + plane) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+                            }
                         }
                     }
                 }
             } else if (ok) {
                 const int kh = hh - a.H - a.Hkv;
-                bf16_t* vr = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kh) * a.kvp) * plane + v_index(16 * t + 4 * g4, pos, 128);
+                bf16_t* vb = a.vc + ((((size_t)a.layer * a.B + b) * a.Hkv + kh) * kv_alloc_planes(a.kvp)) * plane;
+                const size_t vi = v_index(16 * t + 4 * g4, pos, 128);
+                bf16_t* vr = vb + vi;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float vq = kv_round(vv[e], a.kvq >> 4);
-                    const uint32_t h0 = rne16(vq);
-                    vr[e * 8] = (bf16_t)h0;
-                    if (a.kvp == 2) vr[e * 8 + plane] = (bf16_t)rne16(vq - up16(h0));
+                    if (a.kvp == 3) {
+                        uint32_t h0, l0; kv24_split(vq, h0, l0);
+                        vr[e * 8] = (bf16_t)h0;
+                        ((uint8_t*)(vb + plane))[vi + e * 8] = (uint8_t)l0;
+                    } else {
+                        const uint32_t h0 = rne16(vq);
+                        vr[e * 8] = (bf16_t)h0;
+                        if (a.kvp == 2) vr[e * 8 + plane] = (bf16_t)rne16(vq - up16(h0));
+                    }
                 }
             }
         } else if (EPI == EPI_LMHEAD) {

@@ -9,15 +9,28 @@ template <int DT> __device__ inline float wat(const void* W, size_t i) {
     if (DT == FASTCOT_F32) return ((const float*)W)[i];
     return bf16_to_f32(((const bf16_t*)W)[i]);
 }
-// cached value: fp32 models one fp32 plane; bf16 models a bf16 hi plane plus (kvp == 2) a bf16 lo plane
+// cached value: fp32 models one fp32 plane; bf16 models a bf16 hi plane plus (kvp == 2) a bf16 lo plane or
+// (kvp == 3) a plane of 8-bit residuals; i is the element index of plane 0's entry, `plane` the elements per plane
 template <int DT> __device__ inline void kvstore(void* C, size_t i, size_t plane, int kvp, float v) {
     if (DT == FASTCOT_F32) { ((float*)C)[i] = v; return; }
+    if (kvp == 3) {
+        // (the block's base is part of i: the byte plane of a block starts one plane after its hi plane)
+        uint32_t h, l; kv24_split(v, h, l);
+        ((bf16_t*)C)[i] = (bf16_t)h;
+        const size_t blk = i / plane * plane;
+        ((uint8_t*)((bf16_t*)C + blk + plane))[i - blk] = (uint8_t)l;
+        return;
+    }
     bf16_t hi = f32_to_bf16(v);
     ((bf16_t*)C)[i] = hi;
     if (kvp == 2) ((bf16_t*)C)[i + plane] = f32_to_bf16(v - bf16_to_f32(hi));
 }
 template <int DT> __device__ inline float kvload(const void* C, size_t i, size_t plane, int kvp) {
     if (DT == FASTCOT_F32) return ((const float*)C)[i];
+    if (kvp == 3) {
+        const size_t blk = i / plane * plane;
+        return kv24_join(((const bf16_t*)C)[i], ((const uint8_t*)((const bf16_t*)C + blk + plane))[i - blk]);
+    }
     float v = bf16_to_f32(((const bf16_t*)C)[i]);
     if (kvp == 2) v += bf16_to_f32(((const bf16_t*)C)[i + plane]);
     return v;

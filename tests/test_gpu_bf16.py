@@ -52,6 +52,36 @@ def test_follow_mode_small_models(fc, shape, B, W, P):
     assert r["max_err"] < 2e-3          # far inside the bf16 bar thanks to hi/lo activations
 
 
+@pytest.mark.parametrize("shape,B,W,P,plain", [(SMALL, 1, 16, 45, 0), (SMALL, 4, 32, 40, 0), (SMALL_MHA, 2, 40, 300, 0),
+                                               (SMALL, 2, 24, 70, 0), (SMALL, 2, 8, 33, 1)])
+def test_three_byte_kv_cache(fc, shape, B, W, P, plain):
+    """FASTCOT_OPT_KV_PLANES = 3: cached K/V as bf16 hi + an 8-bit residual (the upper 24 bits of the fp32 value),
+    through the column-owner and the many-row QKV epilogues, the attention kernel's expansion of the residual bytes,
+    and the plain kernels; same bar as the pair cache."""
+    say(f"3-byte kv cache d={shape.d_model} B={B} W={W} P={P} plain={plain}")
+    N = 48
+    S = ((P + N + 2 * W + 31) // 32) * 32
+    ctx, om = setup(fc, shape, B, S, W)
+    ctx.set_option(fc.binding.OPT_KV_PLANES, 3)
+    if plain:
+        ctx.set_option(fc.binding.OPT_PLAIN_KERNELS, 1)
+    lens = [P - 3 * b for b in range(B)]
+    prompts = synthgen.prompts(B, P, shape.vocab, seed=23)
+    buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=24)
+    ctx.prefill(prompts, lens, buf)
+    r = follow_steps(ctx, om, prompts, lens, 5, TOL)
+    print(f"3-byte kv cache: max |dlogit| {r['max_err']:.3e} over {r['rows']} rows")
+    assert r["max_err"] < 2e-3
+    # finished sequences trading slots carry their residual planes with them
+    if B > 1 and not plain:
+        ctx.prefill(prompts, lens, buf)
+        a = ctx.generate(N, eos_id=int(om.greedy_ar(prompts[0, :lens[0]], 6)[-1]))
+        ctx.set_option(fc.binding.OPT_COMPACT, 0)
+        ctx.prefill(prompts, lens, buf)
+        b = ctx.generate(N, eos_id=int(om.greedy_ar(prompts[0, :lens[0]], 6)[-1]))
+        assert (a["ids"] == b["ids"]).all() and (a["len"] == b["len"]).all()
+
+
 @pytest.mark.parametrize("W", [16, 24])
 def test_without_autotune(fc, W):
     """The plan's defaults (no timing runs at prefill) pass the same bar as the measured plan."""
