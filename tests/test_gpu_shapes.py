@@ -13,6 +13,7 @@ pytestmark = pytest.mark.gpu
 
 S70 = synthgen.small_variant(synthgen.SHAPES["70b"], n_layers=2)
 S13 = synthgen.small_variant(synthgen.SHAPES["13b"], n_layers=2)
+S7 = synthgen.small_variant(synthgen.SHAPES["7b"], n_layers=2)      # gate/up: 1376 n-tiles, shared half tiles
 
 
 def build(fc, shape, B, S, W):
@@ -37,7 +38,8 @@ def build(fc, shape, B, S, W):
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("name,shape,B,W,P,steps", [("70b-shaped", S70, 1, 16, 41, 3), ("13b-shaped", S13, 1, 16, 37, 3),
                                                     ("13b-shaped batch 8 window 32", S13, 8, 32, 50, 2),
-                                                    ("13b-shaped window 32", S13, 1, 32, 45, 2), ("70b-shaped window 24", S70, 1, 24, 41, 2)])
+                                                    ("13b-shaped window 32", S13, 1, 32, 45, 2), ("70b-shaped window 24", S70, 1, 24, 41, 2),
+                                                    ("7b-shaped", S7, 1, 16, 39, 3), ("7b-shaped window 32", S7, 1, 32, 39, 2)])
 def test_layer_shapes_follow_mode(name, shape, B, W, P, steps):
     import paper_2311_08263_amd as fc
     say(f"{name}: B={B} W={W} P={P}")
