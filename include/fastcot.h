@@ -211,9 +211,13 @@ enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLAN
  * FASTCOT_PLAN_CO_SINGLE: 0 / 1 = two / one batch in flight for every GEMM, 2 (default) = per GEMM (PLAN_SB).
  * FASTCOT_PLAN_ATTN_SPLITS: key-range splits the attention launch provides (1..16).
  * FASTCOT_PLAN_ATTN_BLOCKS: key blocks of 32 positions per attention workgroup: of the launched splits,
- * ceil(blocks / value) work on a sequence, the rest exit. */
+ * ceil(blocks / value) work on a sequence, the rest exit.
+ * FASTCOT_PLAN_ATTN_MANY_ROWS: which passes use the attention kernel for many rows per sequence (workgroups of
+ * 128 rows that walk the keys once; prompt chunks): 0 none, 1 (default) passes of at least 64 rows per sequence
+ * whose launch gives at least half of the compute units a workgroup, 2 every pass of more than 32 rows. */
 enum { FASTCOT_PLAN_NW = 100, FASTCOT_PLAN_KS = 105, FASTCOT_PLAN_SB = 110, FASTCOT_PLAN_ROT = 115,
-       FASTCOT_PLAN_CO_SINGLE = 120, FASTCOT_PLAN_ATTN_SPLITS = 121, FASTCOT_PLAN_ATTN_BLOCKS = 122 };
+       FASTCOT_PLAN_CO_SINGLE = 120, FASTCOT_PLAN_ATTN_SPLITS = 121, FASTCOT_PLAN_ATTN_BLOCKS = 122,
+       FASTCOT_PLAN_ATTN_MANY_ROWS = 123 };
 int fastcot_set_option(fastcot_ctx* ctx, int32_t option, int32_t value);
 
 /* Debug: copies `count` floats of an activation buffer of the last forward to the host after

@@ -20,7 +20,7 @@ N_KINDS = 16
 
 T = {"emb": 0, "wlm": 1, "gf": 2, "wq": 3, "wk": 4, "wv": 5, "wo": 6, "wg": 7, "wu": 8, "wd": 9, "g1": 10, "g2": 11}
 OPT_PLAIN_KERNELS, OPT_GRAPH, OPT_KV_PLANES, OPT_COMPACT, OPT_AUTOTUNE, OPT_DEBUG_STAGES, OPT_KV_EMULATE, OPT_ACT_EMULATE = 1, 2, 3, 4, 5, 6, 7, 8
-PLAN_NW, PLAN_KS, PLAN_SB, PLAN_ROT, PLAN_CO_SINGLE, PLAN_ATTN_SPLITS, PLAN_ATTN_BLOCKS = 100, 105, 110, 115, 120, 121, 122
+PLAN_NW, PLAN_KS, PLAN_SB, PLAN_ROT, PLAN_CO_SINGLE, PLAN_ATTN_SPLITS, PLAN_ATTN_BLOCKS, PLAN_ATTN_MANY_ROWS = 100, 105, 110, 115, 120, 121, 122, 123
 _STATUS = {0: "OK", -1: "EINVAL", -2: "ESTATE", -3: "ECAPACITY", -4: "EHIP", -5: "ENOMEM"}
 
 

@@ -115,11 +115,11 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
     k.V = c->vocab; k.B = c->max_batch; k.S = (c->max_seq + 31) & ~31; k.W = c->window;
     k.qkvN = qd + 2 * kvd; k.eps = c->rms_eps; k.esz = (int)esz; k.kvp = c->dtype == FASTCOT_BF16 ? 2 : 1; k.kvq = 0; k.actq = 0;
     // prefill runs the same kernels over chunks of the prompt; where the matrix-core path covers the
-    // shape a chunk is up to 256 rows per sequence (at most 512 rows in all), else one window
+    // shape a chunk is up to 1024 rows per sequence (at most 1024 rows in all), else one window
     k.Wcap = k.W; k.M = k.B * k.W;
     if (fc_fast_supported(k, k.M)) {
-        int ch = 256;
-        while (ch > 32 && k.B * ch > 512) ch >>= 1;
+        int ch = 1024;
+        while (ch > 32 && k.B * ch > 1024) ch >>= 1;
         if (ch > k.S) ch = k.S;
         if (ch > k.Wcap) k.Wcap = ch;
     }
@@ -364,6 +364,9 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
     } else if (option == FASTCOT_PLAN_ATTN_BLOCKS) {
         if (value < 1 || value > 4096) return fail(c, FASTCOT_EINVAL, "attention blocks per workgroup out of range%s");
         c->plan.attn_bpw = value;
+    } else if (option == FASTCOT_PLAN_ATTN_MANY_ROWS) {
+        if (value < 0 || value > 2) return fail(c, FASTCOT_EINVAL, "many-row attention: 0 never, 1 by workgroup count, 2 for every pass of more than 32 rows%s");
+        c->plan.attn_many = value;
     }
     else return fail(c, FASTCOT_EINVAL, "unknown option%s");
     drop_graph(c);

@@ -21,4 +21,8 @@ struct AttnArgs {
 };
 
 size_t fc_attn16_part_bytes(int BH, int nsplit, int W);
+// many query rows per sequence (attnp.hip): workgroups of 128 rows x one head that walk the keys once; uses q, kc,
+// vc, layer, B, H, Hkv, S, W, kvp (1 or 2), n_state, out, ldo, ofrag of the argument block
+int fc_attnp_workgroups(int Bact, int H, int W);
+hipError_t fc_attnp(const AttnArgs& a, int Bact, hipStream_t st);
 hipError_t fc_attn16(const AttnArgs& a, int Bact, int nsplit, hipStream_t st);

@@ -8,6 +8,7 @@
 struct FastPlan {
     int32_t attn_splits;
     int32_t attn_bpw;  // key blocks of 32 per attention workgroup (decides at run time how many of the splits work)
+    int32_t attn_many; // many-row attention kernel (attnp.hip): 0 never, 1 where it gives half of the CUs a workgroup, 2 for every pass of more than 32 rows per sequence
     int32_t co_single; // column-owner GEMM: 1 = one weight batch in flight per wave, 0 = two, 2 = chosen per GEMM
     int32_t co_sb[2][5];   // the per-GEMM choice (1 = one batch, 0 = two, 2 = whole slice) for up to 16 rows [0] and 17..32 rows [1]: defaults
                            // from the 7B shape, replaced by fc_fast_tune's measurement on the actual shape

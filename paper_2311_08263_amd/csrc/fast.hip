@@ -29,6 +29,7 @@ void fc_fast_plan(const KernelDims& kd, FastPlan* p) {
     while (sp > 1 && kd.B * kd.H * sp > fc_num_cus()) --sp;
     p->attn_splits = sp < 1 ? 1 : sp;
     p->attn_bpw = 2;
+    p->attn_many = 1;
     // column-owner kernel: workgroups per GEMM (one per CU where the matrix allows)
     const int nts[5] = {kd.qkvN / 16, kd.d / 16, 2 * kd.F / 16, kd.d / 16, kd.V / 16};
     // measured on the 7B shape: one workgroup per CU
@@ -230,6 +231,13 @@ hipError_t fc_fast_forward(const FastArgs& a) {
             at.subrows = 16;
             while (attn_splits > 1 && a.Bact * kd.H * units16 * attn_splits > fc_num_cus()) --attn_splits;
         }
+        // passes with many rows per sequence (prompt chunks): one walk over the keys per 128 rows, where that
+        // still gives at least half of the CUs a workgroup
+        const bool many = a.plan->attn_many == 2 ? kd.W > 32
+                                                  : (a.plan->attn_many == 1 && kd.W >= 64 && 2 * fc_attnp_workgroups(a.Bact, kd.H, kd.W) >= fc_num_cus());
+        if (many && kd.kvp != 3)
+            FLAUNCH(KK_ATTN, fc_attnp(at, a.Bact, a.st));
+        else
         FLAUNCH(KK_ATTN, fc_attn16(at, a.Bact, attn_splits, a.st));
         DBG_STOP();
         gi = 1;

@@ -52,6 +52,42 @@ def test_follow_mode_small_models(fc, shape, B, W, P):
     assert r["max_err"] < 2e-3          # far inside the bf16 bar thanks to hi/lo activations
 
 
+@pytest.mark.parametrize("shape,B,W,P,planes", [(SMALL, 1, 128, 140, 2), (SMALL_MHA, 2, 128, 200, 2), (SMALL_MHA, 1, 16, 4099, 2),
+                                                (SMALL, 3, 40, 300, 2), (SMALL, 2, 64, 1100, 2), (SMALL, 2, 48, 333, 1)])
+def test_many_row_attention(fc, shape, B, W, P, planes):
+    """The attention kernel for passes of many rows per sequence (128-row workgroups that walk the keys once),
+    forced on for every pass of more than 32 rows: prompt chunks of up to 1024 rows with ragged lengths, steps with
+    windows of 40 to 128 rows (waves without rows, rows past the window), grouped K/V heads.  With the pair cache
+    the oracle follows; with the one-plane cache (plain bf16, outside the oracle's bar) the step kernel is the
+    reference, on identical cache contents."""
+    say(f"many-row attention d={shape.d_model} B={B} W={W} P={P} planes={planes}")
+    N = 48
+    S = ((P + N + 2 * W + 31) // 32) * 32
+    ctx, om = setup(fc, shape, B, S, W)
+    lens = [P - 37 * b for b in range(B)]
+    prompts = synthgen.prompts(B, P, shape.vocab, seed=25)
+    buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=26)
+    if planes == 2:
+        ctx.set_option(fc.binding.PLAN_ATTN_MANY_ROWS, 2)
+        ctx.prefill(prompts, lens, buf)
+        r = follow_steps(ctx, om, prompts, lens, 3, TOL)
+        print(f"many-row attention: max |dlogit| {r['max_err']:.3e} over {r['rows']} rows")
+        assert r["max_err"] < 2e-3
+    else:
+        logits = []
+        for many in (0, 2):
+            ctx.set_option(fc.binding.OPT_KV_PLANES, 1)
+            ctx.set_option(fc.binding.PLAN_ATTN_MANY_ROWS, many)
+            ctx.prefill(prompts, lens, buf)
+            dbg = ctx.debug_logits(True)
+            ctx.step()
+            logits.append(dbg.cpu().numpy().copy())
+        err = float(np.abs(logits[0] - logits[1]).max())
+        print(f"many-row attention, one plane: max |dlogit| against the step kernel {err:.3e}")
+        assert err < 2e-3
+    ctx.close()
+
+
 @pytest.mark.parametrize("shape,B,W,P,plain", [(SMALL, 1, 16, 45, 0), (SMALL, 4, 32, 40, 0), (SMALL_MHA, 2, 40, 300, 0),
                                                (SMALL, 2, 24, 70, 0), (SMALL, 2, 8, 33, 1)])
 def test_three_byte_kv_cache(fc, shape, B, W, P, plain):
