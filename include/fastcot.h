@@ -139,11 +139,19 @@ int fastcot_set_window(fastcot_ctx* ctx, int32_t window);
  * windows: host, one entry per sequence of the last fastcot_prefill, 1 <= windows[b] <= the current batch
  * window W.  From the next step on sequence b verifies (Eq. 5), accepts and writes back to its buffer only the
  * first windows[b] rows of its W; its accepted stream, step count and approximate tokens are those of a run with
- * that window alone.  The step still computes W rows for every sequence.  Call after fastcot_prefill (which
+ * that window alone.  On the matrix-core path the step then computes only those rows, packed one sequence after
+ * the other (FASTCOT_OPT_PACKED_ROWS, default 1; the rows of fastcot_debug_logits follow that order); the plain
+ * kernels still compute W rows for every sequence.  Call after fastcot_prefill (which
  * resets every sequence to the batch window) and before fastcot_generate, or between fastcot_jacobi_step
  * calls; fastcot_generate's approx_tail and fastcot_answer's glimpse then hold windows[b] - 1 valid entries for
  * sequence b.  FASTCOT_ESTATE otherwise. */
 int fastcot_set_windows(fastcot_ctx* ctx, const int32_t* windows);
+
+/* Row layout of the next step (the rows of fastcot_debug_logits): row_start: host, B + 1 entries; the rows of
+ * sequence b are row_start[b] .. row_start[b + 1] - 1, slot j of the sequence at row_start[b] + j, and
+ * row_start[B] is the number of rows the step computes.  Dense (b * W) unless per-sequence windows packed the
+ * rows (fastcot_set_windows).  Synchronises the stream when the layout has to be rebuilt.  Sec. 5.4 Time Composition. */
+int fastcot_step_rows(fastcot_ctx* ctx, int32_t* row_start);
 
 /* Ragged batches (Sec. 5.4 Time Composition, Table 2: a padded batch otherwise runs until its longest member ends): between
  * two fastcot_jacobi_step calls (not with fastcot_generate) a new sequence takes over slot `slot`, 0 <= slot <
@@ -198,7 +206,8 @@ int fastcot_debug_logits(fastcot_ctx* ctx, float* d_logits);
  * FASTCOT_OPT_DEBUG_STAGES: run only the first `value` stages of a forward (per layer: QKV, attention, O,
  * gate/up, down); negative (default) = all. */
 enum { FASTCOT_OPT_PLAIN_KERNELS = 1, FASTCOT_OPT_GRAPH = 2, FASTCOT_OPT_KV_PLANES = 3, FASTCOT_OPT_COMPACT = 4,
-       FASTCOT_OPT_AUTOTUNE = 5, FASTCOT_OPT_DEBUG_STAGES = 6, FASTCOT_OPT_KV_EMULATE = 7, FASTCOT_OPT_ACT_EMULATE = 8 };
+       FASTCOT_OPT_AUTOTUNE = 5, FASTCOT_OPT_DEBUG_STAGES = 6, FASTCOT_OPT_KV_EMULATE = 7, FASTCOT_OPT_ACT_EMULATE = 8,
+       FASTCOT_OPT_PACKED_ROWS = 9 };
 
 /* Launch-plan values, also set through fastcot_set_option.  They are measurement aids: defaults are chosen from
  * the model shape, and which values exist may change with the kernels.  The five GEMMs are numbered QKV, O,

@@ -19,7 +19,7 @@ vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_siz
 N_KINDS = 16
 
 T = {"emb": 0, "wlm": 1, "gf": 2, "wq": 3, "wk": 4, "wv": 5, "wo": 6, "wg": 7, "wu": 8, "wd": 9, "g1": 10, "g2": 11}
-OPT_PLAIN_KERNELS, OPT_GRAPH, OPT_KV_PLANES, OPT_COMPACT, OPT_AUTOTUNE, OPT_DEBUG_STAGES, OPT_KV_EMULATE, OPT_ACT_EMULATE = 1, 2, 3, 4, 5, 6, 7, 8
+OPT_PLAIN_KERNELS, OPT_GRAPH, OPT_KV_PLANES, OPT_COMPACT, OPT_AUTOTUNE, OPT_DEBUG_STAGES, OPT_KV_EMULATE, OPT_ACT_EMULATE, OPT_PACKED_ROWS = 1, 2, 3, 4, 5, 6, 7, 8, 9
 PLAN_NW, PLAN_KS, PLAN_SB, PLAN_ROT, PLAN_CO_SINGLE, PLAN_ATTN_SPLITS, PLAN_ATTN_BLOCKS, PLAN_ATTN_MANY_ROWS = 100, 105, 110, 115, 120, 121, 122, 123
 _STATUS = {0: "OK", -1: "EINVAL", -2: "ESTATE", -3: "ECAPACITY", -4: "EHIP", -5: "ENOMEM"}
 
@@ -57,6 +57,7 @@ SYMBOLS = {
     "fastcot_generate": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp, vp]),
     "fastcot_get_state": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp]),
     "fastcot_debug_logits": (ctypes.c_int, [vp, vp]),
+    "fastcot_step_rows": (ctypes.c_int, [vp, vp]),
     "fastcot_set_option": (ctypes.c_int, [vp, i32, i32]),
     "fastcot_debug_read": (ctypes.c_int, [vp, i32, vp, sz]),
     "fastcot_step_times": (ctypes.c_int, [vp, vp, i32, vp]),
@@ -269,6 +270,12 @@ class Context:
         _check(lib().fastcot_get_state(self.h, n.ctypes.data, g.ctypes.data, done.ctypes.data, win.ctypes.data,
                                        o.ctypes.data, K.ctypes.data), self.h)
         return dict(n=n, g=g, done=done, window=win, o=o, K=K)
+
+    def step_rows(self) -> np.ndarray:
+        """Row layout of the next step: rows of sequence b are out[b] .. out[b + 1] - 1 (out[B] = rows computed)."""
+        out = np.zeros(self.B + 1, dtype=np.int32)
+        _check(lib().fastcot_step_rows(self.h, out.ctypes.data), self.h)
+        return out
 
     def debug_logits(self, on: bool = True):
         """Returns the device tensor [max_batch*W, vocab] the following steps fill (or None)."""

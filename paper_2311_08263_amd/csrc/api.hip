@@ -27,6 +27,9 @@ struct fastcot_ctx {
     int last_eos;        // eos_id of the last fastcot_generate (-1 = none)
     int buf_len;
     int opt_plain, opt_graph, dbg_stop;
+    int opt_packed;      // steps of sequences with windows of their own compute only those rows (MFMA path)
+    int rows_dirty;      // the row map has to be rebuilt before the next step (windows, slots or the batch changed)
+    int rows_step;       // rows of a packed step; 0 = dense
     float* dbg_logits;
     hipGraphExec_t graph_exec;
     hipGraph_t graph;
@@ -150,6 +153,7 @@ int fc_build_maps(const fastcot_config* c, ModelMap* mm, WorkspaceMap* wm, Kerne
         s.plen = ti(k.B); s.olen = ti(k.B); s.win = ti(k.B * k.Wcap); s.o = ti(k.B * k.Wcap);
         s.buf = ti(k.B * k.S); s.out = ti(k.B * k.S); s.prompt = ti(k.B * k.S); s.flags = ti(8); s.params = ti(8);
         s.wseq = ti(k.B);
+        s.rowb = ti(k.B * k.Wcap); s.rowj = ti(k.B * k.Wcap); s.rstart = ti(k.B + 1);
         s.words = w;
         wm->st = s;
         wm->state = take((size_t)w * 4);
@@ -269,6 +273,7 @@ extern "C" int fastcot_init(const fastcot_config* cfg, const void* d_packed, voi
     if (workspace_bytes < c->wm.total) { delete c; return fail(nullptr, FASTCOT_ECAPACITY, "workspace too small%s"); }
     c->cfg = *cfg; c->weights = (const char*)d_packed; c->ws = (char*)d_workspace; c->st = (hipStream_t)hip_stream;
     c->Bact = 0; c->prefilled = 0; c->generated = 0; c->buf_len = 0; c->opt_tune = 1; c->opt_compact = 1;
+    c->opt_packed = 1; c->rows_dirty = 1; c->rows_step = 0;
     c->opt_plain = (cfg->dtype == FASTCOT_F32); c->opt_graph = 1; c->dbg_stop = -1; c->dbg_logits = nullptr;
     c->graph_exec = nullptr; c->graph = nullptr; c->graph_valid = 0; c->prof_on = 0; c->prof_used = 0;
     c->pinned = nullptr; c->err[0] = 0;
@@ -305,6 +310,7 @@ static void drop_graph(fastcot_ctx* c) {
     if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
     if (c->graph) (void)hipGraphDestroy(c->graph);
     c->graph_exec = nullptr; c->graph = nullptr; c->graph_valid = 0;
+    c->rows_dirty = 1;          // whatever invalidates the graph may have changed who sits where
 }
 
 extern "C" void fastcot_free(fastcot_ctx* c) {
@@ -326,6 +332,7 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
         c->opt_plain = value != 0;
     } else if (option == FASTCOT_OPT_GRAPH) c->opt_graph = value != 0;
     else if (option == FASTCOT_OPT_DEBUG_STAGES) c->dbg_stop = value;
+    else if (option == FASTCOT_OPT_PACKED_ROWS) c->opt_packed = value != 0;
     else if (option == FASTCOT_OPT_KV_PLANES) {
         if (c->cfg.dtype != FASTCOT_BF16 || value < 1 || value > 3) return fail(c, FASTCOT_EINVAL, "KV planes: 1, 2 or 3, bf16 models only%s");
         c->kd.kvp = value; c->prefilled = 0;      // the cache layout changes: a new prefill is required
@@ -429,13 +436,19 @@ static int forward_plain(fastcot_ctx* c, int lmhead, int R) {
     return 0;
 }
 
-// one forward pass over R rows per sequence (R = 0: the window)
-static int forward(fastcot_ctx* c, int lmhead, int R = 0) {
+// one forward pass over R rows per sequence (R = 0: the window); step: the pass of a Jacobi step, which computes
+// only the sequences' own rows when they have windows of their own
+static int forward(fastcot_ctx* c, int lmhead, int R = 0, bool step = false) {
     if (R <= 0) R = c->kd.W;
     if (R > c->kd.Wcap) return fail(c, FASTCOT_ECAPACITY, "pass of %s%ld rows per sequence exceeds the workspace (%ld)", "", (long)R, (long)c->kd.Wcap);
     if (c->opt_plain || !fc_fast_supported(c->kd, c->Bact * R)) return forward_plain(c, lmhead, R);
     FastArgs a;
     a.kd = c->kd; a.kd.W = R; a.kd.M = c->Bact * R; a.Bact = c->Bact;
+    if (step && c->rows_step > 0) {          // sequences with windows of their own: only those rows
+        const StateMap& sm = c->wm.st; const int32_t* stp = state_ptr(c);
+        a.kd.M = c->rows_step;
+        a.rm = RowMap{stp + sm.rowb, stp + sm.rowj, stp + sm.rstart};
+    }
     a.mm = &c->mm; a.wm = &c->wm; a.weights = c->weights; a.ws = c->ws; a.dbg_logits = c->dbg_logits;
     a.plan = &c->plan; a.st = c->st; a.lmhead = lmhead;
     a.dbg_stop = c->dbg_stop;
@@ -447,13 +460,43 @@ static int forward(fastcot_ctx* c, int lmhead, int R = 0) {
 }
 
 static int step_body(fastcot_ctx* c) {
-    int rc = forward(c, 1);
+    int rc = forward(c, 1, 0, true);
     if (rc) return rc;
     LAUNCH(c, KK_ACCEPT, fc_accept_commit(state_ptr(c), c->wm.st, c->Bact, c->kd.W, c->kd.S, c->st));
     return 0;
 }
 
+// Row map of the next steps: with per-sequence windows (and the option on, and the matrix-core path) sequence b
+// contributes its own W_b rows, packed one sequence after the other; otherwise the layout is dense.  Reads the
+// windows back from the device, where they travel with their sequences when slots are traded.
+static int rebuild_rows(fastcot_ctx* c) {
+    const StateMap& sm = c->wm.st; const int B = c->Bact, W = c->kd.W;
+    int32_t* stp = state_ptr(c);
+    c->rows_dirty = 0; c->rows_step = 0;
+    if (!c->opt_packed || c->opt_plain || B < 1) return 0;
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    std::vector<int32_t> ws(B);
+    HIPCHK(c, hipMemcpy(ws.data(), stp + sm.wseq, (size_t)B * 4, hipMemcpyDeviceToHost));
+    bool own = false;
+    for (int b = 0; b < B; ++b) own = own || (ws[b] > 0 && ws[b] < W);
+    if (!own) return 0;
+    std::vector<int32_t> rowb, rowj, rstart(B + 1);
+    for (int b = 0; b < B; ++b) {
+        const int Wb = ws[b] > 0 && ws[b] < W ? ws[b] : W;
+        rstart[b] = (int32_t)rowb.size();
+        for (int j = 0; j < Wb; ++j) { rowb.push_back(b); rowj.push_back(j); }
+    }
+    rstart[B] = (int32_t)rowb.size();
+    if (!fc_fast_supported(c->kd, (int)rowb.size())) return 0;
+    HIPCHK(c, hipMemcpy(stp + sm.rowb, rowb.data(), rowb.size() * 4, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(stp + sm.rowj, rowj.data(), rowj.size() * 4, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(stp + sm.rstart, rstart.data(), rstart.size() * 4, hipMemcpyHostToDevice));
+    c->rows_step = (int)rowb.size();
+    return 0;
+}
+
 static int enqueue_step(fastcot_ctx* c) {
+    if (c->rows_dirty) { int rc = rebuild_rows(c); if (rc) return rc; }
     // the legacy default stream cannot be captured: launch kernel by kernel there
     if (!c->opt_graph || c->prof_on || c->st == nullptr) return step_body(c);
     if (!c->graph_valid) {
@@ -607,8 +650,8 @@ extern "C" int fastcot_set_window(fastcot_ctx* c, int32_t window) {
 }
 
 // Per-sequence window sizes (ragged batches, Sec. 5.4 Time Composition): sequence b verifies, accepts and writes back only the
-// first windows[b] rows of its share of the step.  The step still computes the batch's window for every
-// sequence (rows sit at b * W + j), so this changes what a sequence does per step, not what the step costs.
+// first windows[b] rows of its share of the step.  On the matrix-core path the step then computes only those rows
+// (rebuild_rows packs them); the plain kernels keep the dense layout (rows at b * W + j) and ignore the rest.
 extern "C" int fastcot_set_windows(fastcot_ctx* c, const int32_t* windows) {
     if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
     if (!c->prefilled) return fail(c, FASTCOT_ESTATE, "fastcot_set_windows before fastcot_prefill%s");
@@ -619,6 +662,21 @@ extern "C" int fastcot_set_windows(fastcot_ctx* c, const int32_t* windows) {
         if (windows[b] < 1 || windows[b] > c->kd.W) return fail(c, FASTCOT_EINVAL, "window %s%ld outside 1..%ld", "", (long)windows[b], (long)c->kd.W);
     HIPCHK(c, hipStreamSynchronize(c->st));
     HIPCHK(c, hipMemcpy(state_ptr(c) + c->wm.st.wseq, windows, (size_t)B * 4, hipMemcpyHostToDevice));
+    drop_graph(c);          // the rows of a step may change
+    return 0;
+}
+
+extern "C" int fastcot_step_rows(fastcot_ctx* c, int32_t* row_start) {
+    if (!c) return fail(nullptr, FASTCOT_EINVAL, "ctx is NULL%s");
+    if (!row_start) return fail(c, FASTCOT_EINVAL, "row_start is NULL%s");
+    if (!c->prefilled) return fail(c, FASTCOT_ESTATE, "fastcot_step_rows before fastcot_prefill%s");
+    if (c->rows_dirty) { int rc = rebuild_rows(c); if (rc) return rc; }
+    const int B = c->Bact, W = c->kd.W;
+    if (c->rows_step > 0) {
+        HIPCHK(c, hipStreamSynchronize(c->st));
+        HIPCHK(c, hipMemcpy(row_start, state_ptr(c) + c->wm.st.rstart, (size_t)(B + 1) * 4, hipMemcpyDeviceToHost));
+    } else
+        for (int b = 0; b <= B; ++b) row_start[b] = b * W;
     return 0;
 }
 
@@ -653,6 +711,7 @@ extern "C" int fastcot_join(fastcot_ctx* c, int32_t slot, const int32_t* prompt,
     HIPCHK(c, hipMemcpy(stp + sm.plen, &len, 4, hipMemcpyHostToDevice));
     HIPCHK(c, hipMemsetAsync(stp + sm.n, 0, 4, c->st));
     HIPCHK(c, hipMemsetAsync(stp + sm.wseq, 0, 4, c->st));    // the newcomer runs the batch's window
+    if (c->rows_step > 0) drop_graph(c);                      // (with packed rows the step's row map changes with it)
     // a pass of R rows uses the first R window entries, which at R > W are the other sequences' windows
     std::vector<int32_t> wins((size_t)B * kd.W);
     HIPCHK(c, hipMemcpy(wins.data(), stp + sm.win, wins.size() * 4, hipMemcpyDeviceToHost));
@@ -921,7 +980,8 @@ extern "C" int fastcot_profile_step(fastcot_ctx* c, int32_t iters, float* mean_m
     double sum[FASTCOT_N_KERNEL_KINDS] = {0}; long cnt[FASTCOT_N_KERNEL_KINDS] = {0};
     for (int it = 0; it < iters; ++it) {
         c->prof_on = 1; c->prof_used = 0;
-        int rc = forward(c, 1);
+        int rc = c->rows_dirty ? rebuild_rows(c) : 0;
+        if (!rc) rc = forward(c, 1, 0, true);
         // what an event pair itself adds to a launch: the same pair around a kernel that does nothing
         if (!rc) {
             hipError_t e1 = prof_mark(c, KK_EMPTY);

@@ -9,6 +9,8 @@ struct AttnArgs {
     const bf16_t* vc;      // V cache, transposed [L][B][Hkv][planes][128][S]
     int32_t layer, B, H, Hkv, S, W, kvp;
     const int32_t* n_state;   // committed length per sequence
+    const int32_t* rstart;    // packed rows (per-sequence windows): sequence b owns rows rstart[b] .. rstart[b + 1] - 1 and W is the
+                              // largest window; NULL = dense, W rows per sequence at b * W
     float* out;            // [rows][ldo], head h at column h*128 (may be NULL when ofrag is given)
     int32_t ldo;
     int32_t subrows;       // rows per workgroup: 0 = 32 where the window has more than 16 rows (two query tiles per workgroup),

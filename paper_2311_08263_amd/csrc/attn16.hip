@@ -71,7 +71,9 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
     const int bh = blockIdx.x, hr = bh % a.H, G = a.H / a.Hkv, kvh = hr % a.Hkv, h = kvh * G + hr / a.Hkv;
     const int sub = (bh / a.H) % nsub, b = bh / (a.H * nsub);
     const int sp = blockIdx.y, nsp_max = gridDim.y;
-    const int row0 = SUBR * sub, Wr = a.W - row0 < SUBR ? a.W - row0 : SUBR;      // rows of this unit
+    const int Wb = a.rstart ? a.rstart[b + 1] - a.rstart[b] : a.W, rbase = a.rstart ? a.rstart[b] : b * a.W;
+    const int row0 = SUBR * sub, Wr = Wb - row0 < SUBR ? Wb - row0 : SUBR;        // rows of this unit
+    if (Wr <= 0) return;                                     // a sequence with a smaller window of its own
     const int n = a.n_state[b] + row0;                       // positions every row of the unit sees
     int T = n + Wr;
     if (T > a.S) T = a.S;                                    // capacity guard (the host checks first)
@@ -94,7 +96,7 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
     for (int qt = 0; qt < QT; ++qt) {
         int j = qt * 16 + lm;
         if (j >= Wr) j = Wr - 1;
-        const float* qr = a.q + (size_t)(b * a.W + row0 + j) * a.ldq + h * 128 + 32 * g;
+        const float* qr = a.q + (size_t)(rbase + row0 + j) * a.ldq + h * 128 + 32 * g;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             float4 x0 = *(const float4*)(qr + 8 * s), x1 = *(const float4*)(qr + 8 * s + 4);
@@ -345,7 +347,7 @@ __global__ __launch_bounds__(256, QT) void k_attn16(AttnArgs a) {
         const int j = qt * 16 + lm;
         if (j < Wr) {
             const float inv = 1.0f / lw[qt];
-            const int row = b * a.W + row0 + j;
+            const int row = rbase + row0 + j;
             if (a.out) {
                 float* o = a.out + (size_t)row * a.ldo + h * 128 + 4 * g;
 #pragma unroll

@@ -39,12 +39,14 @@ __global__ __launch_bounds__(256, 2) void k_attnp(AttnArgs a) {
     const int bh = blockIdx.x / nrb, rbk = nrb - 1 - (int)(blockIdx.x % nrb);
     const int hr = bh % a.H, G = a.H / a.Hkv, kvh = hr % a.Hkv, h = kvh * G + hr / a.Hkv, b = bh / a.H;
     const int n = a.n_state[b];
-    const int row_base = 128 * rbk, rows_wg = a.W - row_base < 128 ? a.W - row_base : 128;
+    const int Wb = a.rstart ? a.rstart[b + 1] - a.rstart[b] : a.W, rbase = a.rstart ? a.rstart[b] : b * a.W;
+    const int row_base = 128 * rbk, rows_wg = Wb - row_base < 128 ? Wb - row_base : 128;
+    if (rows_wg <= 0) return;                             // a sequence with a smaller window of its own
     int T = n + row_base + rows_wg;                       // keys the last row of the workgroup sees
     if (T > a.S) T = a.S;                                 // capacity guard (the host checks first)
     const int NB = (T + 31) >> 5;
     const int r0 = row_base + 32 * wv;                    // this wave's rows r0 .. r0 + 31
-    const int rows_wave = a.W - r0 < 32 ? a.W - r0 : 32;  // <= 0: a wave without rows (it still copies blocks)
+    const int rows_wave = Wb - r0 < 32 ? Wb - r0 : 32;    // <= 0: a wave without rows (it still copies blocks)
     const int last_key = n + r0 + rows_wave - 1;          // newest key any row of the wave sees
     const size_t plane = (size_t)a.S * 128;
     const bf16_t* kbase = a.kc + ((((size_t)a.layer * a.B + b) * a.Hkv + kvh) * KVP) * plane;
@@ -55,8 +57,8 @@ __global__ __launch_bounds__(256, 2) void k_attnp(AttnArgs a) {
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
         int j = r0 + qt * 16 + lm;
-        if (j >= a.W) j = a.W - 1;
-        const float* qr = a.q + (size_t)(b * a.W + j) * a.ldq + h * 128 + 32 * g;
+        if (j >= Wb) j = Wb - 1;
+        const float* qr = a.q + (size_t)(rbase + j) * a.ldq + h * 128 + 32 * g;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const float4 x0 = *(const float4*)(qr + 8 * s), x1 = *(const float4*)(qr + 8 * s + 4);
@@ -116,7 +118,7 @@ __global__ __launch_bounds__(256, 2) void k_attnp(AttnArgs a) {
         for (int qt = 0; qt < 2; ++qt) {
             // lane: row j = r0 + qt*16 + lm, keys kb + 8*g + e  (e = 4*t + r)
             int j = r0 + qt * 16 + lm;
-            if (j >= a.W) j = a.W - 1;
+            if (j >= Wb) j = Wb - 1;
             const int lastvis = n + j;
             float p[8];
             float bm = NEG_BIG;
@@ -180,9 +182,9 @@ __global__ __launch_bounds__(256, 2) void k_attnp(AttnArgs a) {
         l += __shfl_xor(l, 16, 64);
         l += __shfl_xor(l, 32, 64);
         const int j = r0 + qt * 16 + lm;
-        if (j < a.W) {
+        if (j < Wb) {
             const float inv = 1.0f / l;
-            const int row = b * a.W + j;
+            const int row = rbase + j;
             if (a.out) {
                 float* o = a.out + (size_t)row * a.ldo + h * 128 + 4 * g;
 #pragma unroll

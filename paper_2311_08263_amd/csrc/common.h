@@ -106,10 +106,17 @@ struct ModelMap {
 struct StateMap {      // offsets in int32 words from the state base
     int32_t n, g, done, steps, newest, lastK, plen, olen, win, o, buf, out, prompt, flags, params;
     int32_t wseq;      // per-sequence window size [B]: 0 = the batch's window, else the smaller of the two
+    int32_t rowb, rowj; // packed rows of a step with per-sequence windows: row m is slot rowj[m] of sequence rowb[m] [B * window]
+    int32_t rstart;    // ... and sequence b's rows are rstart[b] .. rstart[b + 1] - 1 [B + 1]
     int32_t words;
 };
 enum { FLAG_ALL_DONE = 0, FLAG_ERROR = 1 };
 enum { PARAM_MAX_NEW = 0, PARAM_EOS = 1, PARAM_MAX_STEPS = 2, PARAM_BUF_LEN = 3, PARAM_B = 4 };
+
+// Row layout of a pass.  Dense (all three NULL): row m = slot m % W of sequence m / W.  Packed (a step whose
+// sequences have windows of their own, Sec. 5.4 Time Composition): sequence b contributes only its own W_b rows;
+// row m belongs to sequence rowb[m], slot rowj[m], and the rows of sequence b start at rstart[b].
+struct RowMap { const int32_t* rowb; const int32_t* rowj; const int32_t* rstart; };
 
 struct WorkspaceMap {
     size_t kc, vc;              // KV cache [L][B][Hkv][planes][S/32 blocks][32 * Dh] in fragment order (k_index, v_index)

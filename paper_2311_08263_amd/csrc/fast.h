@@ -29,6 +29,7 @@ struct FastArgs {
     hipStream_t st;
     void* prof;
     hipError_t (*prof_mark)(void*, int);
+    RowMap rm = RowMap{nullptr, nullptr, nullptr};   // packed rows of a step with per-sequence windows (kd.M = their sum, kd.W = the largest)
     int dbg_stop;      // debug: number of stages to run (5 per layer), < 0 = all
     int tune_gi = -1;  // >= 0: launch only GEMM tune_gi (0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head) of layer 0 ...
     int tune_sb = 0;   // ... with this many-batches choice, this batch order and this many K slices per owner

@@ -127,16 +127,17 @@ hipError_t fc_fast_forward(const FastArgs& a) {
     g.amax_val = (float*)(ws + wm.amax_part); g.layer = 0;
     AttnArgs at; memset(&at, 0, sizeof(at));
     at.q = q; at.ldq = qd; at.kc = g.kc; at.vc = g.vc; at.B = kd.B; at.H = kd.H; at.Hkv = kd.Hkv; at.S = kd.S; at.W = kd.W; at.kvp = kd.kvp;
+    at.rstart = a.rm.rstart;
     at.n_state = g.n_state; at.out = att; at.ldo = qd; at.part = (float*)(ws + wm.attn_part); at.cnt = (int32_t*)(ws + wm.attn_cnt); at.bpw = a.plan->attn_bpw;
 
     GemmCoArgs co; memset(&co, 0, sizeof(co));
     co.M = M; co.eps = kd.eps; co.n_state = g.n_state; co.cosT = g.cosT; co.sinT = g.sinT; co.kc = g.kc; co.vc = g.vc;
     co.H = kd.H; co.Hkv = kd.Hkv; co.B = kd.B; co.S = kd.S; co.Wn = kd.W; co.kvp = kd.kvp; co.kvq = kd.kvq;
-    co.amax_val = g.amax_val; co.single_buffer = 1;
+    co.amax_val = g.amax_val; co.single_buffer = 1; co.rm = a.rm;
     Gemm256Args big; memset(&big, 0, sizeof(big));
     big.M = M; big.n_state = g.n_state; big.cosT = g.cosT; big.sinT = g.sinT; big.kc = g.kc; big.vc = g.vc;
     big.H = kd.H; big.Hkv = kd.Hkv; big.B = kd.B; big.S = kd.S; big.Wn = kd.W; big.kvp = kd.kvp; big.kvq = kd.kvq;
-    big.amax_stride = (M + 15) / 16 * 16;
+    big.amax_stride = (M + 15) / 16 * 16; big.rm = a.rm;
     // many-row scratch: the fragments of x, of the attention output and of the hidden activations, the partial
     // row sums of squares of x, then the split-K partial tiles
     const ManyRowScratch mrs = many_row_scratch(kd);
@@ -208,7 +209,7 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         }
         return hipErrorInvalidValue;
     }
-    FLAUNCH(KK_EMBED, fc_embed(wt + mm.emb_off, FASTCOT_BF16, stp + wm.st.win, x, M, d, kd.V, a.st));
+    FLAUNCH(KK_EMBED, fc_embed(wt + mm.emb_off, FASTCOT_BF16, stp + wm.st.win, x, M, d, kd.V, a.st, a.rm, kd.W));
     int nstage = 0;
 #define DBG_STOP() do { if (a.dbg_stop >= 0 && nstage++ >= a.dbg_stop) return hipSuccess; } while (0)
     for (int l = 0; l < kd.L; ++l) {
@@ -260,10 +261,10 @@ hipError_t fc_fast_forward(const FastArgs& a) {
         FLAUNCH(KK_LM, gemm(EPI_LMHEAD, wt + mm.lm.off, d, kd.V, x, d, (const float*)(wt + mm.gf_off), a.dbg_logits, kd.V));
         if (M <= 32)
             FLAUNCH(KK_ARGMAX, fc_argmax_final(g.amax_val, (const int32_t*)(g.amax_val + (size_t)nwin * stride), nwin, stride, M, stp + wm.st.o,
-                                               (float*)(ws + wm.topv), a.st));
+                                               (float*)(ws + wm.topv), a.st, a.rm, kd.W));
         else
             FLAUNCH(KK_ARGMAX, fc_argmax_final(big.amax_val, big.amax_idx, lm_ncb, big.amax_stride, M,
-                                               stp + wm.st.o, (float*)(ws + wm.topv), a.st));
+                                               stp + wm.st.o, (float*)(ws + wm.topv), a.st, a.rm, kd.W));
     }
     return hipSuccess;
 }

@@ -12,6 +12,7 @@ struct Gemm256Args {
     const int32_t* n_state; const float* cosT; const float* sinT;
     bf16_t* kc; bf16_t* vc;
     int32_t layer, H, Hkv, B, S, Wn, kvp, kvq;
+    RowMap rm;             // QKV: which sequence and slot a row is (dense when rm.rowb is NULL)
     float* amax_val; int32_t* amax_idx;   // LM head: winners per column block of 256 [column blocks][amax_stride]
     int32_t amax_stride;
     int32_t sk;            // K slices (RESID only when > 1: partial tiles to `part`, then added in slice order)

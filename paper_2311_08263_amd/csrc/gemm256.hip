@@ -133,8 +133,8 @@ __global__ __launch_bounds__(KG == 1 ? 256 : 512, KG == 1 ? 2 : 1) void k_gemm25
         for (int m = 0; m < 4; ++m) {
             const int row = (mt0 + m) * 16 + lm;
             const bool rok = (!KSPLIT || kg == (m >> 1)) && mt0 + m < MT && row < a.M;
-            qb[m] = rok ? row / a.Wn : 0;
-            qpos[m] = rok ? a.n_state[qb[m]] + row % a.Wn : a.S;
+            qb[m] = rok ? (a.rm.rowb ? a.rm.rowb[row] : row / a.Wn) : 0;
+            qpos[m] = rok ? a.n_state[qb[m]] + (a.rm.rowb ? a.rm.rowj[row] : row % a.Wn) : a.S;
         }
     }
 

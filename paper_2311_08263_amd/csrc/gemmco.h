@@ -16,6 +16,7 @@ struct GemmCoArgs {
     const int32_t* n_state; const float* cosT; const float* sinT;
     bf16_t* kc; bf16_t* vc;
     int32_t layer, H, Hkv, B, S, Wn, kvp, kvq;
+    RowMap rm;             // QKV: which sequence and slot a row is (dense when rm.rowb is NULL: m / Wn, m % Wn)
     float* amax_val; int32_t* amax_idx;   // LM head: winners per workgroup [workgroups][16 or 32 rows]
     int32_t ks;            // workgroups per column owner, each taking 1/ks of K (1..8; 1 for the LM head)
     float* xpart;          // ks > 1: partial tiles [workgroup][8 or 16 (more than 8 output tiles)][64 lanes][4], then each
@@ -37,5 +38,6 @@ int fc_gemmco_most(int M, int K, bool gain);
 int fc_num_cus();      // compute units of the current device
 hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st);
 // reduction of the LM head's per-workgroup winners [nparts][stride] to one id and value per row (lowest id on ties)
+// (with a row map the result of row m goes to entry rowb[m] * W + rowj[m] of ids and top)
 hipError_t fc_argmax_final(const float* val, const int32_t* idx, int nparts, int stride, int M, int32_t* ids, float* top,
-                           hipStream_t st);
+                           hipStream_t st, RowMap rm = RowMap{nullptr, nullptr, nullptr}, int W = 0);

@@ -163,7 +163,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         } else if (EPI == EPI_QKV) {
             const int hh = nt >> 3, t = nt & 7;
             if (mine && hh < a.H + a.Hkv) {
-                const int pos = a.n_state[m / a.Wn] + m % a.Wn;
+                const int pos = a.rm.rowb ? a.n_state[a.rm.rowb[m]] + a.rm.rowj[m] : a.n_state[m / a.Wn] + m % a.Wn;
                 if (pos < a.S) {
                     const f32x4_t c4 = *(const f32x4_t*)(a.cosT + (size_t)pos * 64 + 8 * t + 4 * (g4 & 1));
                     const f32x4_t s4 = *(const f32x4_t*)(a.sinT + (size_t)pos * 64 + 8 * t + 4 * (g4 & 1));
@@ -371,7 +371,8 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
             // q/k heads: tile t of a head holds elements 8t..8t+7 (columns 0..7) and their rotary partners
             // 64+8t.. (columns 8..15, lane ^ 32); v heads are in natural order
             const int hh = nt >> 3, t = nt & 7;
-            const int b = m / a.Wn, j = m % a.Wn;
+            const int mc = m < a.M ? m : 0;
+            const int b = a.rm.rowb ? a.rm.rowb[mc] : m / a.Wn, j = a.rm.rowb ? a.rm.rowj[mc] : m % a.Wn;
             const int pos = m < a.M ? a.n_state[b] + j : a.S;
             const bool ok = m < a.M && pos < a.S;               // capacity guard
             const size_t plane = (size_t)a.S * 128;
@@ -604,7 +605,7 @@ hipError_t fc_gemmco(int epi, const GemmCoArgs& a, int G, hipStream_t st) {
 }
 
 // reduction of the LM head's per-workgroup winners: lowest id on ties
-__global__ void k_argmax_final(const float* val, const int32_t* idx, int nparts, int stride, int32_t* ids, float* top) {
+__global__ void k_argmax_final(const float* val, const int32_t* idx, int nparts, int stride, int32_t* ids, float* top, RowMap rm, int W) {
     __shared__ float bv[4];
     __shared__ int bi[4];
     const int m = blockIdx.x;
@@ -622,11 +623,12 @@ __global__ void k_argmax_final(const float* val, const int32_t* idx, int nparts,
     if (threadIdx.x == 0) {
         for (int q = 1; q < (int)(blockDim.x >> 6); ++q)
             if (bv[q] > best || (bv[q] == best && bi[q] < b)) { best = bv[q]; b = bi[q]; }
-        ids[m] = b; top[m] = best;
+        const int dst = rm.rowb ? rm.rowb[m] * W + rm.rowj[m] : m;
+        ids[dst] = b; top[dst] = best;
     }
 }
 hipError_t fc_argmax_final(const float* val, const int32_t* idx, int nparts, int stride, int M, int32_t* ids, float* top,
-                           hipStream_t st) {
-    k_argmax_final<<<M, 256, 0, st>>>(val, idx, nparts, stride, ids, top);
+                           hipStream_t st, RowMap rm, int W) {
+    k_argmax_final<<<M, 256, 0, st>>>(val, idx, nparts, stride, ids, top, rm, W);
     return hipGetLastError();
 }

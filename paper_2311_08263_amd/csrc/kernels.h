@@ -6,7 +6,9 @@
 void fc_set_error(const char* msg);
 
 // ---- plain kernels (one thread per output; used for fp32 models and as the on-device cross-check)
-hipError_t fc_embed(const void* emb, int dt, const int32_t* win, float* x, int M, int d, int V, hipStream_t st);
+// x[m] = embedding of win[m] (dense), or of win[rowb[m] * W + rowj[m]] with a row map
+hipError_t fc_embed(const void* emb, int dt, const int32_t* win, float* x, int M, int d, int V, hipStream_t st,
+                    RowMap rm = RowMap{nullptr, nullptr, nullptr}, int W = 0);
 hipError_t fc_rmsnorm_plain(const float* x, const float* g, float* out, int M, int d, float eps, hipStream_t st);
 hipError_t fc_gemm_plain(const void* W, int dt, int K, int NP, int N, const float* X, int ldx, float* Y, int ldy,
                          int M, int accumulate, hipStream_t st);

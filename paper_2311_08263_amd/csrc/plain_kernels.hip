@@ -38,15 +38,15 @@ template <int DT> __device__ inline float kvload(const void* C, size_t i, size_t
 
 // ------------------------------------------------------------------ embedding gather
 template <int DT>
-__global__ void k_embed(const void* emb, const int32_t* win, float* x, int d, int V) {
+__global__ void k_embed(const void* emb, const int32_t* win, float* x, int d, int V, RowMap rm, int W) {
     int m = blockIdx.x;
-    int t = win[m];
+    int t = win[rm.rowb ? rm.rowb[m] * W + rm.rowj[m] : m];
     if (t < 0 || t >= V) t = 0;
     for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)m * d + i] = wat<DT>(emb, (size_t)t * d + i);
 }
-hipError_t fc_embed(const void* emb, int dt, const int32_t* win, float* x, int M, int d, int V, hipStream_t st) {
-    if (dt == FASTCOT_F32) k_embed<FASTCOT_F32><<<M, 256, 0, st>>>(emb, win, x, d, V);
-    else k_embed<FASTCOT_BF16><<<M, 256, 0, st>>>(emb, win, x, d, V);
+hipError_t fc_embed(const void* emb, int dt, const int32_t* win, float* x, int M, int d, int V, hipStream_t st, RowMap rm, int W) {
+    if (dt == FASTCOT_F32) k_embed<FASTCOT_F32><<<M, 256, 0, st>>>(emb, win, x, d, V, rm, W);
+    else k_embed<FASTCOT_BF16><<<M, 256, 0, st>>>(emb, win, x, d, V, rm, W);
     return hipGetLastError();
 }
 

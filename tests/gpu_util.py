@@ -62,6 +62,7 @@ def follow_steps(ctx, omodel, prompts, lens, n_steps, tol, margin=0.05, check_ro
             assert (st["window"][slot][1:] == np.asarray(bf)[:W - 1]).all()
         win, n0 = st["window"].copy(), st["n"].copy()
         say(f"follow step {step} n={n0.tolist()}")
+        rs = ctx.step_rows()                # dense, or packed when the sequences have windows of their own
         nacc, acc, win_next = ctx.step()
         st = ctx.state()
         glog = dbg.cpu().numpy()
@@ -69,16 +70,20 @@ def follow_steps(ctx, omodel, prompts, lens, n_steps, tol, margin=0.05, check_ro
             if nacc[b] == 0:
                 continue
             olog, oam, _ = sessions[b].forward(win[b], int(n0[b]))
-            gl = glog[b * W:(b + 1) * W]
+            Wr = int(rs[b + 1] - rs[b])     # rows the step computed for this sequence
+            if wins is not None and Wr < W:
+                assert Wr == wins[b]
+            gl = glog[rs[b]:rs[b] + Wr]
+            olog, oam = olog[:Wr], oam[:Wr]
             err = np.abs(gl - olog).max()
             max_err = max(max_err, float(err))
             assert err <= tol, f"step {step} seq {b}: |dlogit| {err} > {tol}"
             mg = margins(olog)
-            o_gpu = st["o"][b]
+            o_gpu = st["o"][b][:Wr]
             clear = mg > margin
             assert (o_gpu[clear] == oam[clear]).all(), f"step {step} seq {b}: argmax differs on a clear-margin row"
             assert (o_gpu == gl.argmax(-1)).all(), "GPU argmax is not the argmax of the GPU's own logits"
-            rows += W
+            rows += Wr
             low += int((~clear).sum())
             # integer path, recomputed by the oracle from the GPU's own argmax row: no tolerance
             Wb = wins[b] if wins is not None else W

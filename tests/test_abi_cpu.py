@@ -45,6 +45,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     one = np.ones(4, dtype=np.int32)
     assert L.fastcot_set_window(None, 4) == -1
     assert L.fastcot_set_windows(None, one.ctypes.data) == -1
+    assert L.fastcot_step_rows(None, one.ctypes.data) == -1
     assert L.fastcot_join(None, 0, one.ctypes.data, 4, one.ctypes.data) == -1
     assert L.fastcot_answer(None, one.ctypes.data, 1, 4, -1, one.ctypes.data, one.ctypes.data) == -1
     assert b"NULL" in L.fastcot_last_error(None)

@@ -265,6 +265,38 @@ def test_per_sequence_windows_bf16(fc):
     print(f"per-sequence windows: verified counts {r['K']}")
 
 
+@pytest.mark.parametrize("B,W,wins", [(4, 16, [16, 4, 4, 4]), (3, 32, [32, 5, 20]), (2, 8, [8, 8]), (4, 64, [3, 64, 17, 40])])
+def test_packed_rows(fc, B, W, wins):
+    """Sequences with windows of their own: the step computes only their rows, packed one sequence after the
+    other (28 rows instead of 64 through the column-owner kernels, 57 instead of 96 and 124 instead of 256 through
+    the many-row kernels), and with the option off all B x W rows; the oracle follows both, and a generation to
+    the end gives the same tokens and step counts either way."""
+    shape, P, N = SMALL, 41, 40
+    S = ((P + N + 2 * W + 31) // 32) * 32
+    ctx, om = setup(fc, shape, B, S, W)
+    prompts = synthgen.prompts(B, P, shape.vocab, seed=131)
+    lens = [P - 4 * b for b in range(B)]
+    buf = synthgen.buffer_init(B, N + 2 * W, shape.vocab, seed=132)
+    say(f"packed rows B={B} W={W} wins={wins}")
+    outs = []
+    for packed in (1, 0):
+        ctx.set_option(fc.binding.OPT_PACKED_ROWS, packed)
+        ctx.prefill(prompts, lens, buf)
+        ctx.set_windows(wins)
+        rows = int(ctx.step_rows()[B])
+        assert rows == (sum(wins) if packed and min(wins) < W else B * W)
+        r = follow_steps(ctx, om, prompts, lens, 4, TOL, wins=wins)
+        assert r["max_err"] < 2e-3
+        ctx.prefill(prompts, lens, buf)
+        ctx.set_windows(wins)
+        outs.append(ctx.generate(N))
+    assert (outs[0]["len"] == outs[1]["len"]).all()
+    for b in range(B):
+        assert (outs[0]["ids"][b, :outs[0]["len"][b]] == outs[1]["ids"][b, :outs[1]["len"][b]]).all()
+    assert (outs[0]["steps"] == outs[1]["steps"]).all()
+    ctx.close()
+
+
 def test_deterministic_replay(fc):
     shape, W, P, N = SMALL, 16, 30, 40
     S = ((P + N + 2 * W + 31) // 32) * 32
