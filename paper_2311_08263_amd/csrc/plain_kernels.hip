@@ -42,6 +42,16 @@ __global__ void k_embed(const void* emb, const int32_t* win, float* x, int d, in
     int m = blockIdx.x;
     int t = win[rm.rowb ? rm.rowb[m] * W + rm.rowj[m] : m];
     if (t < 0 || t >= V) t = 0;
+    if (DT == FASTCOT_BF16 && d % 8 == 0) {          // eight elements (16 bytes) per thread and pass
+        const uint4* src = (const uint4*)((const bf16_t*)emb + (size_t)t * d);
+        float4* dst = (float4*)(x + (size_t)m * d);
+        for (int i = threadIdx.x; i < d / 8; i += blockDim.x) {
+            const uint4 v = src[i];
+            dst[2 * i] = make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xFFFF0000u), __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xFFFF0000u));
+            dst[2 * i + 1] = make_float4(__uint_as_float(v.z << 16), __uint_as_float(v.z & 0xFFFF0000u), __uint_as_float(v.w << 16), __uint_as_float(v.w & 0xFFFF0000u));
+        }
+        return;
+    }
     for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)m * d + i] = wat<DT>(emb, (size_t)t * d + i);
 }
 hipError_t fc_embed(const void* emb, int dt, const int32_t* win, float* x, int M, int d, int V, hipStream_t st, RowMap rm, int W) {

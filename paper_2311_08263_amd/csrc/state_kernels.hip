@@ -49,43 +49,80 @@ hipError_t fc_prefill_advance(int32_t* state, const StateMap& sm, int B, int W, 
 // checked in order and the first miss stops.  K verified slots => K+1 exact tokens o[0..K].
 // Committing their K/V is the bump of n: rows 0..K of this step wrote their K/V at positions
 // n..n+K already.  All W fresh outputs go back to the buffer; the window slides by K+1.
+// One wave per sequence, lane j on window slot j (in rounds of 64 for wider windows): the scans of Eq. 5 and of
+// the EOS rule are ballots, the copies one load and one store per lane.
 __global__ void k_accept_commit(int32_t* st, StateMap sm, int B, int W, int S) {
     __shared__ int not_done;
     if (threadIdx.x == 0) not_done = 0;
     __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int max_new = st[sm.params + PARAM_MAX_NEW], eos = st[sm.params + PARAM_EOS];
     const int max_steps = st[sm.params + PARAM_MAX_STEPS], buf_len = st[sm.params + PARAM_BUF_LEN];
-    for (int b = threadIdx.x; b < B; b += blockDim.x) {
-        if (st[sm.done + b]) { st[sm.lastK + b] = -1; continue; }
+    for (int b = wave; b < B; b += nwaves) {
+        if (st[sm.done + b]) { if (lane == 0) st[sm.lastK + b] = -1; continue; }
         const int32_t* w = st + sm.win + b * W;
         const int32_t* o = st + sm.o + b * W;
         int32_t* buf = st + sm.buf + (size_t)b * S;
         int32_t* out = st + sm.out + (size_t)b * S;
         int n = st[sm.n + b], g = st[sm.g + b], steps = st[sm.steps + b];
-        // a sequence with a window of its own uses the first Wb rows of its W: the others are computed and ignored
+        const int g0 = g, olen0 = st[sm.olen + b];
+        // a sequence with a window of its own uses the first Wb rows of its W: the others are ignored (or not computed)
         const int ws = st[sm.wseq + b], Wb = ws > 0 && ws < W ? ws : W;
-        int K = 0;
-        while (K < Wb - 1 && o[K] == w[K + 1]) ++K;
-        for (int j = 0; j < Wb; ++j) if (g + j < buf_len) buf[g + j] = o[j];
-        int stop = 0, emitted = 0;
-        for (int j = 0; j <= K && !stop; ++j) {
-            if (g + j < max_new && g + j < S) { out[g + j] = o[j]; emitted = g + j + 1; }
-            if (eos >= 0 && o[j] == eos) stop = 1;
+        // K = verified slots: the first i in 1..Wb-1 with o[i-1] != w[i] ends the scan (Eq. 5); E = first accepted
+        // row that is an EOS (rows after it are not emitted)
+        int K = Wb - 1, E = Wb;
+        for (int j0 = 0; j0 < Wb - 1; j0 += 64) {
+            const int j = j0 + lane;
+            const bool miss = j < Wb - 1 && o[j] != w[j + 1];
+            const unsigned long long mask = __ballot(miss);
+            if (mask) { K = j0 + __ffsll((long long)mask) - 1; break; }
         }
-        if (emitted > st[sm.olen + b]) st[sm.olen + b] = emitted;
-        int newest = o[K];
+        if (eos >= 0)
+            for (int j0 = 0; j0 <= K; j0 += 64) {
+                const int j = j0 + lane;
+                const unsigned long long mask = __ballot(j <= K && o[j] == eos);
+                if (mask) { E = j0 + __ffsll((long long)mask) - 1; break; }
+            }
+        // all Wb fresh outputs go back to the buffer ("Cache Update", Sec. 4.3); the next window is read from the
+        // values themselves where they were just written (slot p of the buffer, p - g0 < Wb), else from the buffer
+        const int last = E < K ? E : K;                         // last emitted row
+        for (int j = lane; j < Wb; j += 64) {
+            const int oj = o[j];
+            if (g0 + j < buf_len) buf[g0 + j] = oj;
+            if (j <= last && g0 + j < max_new && g0 + j < S) out[g0 + j] = oj;
+        }
+        int jmax = last;
+        if (jmax > max_new - 1 - g0) jmax = max_new - 1 - g0;
+        if (jmax > S - 1 - g0) jmax = S - 1 - g0;
+        const int emitted = jmax >= 0 ? g0 + jmax + 1 : 0;
+        int stop = E <= K;
+        const int newest = o[K];
         n += K + 1; g += K + 1; ++steps;
         if (g >= max_new || (max_steps > 0 && steps >= max_steps)) stop = 1;
+        bool err = false;
         if (n + W > S || g + 2 * W - 1 > buf_len) {       // no room for another window: stop, flag it
-            if (!stop) st[sm.flags + FLAG_ERROR] = 1;
+            err = !stop;
             stop = 1;
         }
-        st[sm.n + b] = n; st[sm.g + b] = g; st[sm.steps + b] = steps; st[sm.lastK + b] = K;
-        st[sm.newest + b] = newest; st[sm.done + b] = stop;
+        // (the window is rewritten only after every lane has read its o and w above: a wave runs in lockstep, and
+        // the reads below touch o and the part of the buffer this step did not write)
         int32_t* wn = st + sm.win + b * W;
-        wn[0] = newest;
-        for (int j = 1; j < W; ++j) { int p = g + j - 1; wn[j] = p < buf_len ? buf[p] : 0; }
-        if (!stop) atomicAdd(&not_done, 1);
+        for (int j = lane; j < W; j += 64) {
+            int v;
+            if (j == 0) v = newest;
+            else {
+                const int p = g + j - 1;
+                v = p >= buf_len ? 0 : (p - g0 < Wb ? o[p - g0] : buf[p]);
+            }
+            wn[j] = v;
+        }
+        if (lane == 0) {
+            if (emitted > olen0) st[sm.olen + b] = emitted;
+            if (err) st[sm.flags + FLAG_ERROR] = 1;
+            st[sm.n + b] = n; st[sm.g + b] = g; st[sm.steps + b] = steps; st[sm.lastK + b] = K;
+            st[sm.newest + b] = newest; st[sm.done + b] = stop;
+            if (!stop) atomicAdd(&not_done, 1);
+        }
     }
     __syncthreads();
     if (threadIdx.x == 0) st[sm.flags + FLAG_ALL_DONE] = (not_done == 0);
@@ -106,7 +143,8 @@ hipError_t fc_rewindow(int32_t* state, const StateMap& sm, int B, int W, int S, 
 }
 
 hipError_t fc_accept_commit(int32_t* state, const StateMap& sm, int B, int W, int S, hipStream_t st) {
-    k_accept_commit<<<1, 64, 0, st>>>(state, sm, B, W, S);
+    const int waves = B < 16 ? (B < 1 ? 1 : B) : 16;
+    k_accept_commit<<<1, 64 * waves, 0, st>>>(state, sm, B, W, S);
     return hipGetLastError();
 }
 
