@@ -32,7 +32,7 @@ struct GemmCoArgs {
 // 8; fc_gemmco_grid picks one workgroup per CU (all resident, one round) unless the matrix is wider than
 // 8 n-tiles per CU
 int fc_gemmco_grid(int NT, int most = 8);
-// most n-tiles a workgroup may own so that its partial tiles (4 wave pairs x n-tiles x row tiles x 1 KB) and, with a
+// most n-tiles a workgroup may own so that its partial tiles (8 sets x n-tiles x row tiles x 1 KB up to eight output tiles, 4 sets beyond) and, with a
 // norm in front, the gain vector (K floats) fit the LDS of a CU
 int fc_gemmco_most(int M, int K, bool gain);
 int fc_num_cus();      // compute units of the current device

@@ -42,8 +42,10 @@ template <int EPI, int NW, int KB, bool DB, int MT, int KW = 0>
 __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     extern __shared__ float lds[];
     constexpr int TW = NW * MT;                          // output tiles per workgroup
-    f32x4_t* lds_part = (f32x4_t*)lds;                  // [4 wave pairs][TW][64 lanes]
-    float* lds_ss = lds + 4 * TW * 256;                 // [8][MT * 16]
+    // up to 8 output tiles: all eight waves publish at once (one barrier); more: in two rounds of four sets
+    constexpr int SETS = TW <= 8 ? 8 : 4;
+    f32x4_t* lds_part = (f32x4_t*)lds;                  // [SETS][TW][64 lanes]
+    float* lds_ss = lds + SETS * TW * 256;              // [8][MT * 16]
     float* lds_amv = lds_ss + 8 * MT * 16;              // [8][16]
     int* lds_ami = (int*)(lds_amv + 8 * 16);            // [8][16]
     float* lds_gain = (float*)(lds_ami + 8 * 16);       // [K] (only with a norm in front)
@@ -248,14 +250,23 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
     }
     }
 
-    // the eight K slices meet in LDS, in two rounds so that four partial sets (4 x TW KB) are enough: waves
-    // 4..7 publish, waves 0..3 add those to their own and publish the sums
+    // the eight K slices meet in LDS: with up to eight output tiles every wave publishes its partial tiles and one
+    // barrier later each tile's finisher adds the eight in wave order; with more tiles in two rounds, so that
+    // four partial sets (4 x TW KB) are enough: waves 4..7 publish, waves 0..3 add those to their own and
+    // publish the sums
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         ss[mt] += __shfl_xor(ss[mt], 16, 64);
         ss[mt] += __shfl_xor(ss[mt], 32, 64);
         if (g4 == 0) lds_ss[(w * MT + mt) * 16 + lm] = ss[mt];
     }
+    if constexpr (SETS == 8) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < NW; ++j) lds_part[(w * TW + j * MT + mt) * 64 + lane] = acc[j][mt];
+        __syncthreads();
+    } else {
     if (w >= 4) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
@@ -277,6 +288,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
             for (int j = 0; j < NW; ++j) lds_part[(w * TW + j * MT + mt) * 64 + lane] = acc[j][mt];
     }
     __syncthreads();
+    }
 
     // wave w finishes tiles w and (with more than 8 tiles) w + 8: lane holds row tm*16 + lm, columns
     // nt*16 + 4*g4 + r.  MT divides 8, so both tiles of a wave belong to the same row tile tm.
@@ -299,7 +311,7 @@ __global__ __launch_bounds__(512) void k_gemmco(GemmCoArgs a) {
         v[f] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
         if (fin[f]) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) v[f] += lds_part[(q * TW + ti) * 64 + lane];
+            for (int q = 0; q < SETS; ++q) v[f] += lds_part[(q * TW + ti) * 64 + lane];
             if (ks == 1) v[f] *= rs;
         }
     }
@@ -484,7 +496,7 @@ int fc_gemmco_grid(int NT, int most) {
 }
 
 static size_t co_lds_bytes(int nw, int mt, int K, bool gain) {
-    return (size_t)4 * nw * mt * 1024 + (size_t)(8 * mt * 16 + 2 * 8 * 16) * 4 + (gain ? (size_t)K * 4 : 0) + 64;
+    return (size_t)(nw * mt <= 8 ? 8 : 4) * nw * mt * 1024 + (size_t)(8 * mt * 16 + 2 * 8 * 16) * 4 + (gain ? (size_t)K * 4 : 0) + 64;
 }
 
 int fc_gemmco_most(int M, int K, bool gain) {
