@@ -6,6 +6,14 @@
 // (device-coherent) stores and loads, the producer waits until its stores have completed before
 // it bumps the arrival counter (a device-scope atomic), and the consumer reads only after it has
 // seen the final count.  No spinning anywhere: the last workgroup to arrive does the merge.
+//
+// What this rests on: the atomics are relaxed (no release on the counter, no acquire before the partial loads);
+// the order comes from the explicit wait for the stores' completion (wait_vmem_done) in front of the counter
+// increment, from the barrier between the increment's return and the partial loads, and from agent-scope
+// accesses going past the per-XCD L2s.  That is how hipcc of ROCm 7.2 (AMD clang 20) lowers these builtins for
+// gfx950; a compiler that moved the loads above the barrier or dropped the scope bits would break it without a
+// diagnostic.  The guard is tests/test_gpu_bf16.py::test_fresh_contexts_give_identical_bits (identical bits from
+// separate contexts through every K-slice and key-split hand-off) together with the oracle parity tests.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
