@@ -10,7 +10,7 @@
 // What this rests on: the atomics are relaxed (no release on the counter, no acquire before the partial loads);
 // the order comes from the explicit wait for the stores' completion (wait_vmem_done) in front of the counter
 // increment, from the barrier between the increment's return and the partial loads, and from agent-scope
-// accesses going past the per-XCD L2s.  That is how hipcc of ROCm 7.2 (AMD clang 20) lowers these builtins for
+// accesses going past the per-XCD L2s.  That is how hipcc of ROCm 7.2 (AMD clang 22.0.0git, roc-7.2.0) lowers these builtins for
 // gfx950; a compiler that moved the loads above the barrier or dropped the scope bits would break it without a
 // diagnostic.  The guard is tests/test_gpu_bf16.py::test_fresh_contexts_give_identical_bits (identical bits from
 // separate contexts through every K-slice and key-split hand-off) together with the oracle parity tests.
