@@ -357,6 +357,10 @@ extern "C" int fastcot_set_option(fastcot_ctx* c, int32_t option, int32_t value)
         if (nw % value || nw / value > NT || nw / value < 1 || (NT + nw / value - 1) / (nw / value) > 12)
             return fail(c, FASTCOT_EINVAL, "K slices per owner do not fit the workgroup count of that GEMM%s");
         c->plan.ks[gi] = value; c->opt_tune = 0;
+        // steps of 17..32 rows (two row tiles per workgroup, at most 8 n-tiles): the same value where it fits
+        const int nw2 = c->plan.nw2[gi];
+        if (nw2 > 0 && nw2 % value == 0 && nw2 / value >= 1 && nw2 / value <= NT && (NT + nw2 / value - 1) / (nw2 / value) <= 8)
+            c->plan.ks2[gi] = value;
     } else if (option >= FASTCOT_PLAN_SB && option < FASTCOT_PLAN_SB + 5) {
         if (value < 0 || value > 2) return fail(c, FASTCOT_EINVAL, "weight batches in flight: 0 (two), 1 (one) or 2 (whole slice up front)%s");
         c->plan.co_sb[0][option - FASTCOT_PLAN_SB] = c->plan.co_sb[1][option - FASTCOT_PLAN_SB] = value; c->opt_tune = 0;
