@@ -246,7 +246,7 @@ def test_join_bf16(fc):
 
 
 def test_per_sequence_windows_bf16(fc):
-    """bf16 model, follow mode with per-sequence window sizes (per-stage kernels and the one-launch step): the
+    """bf16 model, follow mode with per-sequence window sizes: the
     verified count, accepted tokens and committed length come from the first W_b rows of a sequence; one sequence
     has a perfect draft so that the cut at W_b, not a mismatch, is what ends its verification."""
     shape, W, B, P, N = SMALL, 8, 2, 30, 40
