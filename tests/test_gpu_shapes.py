@@ -54,3 +54,22 @@ def test_layer_shapes_follow_mode(name, shape, B, W, P, steps):
     print(f"{name}: max |dlogit| {r['max_err']:.3e} over {r['rows']} rows ({r['low_margin_rows']} low-margin)")
     assert r["max_err"] < 5e-3
     ctx.close()
+
+
+@pytest.mark.timeout(600)
+def test_many_row_attention_grouped_heads():
+    """The many-row attention kernel at the 70B layer shape (64 query heads on 8 K/V heads, workgroup ids strided by
+    the K/V head count): a 300-token prompt goes through it in one chunk, then the oracle follows two steps."""
+    import paper_2311_08263_amd as fc
+    shape, B, W, P = S70, 1, 16, 300
+    say(f"70b-shaped, many-row attention forced: P={P}")
+    S = ((P + 64 + 2 * W + 31) // 32) * 32
+    ctx, om = build(fc, shape, B, S, W)
+    ctx.set_option(fc.binding.PLAN_ATTN_MANY_ROWS, 2)
+    prompts = synthgen.prompts(B, P, shape.vocab, seed=61)
+    buf = synthgen.buffer_init(B, 64 + 2 * W, shape.vocab, seed=62)
+    ctx.prefill(prompts, [P], buf)
+    r = follow_steps(ctx, om, prompts, [P], 2, 2e-2)
+    print(f"70b-shaped many-row attention: max |dlogit| {r['max_err']:.3e} over {r['rows']} rows")
+    assert r["max_err"] < 5e-3
+    ctx.close()
