@@ -64,7 +64,9 @@ typedef enum {
 typedef struct fastcot_ctx fastcot_ctx;
 
 /* Bytes of the library's packed device weight layout / of the device workspace (KV cache,
- * activations, token buffers, counters) for a configuration.  0 on an invalid configuration. */
+ * activations, token buffers, counters) for a configuration.  0 on an invalid configuration.
+ * The activations are sized for the largest pass: a step of max_batch * window rows, or, for bf16 models
+ * on the matrix-core kernels, a prompt chunk of up to 1024 rows in all (Sec. 4.1, the first forward). */
 size_t fastcot_weight_bytes(const fastcot_config* cfg);
 size_t fastcot_workspace_bytes(const fastcot_config* cfg);
 
